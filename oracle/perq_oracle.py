@@ -1,0 +1,304 @@
+"""CPU oracle for PeRQ's online activation path.  TEST INFRASTRUCTURE ONLY.
+
+This file is the checker, not the product: only the test-suite, the smoke check and the
+benchmark's CPU-baseline leg may import it.  It shares no code, table or constant with the
+HIP library, and it never receives a value that the HIP library produced.
+
+What it computes, in the paper's order and notation (row-vector activations X in R^d,
+d = n*b, Notation paragraph of Section 1):
+
+    X  --P-->  XP  --R~ = I_n (x) R-->  XP R~  --Q-->  codes, scales
+
+  * P   : channel permutation, (XP)_i = X_{pi(i)}            (Notation, Section 1)
+  * R   : normalised b x b Hadamard matrix, entries +-1/sqrt(b) (Notation, Section 1;
+          butterfly form for powers of two in Remark A.1 -- here the plain matrix)
+  * Q   : INT4, symmetric, step s = ||.||_inf / (2^(q-1) - 1), q = 4   (Section 3, Eq. 4
+          with z = 0), one step per token;  or MXFP4: e2m1 elements (e = 2, m = 1) with one
+          power-of-two scale per group of 32, rounded down             (Appendix B, Eq. 5)
+  * calibration: a_i = (1/m) sum_k |X_i^(k)| and the greedy mass-diffusion permutation
+          (Algorithm 1)
+
+Everything is float64 NumPy.  The rotation is the *definition* (an explicit Sylvester matrix
+product), not a fast transform; rounding is half-to-even (numpy.rint).  Readings of points
+the paper leaves open are listed next to each function and collected in the design notes.
+
+Pins (tests/test_oracle_*.py, run without a GPU): Hadamard orthogonality and SciPy's
+construction, per-block l2 preservation, one-hot / all-ones closed forms, involution,
+Propositions 1, 2 and 4 and Corollary 3.3, Table 3's add/sub counts via an instrumented
+butterfly, the Section 3 worst-case INT-q error bound, the e2m1 grid/tie table by brute
+force, scale equivariance, closed forms and brute-force optimum for the greedy.
+"""
+from __future__ import annotations
+
+import itertools
+import math
+
+import numpy as np
+
+__all__ = [
+    "bf16_bits_to_f64", "sylvester_hadamard", "permute_channels", "block_hadamard",
+    "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
+    "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
+    "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
+]
+
+
+# ----------------------------------------------------------------------------------------
+# input decoding
+# ----------------------------------------------------------------------------------------
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float64, exactly.
+
+    bfloat16 is the upper half of an IEEE binary32, so the value is obtained by placing the
+    16 bits in the high half of a 32-bit word; binary32 -> binary64 is exact.
+    """
+    bits = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+# ----------------------------------------------------------------------------------------
+# P and R~   (Notation paragraph, Section 1)
+# ----------------------------------------------------------------------------------------
+def sylvester_hadamard(k: int) -> np.ndarray:
+    """Unnormalised k x k Hadamard matrix of +-1 (int64), k a power of two.
+
+    Sylvester's recursion H_1 = [1], H_2k = [[H_k, H_k], [H_k, -H_k]].  The paper only says
+    "normalized Hadamard matrix" with columns of unit l2 norm and l_inf norm 1/sqrt(k); the
+    reading taken is the Sylvester matrix in natural order with no random sign diagonal.
+    """
+    if k < 1 or (k & (k - 1)) != 0:
+        raise ValueError("k must be a power of two")
+    H = np.array([[1]], dtype=np.int64)
+    while H.shape[0] < k:
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
+def permute_channels(X: np.ndarray, perm) -> np.ndarray:
+    """XP with (XP)_i = X_{perm[i]}  (P e_i = e_{pi(i)} acting on a row vector).
+
+    `perm` is the concatenation [B_1, ..., B_n] that Algorithm 1 returns: perm[j*b + k] is
+    the k-th channel placed in block j.  None means P = I.
+    """
+    if perm is None:
+        return X
+    perm = np.asarray(perm)
+    return X[:, perm]
+
+
+def block_hadamard(X: np.ndarray, b: int) -> np.ndarray:
+    """X R~ with R~ = I_n (x) R, R = H_b / sqrt(b); X is [T, d], d = n*b, float64.
+
+    Written as the definition: each b-wide block of each row is multiplied by the explicit
+    matrix, then scaled by 1/sqrt(b) (the normalisation is applied after the +-1 sums).
+    """
+    T, d = X.shape
+    if d % b != 0:
+        raise ValueError("b must divide d")
+    H = sylvester_hadamard(b).astype(np.float64)
+    Y = (X.reshape(T * (d // b), b) @ H) / math.sqrt(b)
+    return Y.reshape(T, d)
+
+
+def fwht_f64(X: np.ndarray, b: int, counter: list | None = None) -> np.ndarray:
+    """Second, independent evaluation of X R~: radix-2 butterflies in float64 (Remark A.1).
+
+    Used only (i) as a cross-check of `block_hadamard` and (ii) where the explicit product
+    is too slow (b >= 2048 on all rows), after being validated against it on a subset.
+    `counter`, if given, is a one-element list that accumulates the number of additions and
+    subtractions performed per row -- the quantity tabulated in Table 3.
+    """
+    T, d = X.shape
+    Y = np.array(X, dtype=np.float64, copy=True).reshape(T, d // b, b)
+    h = 1
+    while h < b:
+        Z = Y.reshape(T, d // b, b // (2 * h), 2, h)
+        lo = Z[:, :, :, 0, :] + Z[:, :, :, 1, :]
+        hi = Z[:, :, :, 0, :] - Z[:, :, :, 1, :]
+        Y = np.stack([lo, hi], axis=3).reshape(T, d // b, b)
+        if counter is not None:
+            counter[0] += d          # d/2 additions + d/2 subtractions per row per stage
+        h *= 2
+    return (Y / math.sqrt(b)).reshape(T, d)
+
+
+# ----------------------------------------------------------------------------------------
+# Q: INT4, symmetric, one step size per token   (Section 3; Appendix B, Eq. 4 with z = 0)
+# ----------------------------------------------------------------------------------------
+def quant_int4_sym_token(Y: np.ndarray):
+    """Returns (codes int8 [T,d] in [-7, 7], s float64 [T]).
+
+    s = ||Y_t||_inf / (2^(q-1) - 1) with q = 4; code = clip(round_half_even(Y / s), -7, 7).
+    An all-zero row has s = 0 and all codes 0 (the paper is silent; 0/0 is read as 0).
+    The scale handed to a consumer is float32(s).
+    """
+    amax = np.abs(Y).max(axis=1)
+    s = amax / 7.0
+    safe = np.where(s > 0.0, s, 1.0)
+    V = Y / safe[:, None]
+    codes = np.clip(np.rint(V), -7, 7).astype(np.int8)
+    codes[s == 0.0, :] = 0
+    return codes, s
+
+
+def dequant_int4(codes: np.ndarray, s: np.ndarray) -> np.ndarray:
+    return codes.astype(np.float64) * np.asarray(s, dtype=np.float64)[:, None]
+
+
+# ----------------------------------------------------------------------------------------
+# Q: MXFP4   (Appendix B, Eq. 5: e = 2, m = 1; one power-of-two scale per 32, rounded down)
+# ----------------------------------------------------------------------------------------
+# e2m1 magnitudes by 3-bit code: 1 sign bit, 2 exponent bits (bias 1), 1 mantissa bit,
+# exponent field 0 is subnormal (0 and 0.5).
+E2M1_GRID = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64)
+_E2M1_EMAX = 2          # 6 = 1.5 * 2^2
+_E8M0_BIAS = 127
+
+
+def _round_to_e2m1_codes(A: np.ndarray) -> np.ndarray:
+    """Nearest e2m1 magnitude code for non-negative A; ties go to the even code (mantissa
+    bit 0); anything above 6 saturates to 6 (it is its nearest grid point)."""
+    dist = np.abs(A[..., None] - E2M1_GRID)                  # [..., 8]
+    best = dist.min(axis=-1, keepdims=True)
+    is_best = dist == best
+    even = (np.arange(8) % 2 == 0)
+    # prefer an even code among the (at most two) nearest ones
+    pick_even = is_best & even
+    has_even = pick_even.any(axis=-1)
+    code = np.where(has_even, pick_even.argmax(axis=-1), is_best.argmax(axis=-1))
+    return code.astype(np.uint8)
+
+
+def quant_mxfp4(Y: np.ndarray):
+    """Returns (codes uint8 [T,d], 4-bit sign|exp|mant; E uint8 [T, d/32], biased e8m0).
+
+    Per group of 32 contiguous outputs of the (permuted, rotated) row:
+      shared scale 2^(E-127) with E-127 = floor(log2 ||group||_inf) - 2, i.e. the group maximum
+      rounded down to a power of two and divided by the largest e2m1 power of two (2^2);
+      E is clamped to [0, 254]; an all-zero group has E = 0.
+      element code = round-to-nearest-even of y / 2^(E-127) on the e2m1 grid, saturating at 6;
+      zero is always emitted as +0.
+    Reading: the appendix's printed scale formula is inconsistent with its own sentence
+    "rounded down to a power of 2" and with the OCP format it says it follows; the sentence
+    and the format are taken.
+    """
+    T, d = Y.shape
+    if d % 32 != 0:
+        raise ValueError("MXFP4 needs d % 32 == 0")
+    G = Y.reshape(T, d // 32, 32)
+    amax = np.abs(G).max(axis=2)
+    mant, expo = np.frexp(amax)                      # amax = mant * 2^expo, mant in [0.5, 1)
+    floor_log2 = expo.astype(np.int64) - 1
+    E = floor_log2 - _E2M1_EMAX + _E8M0_BIAS
+    E = np.where(amax > 0.0, E, 0)
+    E = np.clip(E, 0, 254).astype(np.int64)
+    V = np.ldexp(G, -(E - _E8M0_BIAS)[:, :, None].astype(np.int64))
+    mag = _round_to_e2m1_codes(np.abs(V))
+    sign = ((V < 0.0) & (mag != 0)).astype(np.uint8)
+    codes = (sign << 3) | mag
+    return codes.reshape(T, d), E.astype(np.uint8)
+
+
+def dequant_mxfp4(codes: np.ndarray, E: np.ndarray) -> np.ndarray:
+    T, d = codes.shape
+    mag = E2M1_GRID[codes & 7]
+    val = np.where((codes & 8) != 0, -mag, mag).reshape(T, d // 32, 32)
+    return np.ldexp(val, (E.astype(np.int64) - _E8M0_BIAS)[:, :, None]).reshape(T, d)
+
+
+def pack_nibbles(codes: np.ndarray) -> np.ndarray:
+    """[T, d] 4-bit codes -> [T, d/2] bytes; element 2k in the low nibble, 2k+1 in the high.
+
+    Signed INT4 codes are stored in two's complement (code & 0xF).  The paper never packs
+    (it fake-quantises); this is the storage convention of the library under test.
+    """
+    u = (codes.astype(np.int16) & 0xF).astype(np.uint8)
+    return (u[:, 0::2] | (u[:, 1::2] << 4)).astype(np.uint8)
+
+
+# ----------------------------------------------------------------------------------------
+# calibration   (Algorithm 1)
+# ----------------------------------------------------------------------------------------
+def colabs_mean(X: np.ndarray) -> np.ndarray:
+    """a_i = (1/m) sum_k |X_i^(k)|  -- the sort key of Algorithm 1, X is [m, d] float64."""
+    return np.abs(X).sum(axis=0) / X.shape[0]
+
+
+def massdiff_greedy(a, b: int) -> np.ndarray:
+    """Algorithm 1 (mass diffusion) on the per-channel means `a`; returns perm int32[d].
+
+    Channels are visited in descending order of a (equal values: lower channel first) and each
+    goes to the block, among those not yet full, whose accumulated mass is smallest (equal
+    masses: lowest block index).  The candidate-dependent term |X_i| in the algorithm's argmin
+    is the same for every block, and the mean of block l1 norms is the sum of the block's
+    a-values, so the data enter only through a.  Blocks keep insertion order and are
+    concatenated in block order.
+    """
+    a = np.asarray(a, dtype=np.float64)
+    d = a.shape[0]
+    if d % b != 0:
+        raise ValueError("b must divide d")
+    n = d // b
+    order = np.argsort(-a, kind="stable")
+    mass = [0.0] * n
+    blocks = [[] for _ in range(n)]
+    for i in order:
+        j_star = -1
+        for j in range(n):
+            if len(blocks[j]) == b:
+                continue
+            if j_star < 0 or mass[j] < mass[j_star]:
+                j_star = j
+        blocks[j_star].append(int(i))
+        mass[j_star] += float(a[i])
+    return np.array([i for blk in blocks for i in blk], dtype=np.int32)
+
+
+def block_masses(a, perm, b: int) -> np.ndarray:
+    """L_j = sum_{i in B_j} a_i for the blocks of `perm` (None = identity)."""
+    a = np.asarray(a, dtype=np.float64)
+    ap = a if perm is None else a[np.asarray(perm)]
+    return ap.reshape(-1, b).sum(axis=1)
+
+
+def brute_force_min_max_block_mass(a, b: int) -> float:
+    """min over all partitions of the channels into d/b blocks of size b of max_j L_j.
+    Exhaustive; tiny d only."""
+    a = [float(v) for v in a]
+    d = len(a)
+    best = [math.inf]
+
+    def rec(remaining, cur_max):
+        if not remaining:
+            best[0] = min(best[0], cur_max)
+            return
+        first, rest = remaining[0], remaining[1:]
+        for others in itertools.combinations(rest, b - 1):
+            m = a[first] + sum(a[i] for i in others)
+            if max(m, cur_max) >= best[0]:
+                continue
+            left = [i for i in rest if i not in others]
+            rec(left, max(m, cur_max))
+
+    rec(list(range(d)), 0.0)
+    return best[0]
+
+
+# ----------------------------------------------------------------------------------------
+# the whole path
+# ----------------------------------------------------------------------------------------
+def perq_apply(x_bits: np.ndarray, perm, b: int, fmt: str, rotate=block_hadamard):
+    """bf16 bits [T,d] -> dict(y, codes, packed, scales[, s64]) following P, R~, Q in order.
+
+    fmt is "int4" (scales: float32 [T]) or "mxfp4" (scales: uint8 [T, d/32]).
+    """
+    X = bf16_bits_to_f64(x_bits)
+    Y = rotate(permute_channels(X, perm), b)
+    if fmt == "int4":
+        codes, s = quant_int4_sym_token(Y)
+        return {"y": Y, "codes": codes, "packed": pack_nibbles(codes),
+                "scales": s.astype(np.float32), "s64": s}
+    if fmt == "mxfp4":
+        codes, E = quant_mxfp4(Y)
+        return {"y": Y, "codes": codes, "packed": pack_nibbles(codes), "scales": E}
+    raise ValueError("fmt must be 'int4' or 'mxfp4'")

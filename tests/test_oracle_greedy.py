@@ -1,0 +1,98 @@
+"""Pins for the oracle's mass-diffusion permutation (Algorithm 1), CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import perq_oracle as orc
+from paper_2601_22347_amd import synth
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+def _check_structure(perm, d):
+    assert perm.dtype == np.int32 and perm.shape == (d,)
+    assert np.array_equal(np.sort(perm), np.arange(d))
+
+
+@pytest.mark.parametrize("d,b", [(64, 16), (256, 32), (96, 8), (128, 128)])
+def test_greedy_is_a_bijection_with_full_blocks(d, b):
+    a = np.abs(_rng(1).standard_t(3, size=d))
+    perm = orc.massdiff_greedy(a, b)
+    _check_structure(perm, d)
+    n = d // b
+    order = np.argsort(-a, kind="stable")
+    # the first n picks meet n empty blocks (all masses 0): lowest index wins each time
+    assert np.array_equal(perm[0::b][:n], order[:n])
+    # inside a block channels appear in the order they were placed: descending a
+    blocks = a[perm].reshape(n, b)
+    assert np.all(np.diff(blocks, axis=1) <= 0)
+    L = orc.block_masses(a, perm, b)
+    assert L.max() >= a.sum() / n - 1e-12 and L.max() >= a.max()
+    assert math.isclose(L.sum(), a.sum(), rel_tol=1e-13)
+
+
+def test_greedy_closed_forms():
+    # all channels equal: round-robin, perm[j*b + k] = k*n + j
+    d, b = 48, 8
+    n = d // b
+    perm = orc.massdiff_greedy(np.full(d, 0.75), b)
+    want = np.array([k * n + j for j in range(n) for k in range(b)])
+    assert np.array_equal(perm, want)
+    # a single block: stable descending argsort
+    a = np.array([1.0, 3.0, 3.0, 0.5, 2.0, 3.0, 0.0, 1.0])
+    assert orc.massdiff_greedy(a, 8).tolist() == [1, 2, 5, 4, 0, 7, 3, 6]
+    # hand-worked example, d = 6, b = 3 (n = 2): a sorted desc = 9(ch2) 7(ch0) 4(ch5) 3(ch1) 2(ch4) 1(ch3)
+    # 9->B0 (9,0); 7->B1 (9,7); 4->B1 (9,11); 3->B0 (12,11); 2->B1 (12,13) full; 1->B0 (13,13)
+    a = np.array([7.0, 3.0, 9.0, 1.0, 2.0, 4.0])
+    assert orc.massdiff_greedy(a, 3).tolist() == [2, 1, 3, 0, 5, 4]
+    assert orc.block_masses(a, [2, 1, 3, 0, 5, 4], 3).tolist() == [13.0, 13.0]
+
+
+def test_full_blocks_are_dropped_from_the_candidate_set():
+    # one huge channel then many small ones: block 0 must still end with exactly b members
+    a = np.array([100.0] + [1.0] * 7)
+    perm = orc.massdiff_greedy(a, 4)
+    _check_structure(perm, 8)
+    # B0 gets ch0, then B1 fills (1,2,3,4) while lighter, then the rest must go to B0
+    assert perm.tolist() == [0, 5, 6, 7, 1, 2, 3, 4]
+
+
+@pytest.mark.parametrize("d,b", [(8, 4), (8, 2), (12, 4), (12, 3), (16, 8)])
+def test_greedy_against_brute_force_optimum(d, b):
+    worst = 1.0
+    for seed in range(6):
+        a = np.abs(_rng(100 + seed).standard_t(3, size=d))
+        if seed % 2:
+            a[_rng(seed).integers(d)] *= 20
+        perm = orc.massdiff_greedy(a, b)
+        g = orc.block_masses(a, perm, b).max()
+        opt = orc.brute_force_min_max_block_mass(a, b)
+        assert opt <= g * (1 + 1e-12)
+        assert opt >= max(a.sum() / (d // b), a.max()) * (1 - 1e-12)
+        worst = max(worst, g / opt)
+    # a greedy heuristic of the longest-processing-time kind; it stays within 4/3 of optimal here
+    assert worst <= 4.0 / 3.0 + 1e-9
+
+
+def test_brute_force_on_known_instance():
+    # {8,1} {7,2} {6,3}: every block 9
+    assert orc.brute_force_min_max_block_mass([8, 7, 6, 3, 2, 1], 2) == 9
+    assert orc.brute_force_min_max_block_mass([5, 5, 5, 5], 4) == 20
+
+
+def test_greedy_beats_identity_on_outlier_workloads():
+    for wl, b in [(synth.tiny(), 16)]:
+        X = orc.bf16_bits_to_f64(wl.calib_rows())
+        a = orc.colabs_mean(X)
+        perm = orc.massdiff_greedy(a, b)
+        Lg, Li = orc.block_masses(a, perm, b), orc.block_masses(a, None, b)
+        assert Lg.max() < Li.max()
+        assert Lg.max() - Lg.min() < Li.max() - Li.min()
+        # and the rotated apply-time rows have a smaller worst-case bound (Prop. 2) on average
+        Xa = orc.bf16_bits_to_f64(wl.apply_rows())
+        bound_g = np.abs(Xa[:, perm]).reshape(wl.T, -1, b).sum(axis=2).max(axis=1)
+        bound_i = np.abs(Xa).reshape(wl.T, -1, b).sum(axis=2).max(axis=1)
+        assert bound_g.mean() < bound_i.mean()

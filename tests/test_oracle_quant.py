@@ -1,0 +1,192 @@
+"""Pins for the oracle's quantizers, packing and column statistic (CPU only)."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import perq_oracle as orc
+
+
+def _rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---- INT4 symmetric per token (Section 3; Eq. 4 with z = 0) ----------------------------
+def test_int4_error_bounds_and_extremes():
+    Y = _rng(1).standard_t(3, size=(50, 256))
+    c, s = orc.quant_int4_sym_token(Y)
+    assert c.min() >= -7 and c.max() <= 7
+    dq = orc.dequant_int4(c, s)
+    assert np.all(np.abs(Y - dq) <= s[:, None] / 2 * (1 + 1e-12))
+    # Section 3: ||X - Q(X)||_2 <= sqrt(d)/(2^q - 2) ||X||_inf, q = 4
+    assert np.all(np.linalg.norm(Y - dq, axis=1)
+                  <= math.sqrt(256) / 14.0 * np.abs(Y).max(axis=1) * (1 + 1e-12))
+    # the element that sets the scale gets +-7 and s = ||Y||_inf / 7
+    arg = np.abs(Y).argmax(axis=1)
+    assert np.all(np.abs(c[np.arange(50), arg]) == 7)
+    assert np.allclose(s, np.abs(Y).max(axis=1) / 7.0, rtol=1e-16)
+
+
+def test_int4_ties_go_to_even_and_zero_row():
+    Y = np.array([[7.0, 0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, 6.5, -6.5, 0.49999, 0.50001],
+                  [0.0] * 12])
+    c, s = orc.quant_int4_sym_token(Y)
+    assert s[0] == 1.0 and s[1] == 0.0
+    assert c[0].tolist() == [7, 0, 2, 2, 4, 0, -2, -2, 6, -6, 0, 1]
+    assert np.all(c[1] == 0)
+
+
+def test_int4_scale_and_sign_equivariance():
+    Y = _rng(2).standard_normal((8, 64))
+    c, s = orc.quant_int4_sym_token(Y)
+    for k in (-9, 3, 20):
+        c2, s2 = orc.quant_int4_sym_token(np.ldexp(Y, k))
+        assert np.array_equal(c, c2) and np.array_equal(np.ldexp(s, k), s2)
+    c3, s3 = orc.quant_int4_sym_token(-Y)
+    assert np.array_equal(c3, -c) and np.array_equal(s3, s)
+
+
+def test_pack_nibbles_layout():
+    codes = np.array([[1, -1, 7, -7, 0, 3, -8 + 1, 2]], dtype=np.int8)
+    assert orc.pack_nibbles(codes).tolist() == [[0xF1, 0x97, 0x30, 0x29]]
+    u = np.array([[0x0, 0xF, 0x8, 0x7]], dtype=np.uint8)
+    assert orc.pack_nibbles(u).tolist() == [[0xF0, 0x78]]
+
+
+# ---- MXFP4 (Appendix B: e = 2, m = 1, one power-of-two scale per 32) --------------------
+def _e2m1_value_from_bits(code):
+    """The e2m1 definition: 1 sign, 2 exponent bits with bias 1, 1 mantissa bit; exponent
+    field 0 is subnormal."""
+    s, e, m = (code >> 3) & 1, (code >> 1) & 3, code & 1
+    mag = m * 0.5 if e == 0 else (1 + m / 2) * 2.0 ** (e - 1)
+    return -mag if s else mag
+
+
+def test_e2m1_table_matches_format_definition():
+    for code in range(16):
+        mag = orc.E2M1_GRID[code & 7]
+        assert _e2m1_value_from_bits(code) == (-mag if code & 8 else mag)
+    assert orc.E2M1_GRID.max() == 6.0
+
+
+def _group(vals):
+    g = np.zeros(32)
+    g[:len(vals)] = vals
+    return g[None, :]
+
+
+def test_mxfp4_grid_points_and_tie_points():
+    # group maximum 6 -> floor(log2 6) = 2 -> scale 2^(2-2) = 1, E = 127
+    vals = [6, 0, 0.5, 1, 1.5, 2, 3, 4,              # grid points
+            0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5,     # midpoints: even code wins
+            -0.25, -0.75, -5, -6, -0.1,
+            0.2499, 0.2501, 4.99, 5.01]
+    want = [7, 0, 1, 2, 3, 4, 5, 6,
+            0, 2, 2, 4, 4, 6, 6,
+            0, 8 | 2, 8 | 6, 8 | 7, 0,
+            0, 1, 6, 7]
+    c, E = orc.quant_mxfp4(_group(vals))
+    assert E.tolist() == [[127]]
+    assert c[0, :len(vals)].tolist() == want
+
+
+def test_mxfp4_scale_is_group_max_rounded_down_to_power_of_two():
+    rng = _rng(3)
+    Y = rng.standard_t(3, size=(40, 128)) * np.exp(rng.uniform(-20, 20, size=(40, 1)))
+    c, E = orc.quant_mxfp4(Y)
+    amax = np.abs(Y).reshape(40, 4, 32).max(axis=2)
+    sc = np.ldexp(1.0, E.astype(int) - 127)
+    assert np.all(4 * sc <= amax) and np.all(amax < 8 * sc)
+    # saturation region (6, 8) * scale -> +-6
+    c2, E2 = orc.quant_mxfp4(_group([7.9, -7.0, 6.01]))
+    assert E2.tolist() == [[127]] and c2[0, :3].tolist() == [7, 15, 7]
+    # exact powers of two at the boundary
+    c3, E3 = orc.quant_mxfp4(_group([8.0, 4.0]))
+    assert E3.tolist() == [[128]] and c3[0, :2].tolist() == [6, 4]       # 8/2 = 4, 4/2 = 2
+    c4, E4 = orc.quant_mxfp4(_group([]))
+    assert E4.tolist() == [[0]] and np.all(c4 == 0)
+
+
+def test_mxfp4_error_bound_and_roundtrip():
+    rng = _rng(4)
+    Y = rng.standard_normal((30, 256)) * 3
+    c, E = orc.quant_mxfp4(Y)
+    dq = orc.dequant_mxfp4(c, E)
+    sc = np.repeat(np.ldexp(1.0, E.astype(int) - 127), 32, axis=1)
+    v = np.abs(Y) / sc
+    spacing = np.where(v < 2, 0.5, np.where(v < 4, 1.0, 2.0))
+    ok_in = (v <= 6) & (np.abs(Y - dq) <= spacing / 2 * sc * (1 + 1e-12))
+    ok_sat = (v > 6) & (np.abs(Y - dq) < 2 * sc)
+    assert np.all(ok_in | ok_sat)
+    # values already on the grid come back exactly
+    grid_vals = rng.choice(orc.E2M1_GRID, size=(10, 64)) * rng.choice([-1, 1], size=(10, 64))
+    grid_vals[:, 0] = 6; grid_vals[:, 32] = -6
+    g = grid_vals * 2.0 ** -5
+    cg, Eg = orc.quant_mxfp4(g)
+    assert np.array_equal(orc.dequant_mxfp4(cg, Eg), g)
+    # power-of-two equivariance
+    for k in (-30, 7):
+        c2, E2 = orc.quant_mxfp4(np.ldexp(Y, k))
+        assert np.array_equal(c2, c) and np.array_equal(E2.astype(int), E.astype(int) + k)
+
+
+def test_mxfp4_rounding_agrees_with_piecewise_rint():
+    """Independent formulation: the e2m1 grid is uniform with step 0.5 on [0,2), 1 on [2,4),
+    2 on [4,6]; round-half-even on the step count equals ties-to-even-code."""
+    a = np.abs(_rng(5).standard_normal(200000)) * 2.5
+    a = np.concatenate([a, np.arange(0, 6.01, 0.125)])
+    code = orc._round_to_e2m1_codes(a)
+    sat = np.minimum(a, 6.0)
+    val = np.where(sat < 2, np.rint(sat / 0.5) * 0.5,
+                   np.where(sat < 4, np.rint(sat), np.rint(sat / 2) * 2))
+    assert np.array_equal(orc.E2M1_GRID[code], val)
+
+
+def test_mxfp4_group_is_32_contiguous_positions():
+    Y = np.zeros((1, 64)); Y[0, 31] = 6.0; Y[0, 32] = 96.0; Y[0, 0] = 1.0; Y[0, 63] = 16.0
+    c, E = orc.quant_mxfp4(Y)
+    assert E.tolist() == [[127, 131]]
+    assert c[0, [0, 31, 32, 63]].tolist() == [2, 7, 7, 2]
+
+
+def test_mxfp4_exponent_clamp():
+    c, E = orc.quant_mxfp4(_group([2.0 ** -140, 2.0 ** -141]))
+    assert E.tolist() == [[0]]          # floor(log2) - 2 + 127 < 0 -> clamped
+    assert c[0, 0] == 0
+
+
+# ---- a_i (Algorithm 1, sort key) ---------------------------------------------------------
+def test_colabs_mean_closed_forms():
+    X = np.array([[1.0, -2.0, 0.0], [-3.0, 2.0, 0.5], [1.0, -2.0, -0.5], [-1.0, 2.0, 0.0]])
+    assert orc.colabs_mean(X).tolist() == [1.5, 2.0, 0.25]
+    R = _rng(6).standard_normal((100, 37))
+    a = orc.colabs_mean(R)
+    assert math.isclose(a.sum(), np.abs(R).sum(axis=1).mean(), rel_tol=1e-13)
+    s = np.array([math.fsum(np.abs(R[:, i])) / 100 for i in range(37)])
+    assert np.allclose(a, s, rtol=1e-14)
+    C = np.sign(R) * np.arange(1, 38)
+    assert np.allclose(orc.colabs_mean(C), np.arange(1, 38), rtol=1e-15)
+
+
+# ---- whole path ---------------------------------------------------------------------------
+@pytest.mark.parametrize("fmt", ["int4", "mxfp4"])
+def test_end_to_end_reconstruction(fmt):
+    """dequantised codes, rotated back and un-permuted, reproduce x within the format's bound."""
+    from paper_2601_22347_amd import synth
+    rng = _rng(7)
+    d, b, T = 256, 32, 16
+    bits = synth.f64_to_bf16_bits(rng.standard_normal((T, d)) * 2)
+    perm = rng.permutation(d).astype(np.int32)
+    out = orc.perq_apply(bits, perm, b, fmt)
+    X = orc.bf16_bits_to_f64(bits)
+    if fmt == "int4":
+        dq = orc.dequant_int4(out["codes"], out["s64"])
+        tol = out["s64"][:, None] / 2 * math.sqrt(d)
+    else:
+        dq = orc.dequant_mxfp4(out["codes"], out["scales"])
+        tol = np.abs(out["y"]).max() * math.sqrt(d)
+    back = orc.block_hadamard(dq, b)                # R~ is an involution
+    rec = np.empty_like(back); rec[:, perm] = back
+    assert np.all(np.linalg.norm(rec - X, axis=1) <= np.ravel(tol.max(axis=1) if tol.ndim > 1 else tol))
+    assert np.allclose(np.linalg.norm(out["y"], axis=1), np.linalg.norm(X, axis=1), rtol=1e-12)
+    assert out["packed"].shape == (T, d // 2)
