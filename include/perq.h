@@ -1,0 +1,131 @@
+/*
+ * perq.h -- C ABI of the MI355X (gfx950) PeRQ online activation path.
+ *
+ * The path, in the paper's notation (Section 1, Notation; Figure 2):
+ *
+ *     X[T,d] (bf16)  --P-->  XP  --R~ = I_n (x) R-->  XP R~  --Q-->  packed 4-bit codes + scales
+ *
+ * P  is a channel permutation, (XP)_i = X_{perm[i]};  R is the normalised b x b Sylvester
+ * Hadamard matrix (entries +-1/sqrt(b)), d = n*b;  Q is either the symmetric INT4 quantizer
+ * with one step per token (Section 3; Appendix B Eq. 4 with z = 0) or MXFP4 (Appendix B Eq. 5:
+ * e2m1 elements, one power-of-two scale per 32 contiguous outputs).  The permutation comes
+ * from Algorithm 1 (mass diffusion), whose only data dependence is the per-channel mean
+ * magnitude a_i = (1/m) sum_k |X_i^(k)|.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device, "host" pointers are
+ *     ordinary host memory.  Every buffer is owned by the caller; the library keeps no state,
+ *     allocates nothing and frees nothing.
+ *   - bf16 tensors are passed as uint16_t bit patterns, row-major, leading dimension in
+ *     elements.
+ *   - Device entry points enqueue on `hip_stream` (a hipStream_t, NULL = default stream) and
+ *     return without synchronising; outputs are valid once the stream has been synchronised.
+ *   - Every entry point returns a perq_status_t; nothing throws or aborts.  Arguments are
+ *     checked on the host before any launch.  Contents of `perm` are NOT checked on the
+ *     device: a perm that is not a bijection on [0,d) gives undefined output values (reads
+ *     stay inside the row only if every entry is in [0,d); validate with perq_perm_validate).
+ *   - Non-finite inputs give unspecified output values but no fault.
+ */
+#ifndef PERQ_H
+#define PERQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PERQ_OK = 0,
+    PERQ_ERR_INVALID_ARG = 1,  /* null pointer, bad size, b not a power of two in [16,d], ... */
+    PERQ_ERR_UNSUPPORTED = 2,  /* valid problem the kernels do not cover (alignment, d too large) */
+    PERQ_ERR_LAUNCH = 3        /* HIP reported an error at launch */
+} perq_status_t;
+
+typedef enum {
+    PERQ_FMT_INT4_SYM_TOKEN = 0,  /* codes in [-7,7] as two's-complement nibbles; float scale per token */
+    PERQ_FMT_MXFP4 = 1            /* e2m1 nibbles (sign|exp2|mant1); e8m0 byte per 32 outputs */
+} perq_fmt_t;
+
+/* Which rotation kernel runs.  AUTO picks the fastest one that covers the shape; the explicit
+ * values exist so that the kernels can be compared with each other and each checked alone. */
+typedef enum {
+    PERQ_ALGO_AUTO = 0,
+    PERQ_ALGO_BUTTERFLY = 1,  /* register / cross-lane / LDS radix-2 butterflies; every shape */
+    PERQ_ALGO_MFMA = 2        /* X * H on the matrix cores for the low index bits; UNSUPPORTED
+                                 for shapes it does not cover */
+} perq_algo_t;
+
+/* Largest row width the kernels accept (elements). */
+#define PERQ_MAX_D 32768
+
+const char* perq_status_string(perq_status_t status);
+
+/*
+ * Column statistic of Algorithm 1 (its sort key): out_mean[i] = (1/M) * sum_k |x[k, i]|.
+ *
+ *   x_bf16     device, bf16 [M, ldx], ldx >= d, ldx % 8 == 0 and base 16-byte aligned
+ *   out_mean   device, float [d]
+ *   workspace  device, at least perq_colabs_mean_workspace_bytes(M, d) bytes, 16-byte aligned
+ *
+ * Two deterministic passes (row-slice partial sums in fp32, then a fixed-order reduction);
+ * the result does not depend on scheduling.  M == 0 is INVALID_ARG (the mean is undefined).
+ */
+size_t perq_colabs_mean_workspace_bytes(int64_t M, int32_t d);
+perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                               float* out_mean, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+
+/*
+ * Algorithm 1 (mass diffusion), host side, on the sufficient statistic a = colabs_mean.
+ *
+ *   colabs_mean  host, float [d], finite and >= 0
+ *   perm_out     host, int32 [d]; perm_out[j*b + k] = k-th channel placed in block j
+ *
+ * Channels are visited by descending a (ties: lower channel first); each goes to the not-yet-
+ * full block of least accumulated mass (ties: lowest block).  Masses accumulate in double.
+ * Any b >= 1 dividing d is accepted here (the rotation's b >= 16 limit does not apply).
+ */
+perq_status_t perq_massdiff_perm(const float* colabs_mean, int32_t d, int32_t b, int32_t* perm_out);
+
+/* OK iff perm (host, int32 [d]) is a bijection on [0, d); INVALID_ARG otherwise. */
+perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
+
+/*
+ * The fused online path: gather through perm, rotate every b-block, quantize, pack.
+ *
+ *   x_bf16   device, bf16 [T, ldx]; ldx >= d; base 16-byte aligned and ldx % 8 == 0
+ *   perm     device, int32 [d], or NULL for P = I
+ *   b        power of two, 16 <= b <= d, b divides d
+ *   codes    device, uint8 [T, d/2]; element 2k in the low nibble of byte k, 2k+1 in the high
+ *   scales   INT4:  device float [T], s_t = ||y_t||_inf / 7 (0 for an all-zero row)
+ *            MXFP4: device uint8 [T, d/32], biased exponent E, scale = 2^(E-127),
+ *                   E - 127 = floor(log2 ||group||_inf) - 2, clamped to [0,254], 0 for a zero group
+ *   d % 32 == 0 is required for both formats; T == 0 is OK and does nothing.
+ *
+ * Rounding is to nearest, ties to even; MXFP4 saturates at +-6 and always writes zero as +0.
+ */
+perq_status_t perq_permute_rotate_quant(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                        const int32_t* perm, int32_t b, perq_fmt_t fmt,
+                                        uint8_t* codes, void* scales, void* hip_stream);
+
+/* Same as perq_permute_rotate_quant with the rotation kernel chosen by the caller. */
+perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                             const int32_t* perm, int32_t b, perq_fmt_t fmt,
+                                             perq_algo_t algo, uint8_t* codes, void* scales,
+                                             void* hip_stream);
+
+/*
+ * Test entry: the same gather + rotation device code as perq_permute_rotate_quant(_algo),
+ * writing the pre-quantization values y = (XP R~)[T, d] as float (normalised by 1/sqrt(b)).
+ *   y   device, float [T, d], 16-byte aligned
+ */
+perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                      const int32_t* perm, int32_t b, perq_algo_t algo,
+                                      float* y, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PERQ_H */

@@ -169,7 +169,7 @@ def _round_to_e2m1_codes(A: np.ndarray) -> np.ndarray:
     return code.astype(np.uint8)
 
 
-def quant_mxfp4(Y: np.ndarray):
+def quant_mxfp4(Y: np.ndarray, E_given: np.ndarray | None = None):
     """Returns (codes uint8 [T,d], 4-bit sign|exp|mant; E uint8 [T, d/32], biased e8m0).
 
     Per group of 32 contiguous outputs of the (permuted, rotated) row:
@@ -181,6 +181,9 @@ def quant_mxfp4(Y: np.ndarray):
     Reading: the appendix's printed scale formula is inconsistent with its own sentence
     "rounded down to a power of 2" and with the OCP format it says it follows; the sentence
     and the format are taken.
+
+    `E_given` (uint8 [T, d/32]) replaces the computed exponents; the parity tests use it to
+    check the codes of a group whose maximum sits on a power-of-two boundary.
     """
     T, d = Y.shape
     if d % 32 != 0:
@@ -192,6 +195,8 @@ def quant_mxfp4(Y: np.ndarray):
     E = floor_log2 - _E2M1_EMAX + _E8M0_BIAS
     E = np.where(amax > 0.0, E, 0)
     E = np.clip(E, 0, 254).astype(np.int64)
+    if E_given is not None:
+        E = np.asarray(E_given).astype(np.int64).reshape(T, d // 32)
     V = np.ldexp(G, -(E - _E8M0_BIAS)[:, :, None].astype(np.int64))
     mag = _round_to_e2m1_codes(np.abs(V))
     sign = ((V < 0.0) & (mag != 0)).astype(np.uint8)

@@ -1,0 +1,171 @@
+"""ctypes binding of libperq.so -- argument marshalling only; every step runs in the library.
+
+Function names and argument order mirror include/perq.h.  Device buffers are PyTorch tensors
+(PyTorch is used for device memory and streams, nothing else); host buffers are NumPy arrays.
+There is no fallback: if the library is not built or cannot be loaded, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libperq.so")
+
+PERQ_OK, PERQ_ERR_INVALID_ARG, PERQ_ERR_UNSUPPORTED, PERQ_ERR_LAUNCH = 0, 1, 2, 3
+PERQ_FMT_INT4_SYM_TOKEN, PERQ_FMT_MXFP4 = 0, 1
+PERQ_ALGO_AUTO, PERQ_ALGO_BUTTERFLY, PERQ_ALGO_MFMA = 0, 1, 2
+FMT = {"int4": PERQ_FMT_INT4_SYM_TOKEN, "mxfp4": PERQ_FMT_MXFP4}
+ALGO = {"auto": PERQ_ALGO_AUTO, "butterfly": PERQ_ALGO_BUTTERFLY, "mfma": PERQ_ALGO_MFMA}
+
+EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colabs_mean",
+           "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
+           "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32"]
+
+_lib = None
+
+
+class PerqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)}")
+
+
+def load(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Load libperq.so (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise RuntimeError(f"{LIB_PATH} is not built; run paper_2601_22347_amd.build.build()")
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_size_t
+    lib.perq_status_string.restype = ctypes.c_char_p
+    lib.perq_status_string.argtypes = [ctypes.c_int]
+    lib.perq_colabs_mean_workspace_bytes.restype = sz
+    lib.perq_colabs_mean_workspace_bytes.argtypes = [i64, i32]
+    lib.perq_colabs_mean.restype = ctypes.c_int
+    lib.perq_colabs_mean.argtypes = [vp, i64, i32, i64, vp, vp, sz, vp]
+    lib.perq_massdiff_perm.restype = ctypes.c_int
+    lib.perq_massdiff_perm.argtypes = [vp, i32, i32, vp]
+    lib.perq_perm_validate.restype = ctypes.c_int
+    lib.perq_perm_validate.argtypes = [vp, i32]
+    lib.perq_permute_rotate_quant.restype = ctypes.c_int
+    lib.perq_permute_rotate_quant.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, vp, vp, vp]
+    lib.perq_permute_rotate_quant_algo.restype = ctypes.c_int
+    lib.perq_permute_rotate_quant_algo.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, ctypes.c_int,
+                                                   vp, vp, vp]
+    lib.perq_permute_rotate_f32.restype = ctypes.c_int
+    lib.perq_permute_rotate_f32.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, vp, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().perq_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != PERQ_OK:
+        raise PerqError(status, where)
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev_ptr(t):
+    return ctypes.c_void_p(t.data_ptr()) if t is not None else ctypes.c_void_p(0)
+
+
+def _check_x(x):
+    import torch
+    if not x.is_cuda or x.dim() != 2 or x.stride(1) != 1 or x.element_size() != 2:
+        raise ValueError("x must be a 2-D CUDA tensor of 16-bit elements with unit column stride")
+    if x.dtype not in (torch.bfloat16, torch.int16, torch.uint16):
+        raise ValueError("x must hold bf16 values (dtype bfloat16, or int16/uint16 bit patterns)")
+    return x.shape[0], x.shape[1], x.stride(0)
+
+
+# ---- host entry points --------------------------------------------------------------------
+def perq_massdiff_perm(colabs_mean: np.ndarray, b: int) -> np.ndarray:
+    a = np.ascontiguousarray(colabs_mean, dtype=np.float32)
+    perm = np.empty(a.shape[0], dtype=np.int32)
+    st = load().perq_massdiff_perm(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], int(b),
+                                   perm.ctypes.data_as(ctypes.c_void_p))
+    _check(st, "perq_massdiff_perm")
+    return perm
+
+
+def perq_perm_validate(perm: np.ndarray) -> bool:
+    p = np.ascontiguousarray(perm, dtype=np.int32)
+    return load().perq_perm_validate(p.ctypes.data_as(ctypes.c_void_p), p.shape[0]) == PERQ_OK
+
+
+# ---- device entry points ------------------------------------------------------------------
+def perq_colabs_mean(x, out=None, stream=None):
+    """x: CUDA bf16 [M, d] -> CUDA float32 [d]."""
+    import torch
+    M, d, ldx = _check_x(x)
+    lib = load()
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=x.device)
+    nbytes = lib.perq_colabs_mean_workspace_bytes(M, d)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    st = lib.perq_colabs_mean(_dev_ptr(x), M, d, ldx, _dev_ptr(out), _dev_ptr(ws), nbytes, _stream_ptr(stream))
+    _check(st, "perq_colabs_mean")
+    return out
+
+
+def alloc_outputs(T: int, d: int, fmt: str, device):
+    import torch
+    codes = torch.empty((T, d // 2), dtype=torch.uint8, device=device)
+    if FMT[fmt] == PERQ_FMT_INT4_SYM_TOKEN:
+        scales = torch.empty(T, dtype=torch.float32, device=device)
+    else:
+        scales = torch.empty((T, d // 32), dtype=torch.uint8, device=device)
+    return codes, scales
+
+
+def perq_permute_rotate_quant(x, perm, b: int, fmt: str, codes=None, scales=None, stream=None,
+                              algo: str = "auto"):
+    """x: CUDA bf16 [T, d]; perm: CUDA int32 [d] or None.  Returns (codes, scales) tensors."""
+    T, d, ldx = _check_x(x)
+    if codes is None or scales is None:
+        codes, scales = alloc_outputs(T, d, fmt, x.device)
+    lib = load()
+    if algo == "auto":
+        st = lib.perq_permute_rotate_quant(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), int(b), FMT[fmt],
+                                           _dev_ptr(codes), _dev_ptr(scales), _stream_ptr(stream))
+    else:
+        st = lib.perq_permute_rotate_quant_algo(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), int(b), FMT[fmt],
+                                                ALGO[algo], _dev_ptr(codes), _dev_ptr(scales),
+                                                _stream_ptr(stream))
+    _check(st, "perq_permute_rotate_quant")
+    return codes, scales
+
+
+def perq_permute_rotate_f32(x, perm, b: int, y=None, stream=None, algo: str = "auto"):
+    """Test entry: pre-quantization values, CUDA float32 [T, d]."""
+    import torch
+    T, d, ldx = _check_x(x)
+    if y is None:
+        y = torch.empty((T, d), dtype=torch.float32, device=x.device)
+    st = load().perq_permute_rotate_f32(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), int(b), ALGO[algo],
+                                        _dev_ptr(y), _stream_ptr(stream))
+    _check(st, "perq_permute_rotate_f32")
+    return y
+
+
+def bits_to_device(bits: np.ndarray, device="cuda"):
+    """uint16 bf16 bit patterns (NumPy) -> CUDA bfloat16 tensor with the same bits."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device)
+    return t.view(torch.bfloat16)

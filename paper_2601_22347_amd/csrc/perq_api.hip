@@ -1,0 +1,119 @@
+// C-ABI entry points of the fused apply path: argument checks, kernel choice, launch.
+#include "perq.h"
+#include "perq_launch.h"
+
+#include <cmath>
+#include <mutex>
+
+namespace perq {
+
+const LaunchInfo& launch_info() {
+    static LaunchInfo info[64];
+    static bool known[64] = {};
+    static std::mutex mu;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (dev < 0 || dev >= 64) dev = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!known[dev]) {
+        int cus = 0, lds = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            cus = 256;
+        if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess ||
+            lds <= 0)
+            lds = 64 * 1024;
+        info[dev].num_cus = cus;
+        info[dev].lds_per_cu = lds;
+        known[dev] = true;
+    }
+    return info[dev];
+}
+
+namespace {
+
+bool is_pow2(int32_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// Shared checks of the apply entry points; fills the kernel parameters.
+perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, const int32_t* perm,
+                          int32_t b, ApplyParams* p) {
+    if (x == nullptr) return PERQ_ERR_INVALID_ARG;
+    if (T < 0 || d <= 0 || ldx < d) return PERQ_ERR_INVALID_ARG;
+    if (!is_pow2(b) || b < 16 || b > d || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    if (d % 32 != 0) return PERQ_ERR_INVALID_ARG;
+    if (d > PERQ_MAX_D) return PERQ_ERR_UNSUPPORTED;
+    if (ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
+    if (perm != nullptr && (reinterpret_cast<uintptr_t>(perm) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
+    int log2b = 0;
+    while ((1 << log2b) < b) ++log2b;
+    p->x = x;
+    p->T = T;
+    p->ldx = ldx;
+    p->perm = perm;
+    p->codes = nullptr;
+    p->scales = nullptr;
+    p->y = nullptr;
+    p->d = d;
+    p->b = b;
+    p->log2b = log2b;
+    p->rsqrt_b = (float)(1.0 / std::sqrt((double)b));
+    p->odd_norm = (log2b & 1) ? (float)std::sqrt(0.5) : 1.0f;
+    p->half_log2b = log2b / 2;
+    p->inv_7sqrt_b = 1.0 / (7.0 * std::sqrt((double)b));
+    return PERQ_OK;
+}
+
+perq_status_t dispatch(const ApplyParams& p, int out_kind, perq_algo_t algo, hipStream_t stream) {
+    if (p.T == 0) return PERQ_OK;
+    hipError_t e;
+    switch (algo) {
+        case PERQ_ALGO_AUTO:
+        case PERQ_ALGO_BUTTERFLY:
+            e = launch_butterfly(p, out_kind, stream);
+            break;
+        case PERQ_ALGO_MFMA:
+            return PERQ_ERR_UNSUPPORTED;
+        default:
+            return PERQ_ERR_INVALID_ARG;
+    }
+    return e == hipSuccess ? PERQ_OK : PERQ_ERR_LAUNCH;
+}
+
+}  // namespace
+}  // namespace perq
+
+extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, int64_t T, int32_t d,
+                                                        int64_t ldx, const int32_t* perm, int32_t b,
+                                                        perq_fmt_t fmt, perq_algo_t algo, uint8_t* codes,
+                                                        void* scales, void* hip_stream) {
+    perq::ApplyParams p;
+    if (codes == nullptr || scales == nullptr) return PERQ_ERR_INVALID_ARG;
+    if (fmt != PERQ_FMT_INT4_SYM_TOKEN && fmt != PERQ_FMT_MXFP4) return PERQ_ERR_INVALID_ARG;
+    const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
+    if (st != PERQ_OK) return st;
+    if ((reinterpret_cast<uintptr_t>(codes) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
+    if (fmt == PERQ_FMT_INT4_SYM_TOKEN && (reinterpret_cast<uintptr_t>(scales) & 3u) != 0)
+        return PERQ_ERR_UNSUPPORTED;
+    p.codes = codes;
+    p.scales = scales;
+    return perq::dispatch(p, fmt == PERQ_FMT_MXFP4 ? perq::OUT_MXFP4 : perq::OUT_INT4, algo,
+                          static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" perq_status_t perq_permute_rotate_quant(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                                   const int32_t* perm, int32_t b, perq_fmt_t fmt,
+                                                   uint8_t* codes, void* scales, void* hip_stream) {
+    return perq_permute_rotate_quant_algo(x_bf16, T, d, ldx, perm, b, fmt, PERQ_ALGO_AUTO, codes, scales,
+                                          hip_stream);
+}
+
+extern "C" perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                                 const int32_t* perm, int32_t b, perq_algo_t algo, float* y,
+                                                 void* hip_stream) {
+    perq::ApplyParams p;
+    if (y == nullptr) return PERQ_ERR_INVALID_ARG;
+    const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
+    if (st != PERQ_OK) return st;
+    if ((reinterpret_cast<uintptr_t>(y) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
+    p.y = y;
+    return perq::dispatch(p, perq::OUT_F32, algo, static_cast<hipStream_t>(hip_stream));
+}

@@ -1,0 +1,258 @@
+// Shuffle-butterfly kernel for X -> quantize(XP R~): every shape the C ABI accepts.
+//
+// Layout.  A row of d = 32*nt elements is spread over nt lanes; lane t owns the 32 contiguous
+// positions [32t, 32t+32) of the permuted row.  Index bits 0..4 are therefore in registers,
+// bits 5..10 are the lane number inside a wave, bits 11.. are the wave number inside the row:
+//
+//    stages 1..16   in registers                       (b = 16, 32 need nothing else)
+//    stages 32..1024 across lanes: DPP, swizzle, permlane swaps
+//    stages 2048..  across waves through LDS           (b >= 4096)
+//
+// The raw bf16 row is staged once in LDS with perfectly coalesced 16-byte global loads (the
+// only HBM read); the gather through `perm` is a 2-byte LDS read per element whose byte
+// address is computed once per lane and kept in registers for every row the workgroup
+// processes.  With one lane per 32 outputs an MXFP4 group is lane-local and each lane stores
+// 16 contiguous bytes of codes.
+//
+// Rows narrower than 8192 are packed several to a 256-thread workgroup when nt is a power of
+// two; otherwise a workgroup of ceil(nt/64) waves handles one row at a time.
+#include "perq_device.h"
+#include "perq_launch.h"
+
+namespace perq {
+
+namespace {
+
+// 16-byte granule g of a row is stored at granule slot g ^ ((g >> 3) & 3): both the coalesced
+// writer (consecutive lanes, consecutive g) and the reader (lane t reads granules 4t..4t+3,
+// one per instruction) then touch 8 distinct 16-byte bank groups per 8 lanes.
+__device__ __forceinline__ uint32_t granule_slot(uint32_t g) { return g ^ ((g >> 3) & 3u); }
+
+struct BflyGeom {
+    int nt;              // lanes per row = d / 32
+    int rows;            // rows per workgroup iteration
+    int waves_per_row;   // ceil(nt / 64)
+    uint32_t row_bytes;  // d * 2
+    uint32_t red_off;    // byte offset of the reduction scratch in LDS
+};
+
+template <int OUT, bool PERM>
+__global__ void __launch_bounds__(1024)
+butterfly_kernel(ApplyParams p, BflyGeom g) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int r = tid / g.nt < g.rows ? tid / g.nt : g.rows - 1;   // row slot of this thread
+    const int t = g.rows > 1 ? tid % g.nt : tid;                   // lane index inside the row
+    const bool active = t < g.nt && tid < g.rows * g.nt;
+    const int d = p.d, b = p.b;
+
+    // -1 / +1 per butterfly distance, in lane units
+    float sgn[6];
+#pragma unroll
+    for (int k = 0; k < 6; ++k) sgn[k] = (t >> k) & 1 ? -1.0f : 1.0f;
+
+    // LDS byte address (inside one staged row) of each of this lane's 32 source elements
+    uint32_t src_addr[PERM ? 32 : 1];
+    if constexpr (PERM) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            int4 e4 = make_int4(0, 0, 0, 0);
+            if (active) e4 = *reinterpret_cast<const int4*>(p.perm + 32 * t + 4 * q);
+            const int e[4] = {e4.x, e4.y, e4.z, e4.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t ee = (uint32_t)e[j];
+                src_addr[4 * q + j] = (granule_slot(ee >> 3) << 4) | ((ee & 7u) << 1);
+            }
+        }
+    }
+
+    const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
+    unsigned char* my_row = lds + (uint32_t)r * g.row_bytes;
+
+    auto load_group = [&](int64_t grp, uint4 (&buf)[4]) {
+        const int64_t row = grp * g.rows + r;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            buf[k] = make_uint4(0, 0, 0, 0);
+            if (active && row < p.T)
+                buf[k] = *reinterpret_cast<const uint4*>(p.x + row * p.ldx + (int64_t)(t + k * g.nt) * 8);
+        }
+    };
+
+    uint4 stage[4];
+    if (blockIdx.x < ngroups) load_group(blockIdx.x, stage);
+
+    for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+        const int64_t row = grp * g.rows + r;
+        const bool live = active && row < p.T;
+
+        // ---- stage the raw rows in LDS ----------------------------------------------------
+        if (active) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                *reinterpret_cast<uint4*>(my_row + (granule_slot((uint32_t)(t + k * g.nt)) << 4)) = stage[k];
+        }
+        __syncthreads();
+        if (grp + gridDim.x < ngroups) load_group(grp + gridDim.x, stage);   // prefetch next rows
+
+        // ---- this lane's 32 permuted elements -> fp32 --------------------------------------
+        float v[32];
+        if constexpr (PERM) {
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                const uint32_t h = active ? *reinterpret_cast<const uint16_t*>(my_row + src_addr[i]) : 0u;
+                v[i] = __uint_as_float(h << 16);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint4 w = make_uint4(0, 0, 0, 0);
+                if (active) w = *reinterpret_cast<const uint4*>(my_row + (granule_slot((uint32_t)(4 * t + j)) << 4));
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    v[8 * j + 2 * q] = bf16lo_to_f32(ww[q]);
+                    v[8 * j + 2 * q + 1] = bf16hi_to_f32(ww[q]);
+                }
+            }
+        }
+
+        // ---- rotation: unnormalised +-1 butterflies ----------------------------------------
+        reg_stages<32>(v, b);                               // distances 1..16 (16 only if b >= 32)
+        if (b >= 64) lane_stage<1>(v, sgn[0]);
+        if (b >= 128) lane_stage<2>(v, sgn[1]);
+        if (b >= 256) lane_stage<4>(v, sgn[2]);
+        if (b >= 512) lane_stage<8>(v, sgn[3]);
+        if (b >= 1024) lane_stage<16>(v, sgn[4]);
+        if (b >= 2048) lane_stage<32>(v, sgn[5]);
+        if (b >= 4096) {
+            // distances 2048.. : partner lane is in another wave; exchange all 32 values through
+            // LDS (aliasing the staged rows, which are dead by now).  Granule j of lane t sits at
+            // slot t*8 + (j ^ (t & 7)) so that 8 consecutive lanes cover all banks.
+            float4* xbuf = reinterpret_cast<float4*>(lds) + (size_t)r * (d >> 2);
+            for (int m = 64; 32 * m < b; m <<= 1) {
+                __syncthreads();
+                if (active) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        xbuf[t * 8 + (j ^ (t & 7))] = make_float4(v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]);
+                }
+                __syncthreads();
+                const int pt = t ^ m;
+                const float s = (t & m) ? -1.0f : 1.0f;
+                if (active) {
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float4 q = xbuf[pt * 8 + (j ^ (pt & 7))];
+                        v[4 * j] = __builtin_fmaf(v[4 * j], s, q.x);
+                        v[4 * j + 1] = __builtin_fmaf(v[4 * j + 1], s, q.y);
+                        v[4 * j + 2] = __builtin_fmaf(v[4 * j + 2], s, q.z);
+                        v[4 * j + 3] = __builtin_fmaf(v[4 * j + 3], s, q.w);
+                    }
+                }
+            }
+        }
+
+        // ---- epilogue -------------------------------------------------------------------------
+        if constexpr (OUT == OUT_F32) {
+            if (live) {
+                float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + 32 * t);
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    yo[j] = make_float4(v[4 * j] * p.rsqrt_b, v[4 * j + 1] * p.rsqrt_b,
+                                        v[4 * j + 2] * p.rsqrt_b, v[4 * j + 3] * p.rsqrt_b);
+            }
+        } else if constexpr (OUT == OUT_MXFP4) {
+            if (p.odd_norm != 1.0f) {
+#pragma unroll
+                for (int i = 0; i < 32; ++i) v[i] *= p.odd_norm;
+            }
+            const int E = mx_shared_exponent(absmax(v), p.half_log2b);
+            const float scale = __uint_as_float((uint32_t)(E + p.half_log2b) << 23);
+            if (live) {
+                const uint4 c = make_uint4(mxfp4_pack8(v, scale), mxfp4_pack8(v + 8, scale),
+                                           mxfp4_pack8(v + 16, scale), mxfp4_pack8(v + 24, scale));
+                *reinterpret_cast<uint4*>(p.codes + row * (int64_t)(d >> 1) + 16 * t) = c;
+                static_cast<uint8_t*>(p.scales)[row * (int64_t)(d >> 5) + t] = (uint8_t)E;
+            }
+        } else {
+            // per-token maximum: lanes of the row inside this wave, then the row's waves
+            float m = absmax(v);
+            if (g.nt > 1) m = fmaxf(m, lane_xor<1>(m));
+            if (g.nt > 2) m = fmaxf(m, lane_xor<2>(m));
+            if (g.nt > 4) m = fmaxf(m, lane_xor<4>(m));
+            if (g.nt > 8) m = fmaxf(m, lane_xor<8>(m));
+            if (g.nt > 16) m = fmaxf(m, lane_xor<16>(m));
+            if (g.nt > 32) m = fmaxf(m, lane_xor<32>(m));
+            if (g.waves_per_row > 1) {
+                float* red = reinterpret_cast<float*>(lds + g.red_off);
+                const int wave = tid >> 6;
+                __syncthreads();               // red[] of the previous row has been consumed
+                if (lane == 0) red[wave] = m;
+                __syncthreads();
+                const int w0 = (r * g.nt) >> 6;
+                for (int w = 0; w < g.waves_per_row; ++w) m = fmaxf(m, red[w0 + w]);
+            }
+            const float inv = m > 0.0f ? 7.0f / m : 0.0f;
+            if (live) {
+                const uint4 c = make_uint4(int4_pack8(v, inv), int4_pack8(v + 8, inv),
+                                           int4_pack8(v + 16, inv), int4_pack8(v + 24, inv));
+                *reinterpret_cast<uint4*>(p.codes + row * (int64_t)(d >> 1) + 16 * t) = c;
+                if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m * p.inv_7sqrt_b);
+            }
+        }
+        __syncthreads();   // LDS is rewritten by the next iteration
+    }
+}
+
+template <int OUT>
+hipError_t launch_butterfly_out(const ApplyParams& p, hipStream_t stream) {
+    BflyGeom g;
+    g.nt = p.d / 32;
+    const bool pow2 = (g.nt & (g.nt - 1)) == 0;
+    int threads;
+    if (pow2 && g.nt <= 256) {
+        g.rows = 256 / g.nt;
+        threads = 256;
+    } else {
+        g.rows = 1;
+        threads = ((g.nt + 63) / 64) * 64;
+    }
+    g.waves_per_row = (g.nt + 63) / 64;
+    g.row_bytes = (uint32_t)p.d * 2u;
+    const uint32_t stage_bytes = (uint32_t)g.rows * g.row_bytes;
+    const uint32_t xchg_bytes = p.b >= 4096 ? (uint32_t)g.rows * (uint32_t)p.d * 4u : 0u;
+    g.red_off = stage_bytes > xchg_bytes ? stage_bytes : xchg_bytes;
+    const uint32_t lds_bytes = g.red_off + 64u * sizeof(float);
+
+    auto kern = p.perm ? butterfly_kernel<OUT, true> : butterfly_kernel<OUT, false>;
+    if (lds_bytes > 64u * 1024u) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    // Persistent grid: as many workgroups as the device keeps resident, each walking the rows.
+    int per_cu = 0;
+    hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, lds_bytes);
+    if (oe != hipSuccess) return oe;
+    if (per_cu < 1) per_cu = 1;
+    const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
+    int64_t grid = (int64_t)launch_info().num_cus * per_cu;
+    if (grid > ngroups) grid = ngroups;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3((unsigned)threads), lds_bytes, stream, p, g);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_butterfly(const ApplyParams& p, int out_kind, hipStream_t stream) {
+    switch (out_kind) {
+        case OUT_INT4: return launch_butterfly_out<OUT_INT4>(p, stream);
+        case OUT_MXFP4: return launch_butterfly_out<OUT_MXFP4>(p, stream);
+        default: return launch_butterfly_out<OUT_F32>(p, stream);
+    }
+}
+
+}  // namespace perq

@@ -1,0 +1,102 @@
+// a_i = (1/M) sum_k |x[k,i]|  -- the sort key of Algorithm 1 -- as two deterministic passes.
+//
+// Pass 1: the M rows are cut into S slices; workgroup (column tile, slice) adds |x| over its
+// rows, each lane owning 8 adjacent columns (one 16-byte bf16 load per row), and writes fp32
+// partial sums part[slice][column].  Pass 2: one lane per column adds the S partials in slice
+// order (in double) and divides by M.  No atomics: the result is independent of scheduling.
+// Rounding: at most rows_per_slice - 1 fp32 additions of non-negative terms per partial, so the
+// relative error of a_i is below (rows_per_slice + 1) * 2^-24.
+#include "perq.h"
+#include "perq_launch.h"
+
+namespace perq {
+namespace {
+
+constexpr int kColsPerLane = 8;
+constexpr int kThreads = 256;
+constexpr int kTileCols = kColsPerLane * kThreads;   // 2048
+
+struct ColabsPlan {
+    int col_tiles;
+    int slices;
+    int rows_per_slice;
+};
+
+ColabsPlan colabs_plan(int64_t M, int32_t d) {
+    ColabsPlan pl;
+    pl.col_tiles = (d + kTileCols - 1) / kTileCols;
+    int64_t want = 2048 / pl.col_tiles;          // ~8 workgroups per CU in total
+    if (want < 1) want = 1;
+    int64_t rps = (M + want - 1) / want;
+    if (rps < 8) rps = 8;                        // at least a few rows per lane
+    pl.rows_per_slice = (int)rps;
+    pl.slices = (int)((M + rps - 1) / rps);
+    return pl;
+}
+
+__global__ void __launch_bounds__(kThreads)
+colabs_partial_kernel(const uint16_t* __restrict__ x, int64_t M, int32_t d, int64_t ldx,
+                      int rows_per_slice, float* __restrict__ part) {
+    const int col = blockIdx.x * kTileCols + threadIdx.x * kColsPerLane;
+    if (col >= d) return;
+    const int64_t r0 = (int64_t)blockIdx.y * rows_per_slice;
+    const int64_t r1 = r0 + rows_per_slice < M ? r0 + rows_per_slice : M;
+    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    const uint16_t* px = x + col;
+#pragma unroll 4
+    for (int64_t r = r0; r < r1; ++r) {
+        const uint4 w = *reinterpret_cast<const uint4*>(px + r * ldx);
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            acc[2 * q] += fabsf(bf16lo_to_f32(ww[q]));
+            acc[2 * q + 1] += fabsf(bf16hi_to_f32(ww[q]));
+        }
+    }
+    float4* out = reinterpret_cast<float4*>(part + (int64_t)blockIdx.y * d + col);
+    out[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+}
+
+__global__ void __launch_bounds__(kThreads)
+colabs_finish_kernel(const float* __restrict__ part, int slices, int32_t d, float m_rows,
+                     float* __restrict__ out) {
+    const int col = blockIdx.x * kThreads + threadIdx.x;
+    if (col >= d) return;
+    double s = 0.0;   // the slice partials are combined in double: only pass 1 rounds in fp32
+    for (int k = 0; k < slices; ++k) s += (double)part[(int64_t)k * d + col];
+    out[col] = (float)(s / (double)m_rows);
+}
+
+}  // namespace
+}  // namespace perq
+
+extern "C" size_t perq_colabs_mean_workspace_bytes(int64_t M, int32_t d) {
+    if (M <= 0 || d <= 0) return 0;
+    const perq::ColabsPlan pl = perq::colabs_plan(M, d);
+    return (size_t)pl.slices * (size_t)d * sizeof(float);
+}
+
+extern "C" perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                                          float* out_mean, void* workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+    if (x_bf16 == nullptr || out_mean == nullptr) return PERQ_ERR_INVALID_ARG;
+    if (M <= 0 || d <= 0 || ldx < d) return PERQ_ERR_INVALID_ARG;
+    if (d % 8 != 0 || ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x_bf16) & 15u) != 0)
+        return PERQ_ERR_UNSUPPORTED;
+    const size_t need = perq_colabs_mean_workspace_bytes(M, d);
+    if (workspace == nullptr || workspace_bytes < need) return PERQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return PERQ_ERR_INVALID_ARG;
+
+    const perq::ColabsPlan pl = perq::colabs_plan(M, d);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    float* part = static_cast<float*>(workspace);
+    hipLaunchKernelGGL(perq::colabs_partial_kernel, dim3(pl.col_tiles, pl.slices), dim3(perq::kThreads),
+                       0, stream, x_bf16, M, d, ldx, pl.rows_per_slice, part);
+    if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
+    hipLaunchKernelGGL(perq::colabs_finish_kernel, dim3((d + perq::kThreads - 1) / perq::kThreads),
+                       dim3(perq::kThreads), 0, stream, part, pl.slices, d, (float)M,
+                       out_mean);
+    if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
+    return PERQ_OK;
+}

@@ -1,0 +1,154 @@
+// Device-side building blocks shared by the PeRQ apply kernels (gfx950, wave64).
+//
+//  - bf16 <-> fp32 bit moves
+//  - lane-xor butterflies on DPP / swizzle / permlane-swap
+//  - the three epilogues on a run of 32 contiguous rotated outputs held by one lane:
+//      INT4 symmetric per token   (Section 3; Appendix B Eq. 4, z = 0)
+//      MXFP4                      (Appendix B Eq. 5: e2m1 + one power-of-two scale per 32)
+//      fp32 dump                  (test entry)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace perq {
+
+enum OutKind { OUT_INT4 = 0, OUT_MXFP4 = 1, OUT_F32 = 2 };
+
+struct ApplyParams {
+    const uint16_t* x;      // bf16 [T, ldx]
+    int64_t T;
+    int64_t ldx;
+    const int32_t* perm;    // int32 [d] or nullptr
+    uint8_t* codes;         // [T, d/2]
+    void* scales;           // float [T] or uint8 [T, d/32]
+    float* y;               // [T, d] (test entry only)
+    int32_t d;
+    int32_t b;
+    int32_t log2b;
+    float rsqrt_b;          // fl32(1/sqrt(b))
+    float odd_norm;         // 1.0 if log2b even, fl32(1/sqrt(2)) if odd
+    int32_t half_log2b;     // floor(log2b / 2)
+    double inv_7sqrt_b;     // 1 / (7 sqrt(b)) in double
+};
+
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// ---- lane-xor exchange: value held by lane (l ^ M) ---------------------------------------
+template <int M>
+__device__ __forceinline__ float lane_xor(float v) {
+    const int iv = __float_as_int(v);
+    if constexpr (M == 1) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(iv, iv, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+    } else if constexpr (M == 2) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(iv, iv, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+    } else if constexpr (M == 4) {
+        return __int_as_float(__builtin_amdgcn_ds_swizzle(iv, 0x101F));                      // xor 4 inside 32 lanes
+    } else if constexpr (M == 8) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(iv, iv, 0x128, 0xF, 0xF, false));  // row_ror:8
+    } else if constexpr (M == 16) {
+        return __int_as_float(__builtin_amdgcn_ds_swizzle(iv, 0x401F));                      // xor 16 inside 32 lanes
+    } else {
+        return __shfl_xor(v, 32, 64);
+    }
+}
+
+// One radix-2 butterfly stage across lanes for N registers: v <- (lane & M) ? p - v : p + v,
+// p = value of lane ^ M.  `sgn` is -1 in lanes with bit M set, +1 elsewhere.
+template <int M, int N>
+__device__ __forceinline__ void lane_stage(float (&v)[N], float sgn) {
+    if constexpr (M == 16 || M == 32) {
+        // Two registers at a time through a half-wave (or odd/even row) swap: after the first
+        // swap every lane holds both operands of one butterfly, after the second each result
+        // is back with its owner.  Pure VALU, no LDS crossbar.
+#pragma unroll
+        for (int i = 0; i < N; i += 2) {
+            const uint32_t u = __float_as_uint(v[i]), w = __float_as_uint(v[i + 1]);
+            uint32_t r0, r1;
+            if constexpr (M == 32) {
+                auto r = __builtin_amdgcn_permlane32_swap(u, w, false, false); r0 = r[0]; r1 = r[1];
+            } else {
+                auto r = __builtin_amdgcn_permlane16_swap(u, w, false, false); r0 = r[0]; r1 = r[1];
+            }
+            const float s = __uint_as_float(r0) + __uint_as_float(r1);
+            const float t = __uint_as_float(r0) - __uint_as_float(r1);
+            uint32_t q0, q1;
+            if constexpr (M == 32) {
+                auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(s), __float_as_uint(t), false, false);
+                q0 = q[0]; q1 = q[1];
+            } else {
+                auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(s), __float_as_uint(t), false, false);
+                q0 = q[0]; q1 = q[1];
+            }
+            v[i] = __uint_as_float(q0);
+            v[i + 1] = __uint_as_float(q1);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = __builtin_fmaf(v[i], sgn, lane_xor<M>(v[i]));
+    }
+}
+
+// In-register radix-2 stages on a run of N = 2^k contiguous elements, strides 1 .. hmax/2.
+template <int N>
+__device__ __forceinline__ void reg_stages(float (&v)[N], int hmax) {
+#pragma unroll
+    for (int h = 1; h < N; h <<= 1) {
+        if (h < hmax) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+                if ((i & h) == 0) {
+                    const float a = v[i], c = v[i | h];
+                    v[i] = a + c;
+                    v[i | h] = a - c;
+                }
+            }
+        }
+    }
+}
+
+template <int N>
+__device__ __forceinline__ float absmax(const float (&v)[N]) {
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) m = fmaxf(m, fabsf(v[i]));
+    return m;
+}
+
+// ---- INT4: 8 values -> one dword of two's-complement nibbles, element 0 in bits 3:0 ------
+// fma(y, inv, 1.5*2^23) rounds y*inv to an integer with ties to even in one step; the low
+// mantissa bits of the sum are the integer in two's complement.
+__device__ __forceinline__ uint32_t int4_pack8(const float* v, float inv) {
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 7; i >= 0; --i) {
+        const uint32_t t = __float_as_uint(__builtin_fmaf(v[i], inv, 12582912.0f));
+        w = (w << 4) | (t & 0xFu);
+    }
+    return w;
+}
+
+// ---- MXFP4: 8 values -> one dword of e2m1 nibbles ----------------------------------------
+// The hardware convert divides by 2^(exponent field of `scale` - 127), rounds to nearest even
+// on the e2m1 grid and saturates at 6.  A value that rounds to zero keeps its sign bit, so
+// nibbles 0x8 are rewritten to 0x0 (zero is always stored as +0).
+__device__ __forceinline__ uint32_t mxfp4_pack8(const float* v, float scale) {
+    uint32_t w = 0;
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[0], v[1], scale, 0);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[2], v[3], scale, 1);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[4], v[5], scale, 2);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[6], v[7], scale, 3);
+    const uint32_t mag = w & 0x77777777u;
+    const uint32_t nz = (mag + 0x77777777u) & 0x88888888u;   // bit 3 of a nibble set iff magnitude != 0
+    return mag | (w & nz);
+}
+
+// Shared exponent of one 32-group from its (already normalised up to 2^-k) maximum:
+// E = clamp(expfield(amax) - k - 2, 0, 254); an all-zero or subnormal maximum gives E = 0.
+__device__ __forceinline__ int mx_shared_exponent(float amax_scaled, int k) {
+    int e = (int)((__float_as_uint(amax_scaled) >> 23) & 0xFFu) - k - 2;
+    e = e < 0 ? 0 : e;
+    return e > 254 ? 254 : e;
+}
+
+}  // namespace perq

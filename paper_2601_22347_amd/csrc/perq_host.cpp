@@ -1,0 +1,66 @@
+// Host side of the PeRQ library: status strings, Algorithm 1 (mass diffusion) and the
+// permutation validator.  No device code here.
+#include "perq.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <numeric>
+#include <queue>
+#include <utility>
+#include <vector>
+
+extern "C" const char* perq_status_string(perq_status_t status) {
+    switch (status) {
+        case PERQ_OK: return "PERQ_OK";
+        case PERQ_ERR_INVALID_ARG: return "PERQ_ERR_INVALID_ARG";
+        case PERQ_ERR_UNSUPPORTED: return "PERQ_ERR_UNSUPPORTED";
+        case PERQ_ERR_LAUNCH: return "PERQ_ERR_LAUNCH";
+    }
+    return "PERQ_ERR_UNKNOWN";
+}
+
+// Algorithm 1.  The argmin over not-yet-full blocks of the accumulated block mass is served by
+// a binary heap keyed on (mass, block index); a block that fills up is simply not pushed back,
+// which is the algorithm's "drop j* from the valid set".  Lexicographic keys give the
+// lowest-index block among equal masses, the stable sort gives the lower channel among equal
+// means -- the two tie rules the paper leaves open.
+extern "C" perq_status_t perq_massdiff_perm(const float* colabs_mean, int32_t d, int32_t b,
+                                            int32_t* perm_out) {
+    if (colabs_mean == nullptr || perm_out == nullptr) return PERQ_ERR_INVALID_ARG;
+    if (d <= 0 || b <= 0 || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < d; ++i)
+        if (!std::isfinite(colabs_mean[i]) || colabs_mean[i] < 0.0f) return PERQ_ERR_INVALID_ARG;
+
+    const int32_t n = d / b;
+    std::vector<int32_t> order(d);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+        return colabs_mean[x] > colabs_mean[y];
+    });
+
+    using Key = std::pair<double, int32_t>;   // (accumulated mass L_j, block j)
+    std::priority_queue<Key, std::vector<Key>, std::greater<Key>> valid;
+    for (int32_t j = 0; j < n; ++j) valid.emplace(0.0, j);
+    std::vector<int32_t> fill(n, 0);
+
+    for (int32_t i : order) {
+        Key top = valid.top();
+        valid.pop();
+        const int32_t j = top.second;
+        perm_out[static_cast<int64_t>(j) * b + fill[j]] = i;
+        if (++fill[j] < b) valid.emplace(top.first + static_cast<double>(colabs_mean[i]), j);
+    }
+    return PERQ_OK;
+}
+
+extern "C" perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d) {
+    if (perm_host == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
+    std::vector<uint8_t> seen(d, 0);
+    for (int32_t i = 0; i < d; ++i) {
+        const int32_t p = perm_host[i];
+        if (p < 0 || p >= d || seen[p]) return PERQ_ERR_INVALID_ARG;
+        seen[p] = 1;
+    }
+    return PERQ_OK;
+}

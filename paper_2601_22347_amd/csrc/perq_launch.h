@@ -1,0 +1,20 @@
+// Host-side launch plumbing shared by the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "perq_device.h"
+
+namespace perq {
+
+struct LaunchInfo {
+    int num_cus;
+    int lds_per_cu;   // bytes
+};
+
+// Properties of the current device (queried once per process and device).
+const LaunchInfo& launch_info();
+
+// Kernel families behind perq_permute_rotate_quant / perq_permute_rotate_f32.
+hipError_t launch_butterfly(const ApplyParams& p, int out_kind, hipStream_t stream);
+
+}  // namespace perq

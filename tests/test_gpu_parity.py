@@ -1,0 +1,196 @@
+"""HIP library vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import parity  # noqa: E402
+from oracle import perq_oracle as orc  # noqa: E402
+from paper_2601_22347_amd import binding, synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = ["butterfly", "auto"]
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def run_gpu(x_bits, perm, b, fmt, algo="auto", want_y=True, ldx=None):
+    """One call of the fused path (+ the fp32 test entry) on cuda:0; NumPy results."""
+    torch = _torch()
+    T, d = x_bits.shape
+    if ldx is None:
+        x = binding.bits_to_device(x_bits)
+    else:
+        buf = torch.zeros((max(T, 1), ldx), dtype=torch.bfloat16, device="cuda")
+        buf[:T, :d] = binding.bits_to_device(x_bits)
+        x = buf[:T, :d]
+    perm_t = None if perm is None else torch.from_numpy(np.ascontiguousarray(perm, dtype=np.int32)).cuda()
+    codes, scales = binding.perq_permute_rotate_quant(x, perm_t, b, fmt, algo=algo)
+    y = binding.perq_permute_rotate_f32(x, perm_t, b, algo=algo) if want_y else None
+    torch.cuda.synchronize()
+    return codes.cpu().numpy(), scales.cpu().numpy(), (None if y is None else y.cpu().numpy())
+
+
+def assert_parity(x_bits, perm, b, fmt, algo="auto", rotate=None, ldx=None, label=""):
+    print(f"[case] {label} T={x_bits.shape[0]} d={x_bits.shape[1]} b={b} fmt={fmt} algo={algo} "
+          f"perm={'yes' if perm is not None else 'no'}", flush=True)
+    codes, scales, y = run_gpu(x_bits, perm, b, fmt, algo=algo, ldx=ldx)
+    rep = parity.compare_apply(x_bits, perm, b, fmt, codes, scales, y, rotate=rotate)
+    print("       ", rep.summary(), flush=True)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
+    return rep
+
+
+# ---- configs[0]: tiny, identity and greedy perm ------------------------------------------
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("fmt", ["int4", "mxfp4"])
+def test_tiny_identity_and_greedy(fmt, algo):
+    wl = synth.tiny()
+    x = wl.apply_rows()
+    assert_parity(x, None, 16, fmt, algo, label="tiny/identity")
+    a = orc.colabs_mean(orc.bf16_bits_to_f64(wl.calib_rows())).astype(np.float32)
+    perm = binding.perq_massdiff_perm(a, 16)
+    assert_parity(x, perm, 16, fmt, algo, label="tiny/greedy")
+
+
+# ---- structured inputs with closed-form answers --------------------------------------------
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("d,b", [(256, 16), (256, 256), (1024, 64), (4096, 4096), (2048, 128)])
+def test_structured_rows(d, b, algo):
+    rng = np.random.default_rng(d + b)
+    rows = []
+    for pos in (0, b - 1, d - 1, d // 2 + 3):
+        r = np.zeros(d); r[pos] = -3.5; rows.append(r)               # one-hot
+    rows.append(np.ones(d) * 0.75)                                    # all equal
+    rows.append(np.zeros(d))                                          # all zero
+    base = rng.standard_normal(d)
+    rows += [base, -base, base * 2.0 ** 10, base * 2.0 ** -10]        # sign flip, power-of-two scaling
+    rows.append(np.where(np.arange(d) % 2 == 0, 1.0, -1.0))           # alternating signs
+    x = synth.f64_to_bf16_bits(np.array(rows))
+    for fmt in ("int4", "mxfp4"):
+        codes, scales, y = run_gpu(x, None, b, fmt, algo)
+        rep = parity.compare_apply(x, None, b, fmt, codes, scales, y)
+        assert rep.ok(), (rep.summary(), rep.notes[:5])
+        # one-hot row: every output of the hit block has magnitude 3.5/sqrt(b), others are 0
+        blk = y[0].reshape(d // b, b)
+        assert np.allclose(np.abs(blk[0]), 3.5 / np.sqrt(b), rtol=1e-6) and np.all(blk[1:] == 0)
+        # all-equal row: (0.75*sqrt(b), 0, ..., 0) per block; all-zero row: zeros and zero scale
+        assert np.allclose(y[4].reshape(d // b, b)[:, 0], 0.75 * np.sqrt(b), rtol=1e-6)
+        assert np.all(y[4].reshape(d // b, b)[:, 1:] == 0)
+        assert np.all(codes[5] == 0) and np.all(scales[5] == 0)
+        # sign flip negates INT4 codes; scaling by 2^k keeps the codes
+        if fmt == "int4":
+            c = parity.unpack_nibbles(codes).astype(np.int16); c = np.where(c >= 8, c - 16, c)
+            assert np.array_equal(c[6], -c[7])
+            assert np.array_equal(c[6], c[8]) and np.array_equal(c[6], c[9])
+            assert scales[8] == scales[6] * 2.0 ** 10 and scales[9] == scales[6] * 2.0 ** -10
+        else:
+            assert np.array_equal(codes[6], codes[8]) and np.array_equal(codes[6], codes[9])
+            assert np.array_equal(scales[8].astype(int), scales[6].astype(int) + 10)
+
+
+# ---- shapes: several tiles, ragged tails, row strides, permutations -------------------------
+SHAPES = [
+    # (T, d, b list)
+    (37, 256, [16, 32, 64, 128, 256]),
+    (19, 1024, [16, 32, 256, 512, 1024]),
+    (13, 3072, [16, 32, 64, 1024]),          # nt = 96: not a power of two
+    (21, 2048, [32, 2048]),
+    (9, 8192, [16, 32, 64, 128, 2048, 8192]),
+    (5, 14336, [32, 128, 512, 2048]),
+    (3, 32768, [16, 32768]),
+]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("T,d,bs", SHAPES)
+def test_shapes_against_oracle(T, d, bs, algo):
+    rng = np.random.default_rng(1000 + d)
+    x = synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d)) * np.exp(rng.uniform(-3, 3, size=(T, 1))))
+    x[:, rng.choice(d, size=max(1, d // 100), replace=False)] = synth.f64_to_bf16_bits(
+        rng.standard_normal((T, max(1, d // 100))) * 60)
+    perm = rng.permutation(d).astype(np.int32)
+    for b in bs:
+        rotate = orc.fwht_f64 if b > 4096 else None
+        for fmt in ("int4", "mxfp4"):
+            assert_parity(x, None, b, fmt, algo, rotate=rotate, label="shape/identity")
+            assert_parity(x, perm, b, fmt, algo, rotate=rotate, label="shape/perm")
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_row_stride_and_special_perms(algo):
+    rng = np.random.default_rng(7)
+    T, d = 11, 512
+    x = synth.f64_to_bf16_bits(rng.standard_normal((T, d)))
+    assert_parity(x, None, 32, "int4", algo, ldx=d + 64, label="ldx")
+    assert_parity(x, np.arange(d, dtype=np.int32), 32, "int4", algo, label="identity-as-perm")
+    assert_parity(x, np.arange(d, dtype=np.int32)[::-1].copy(), 64, "mxfp4", algo, ldx=d + 8, label="reverse")
+    # a permutation followed by its inverse is the identity path on the un-permuted data
+    perm = rng.permutation(d).astype(np.int32)
+    xp = x[:, perm]
+    c1, s1, y1 = run_gpu(xp, np.argsort(perm).astype(np.int32), 128, "int4", algo)
+    c2, s2, y2 = run_gpu(x, None, 128, "int4", algo)
+    assert np.array_equal(c1, c2) and np.array_equal(s1, s2) and np.array_equal(y1, y2)
+
+
+def test_empty_and_single_row():
+    torch = _torch()
+    x = torch.zeros((0, 256), dtype=torch.bfloat16, device="cuda")
+    codes, scales = binding.perq_permute_rotate_quant(x, None, 16, "int4")
+    assert codes.shape == (0, 128) and scales.shape == (0,)
+    bits = synth.f64_to_bf16_bits(np.random.default_rng(3).standard_normal((1, 4096)))
+    assert_parity(bits, None, 128, "int4", label="single-row")
+    assert_parity(bits, None, 32, "mxfp4", label="single-row")
+
+
+def test_deterministic_across_launches():
+    bits = synth.llama1b_down().apply_rows(0, 300)
+    a = run_gpu(bits, None, 128, "int4", want_y=False)
+    b_ = run_gpu(bits, None, 128, "int4", want_y=False)
+    assert np.array_equal(a[0], b_[0]) and np.array_equal(a[1], b_[1])
+
+
+# ---- reduced-T versions of configs[1..4]: every (d, b, fmt) the workloads name ---------------
+def _calibrated_perm(wl, b):
+    a = orc.colabs_mean(orc.bf16_bits_to_f64(wl.calib_rows())).astype(np.float32)
+    return binding.perq_massdiff_perm(a, b)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("name", ["llama1b_down", "block_vs_full", "llama8b_d4096", "llama8b_d14336",
+                                  "calib_apply"])
+def test_workload_slices(name, algo):
+    wl = synth.ALL[name]()
+    rows = 160 if wl.d <= 8192 else 96
+    x = wl.apply_rows(0, rows)
+    if wl.massive_rows.size:                      # include a x200 row
+        r = int(wl.massive_rows[0])
+        x = np.concatenate([x, wl.apply_rows(r, r + 1)])
+    for b in wl.block_sizes:
+        perm = _calibrated_perm(wl, b) if wl.calib_tokens else None
+        assert_parity(x, perm, b, wl.fmt, algo, label=name)
+
+
+# ---- perq_colabs_mean ---------------------------------------------------------------------------
+@pytest.mark.parametrize("M,d", [(256, 256), (2048, 8192), (4096, 8192), (1000, 14336), (3, 32)])
+def test_colabs_mean(M, d):
+    rng = np.random.default_rng(M + d)
+    bits = synth.f64_to_bf16_bits(rng.standard_t(3, size=(M, d)))
+    got = binding.perq_colabs_mean(binding.bits_to_device(bits))
+    _torch().cuda.synchronize()
+    got = got.cpu().numpy()
+    want = orc.colabs_mean(orc.bf16_bits_to_f64(bits))
+    # fp32 accumulation: rows-per-slice sequential adds, then <= 2048 partials; all terms >= 0
+    assert np.all(np.abs(got - want) <= 2e-6 * want + 1e-30)
+    again = binding.perq_colabs_mean(binding.bits_to_device(bits)).cpu().numpy()
+    assert np.array_equal(got, again)
+    # constant-magnitude columns are exact
+    const = synth.f64_to_bf16_bits(np.sign(rng.standard_normal((M, d))) * (1 + np.arange(d) % 7))
+    got = binding.perq_colabs_mean(binding.bits_to_device(const)).cpu().numpy()
+    assert np.array_equal(got, (1 + np.arange(d) % 7).astype(np.float32))

@@ -1,0 +1,101 @@
+"""Host-side checks that need no GPU: the C-ABI library loads, exports what the header
+declares, rejects bad arguments before touching the device, and its greedy matches the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import perq_oracle as orc
+from paper_2601_22347_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "perq.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(perq_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert binding.status_string(0) == "PERQ_OK"
+    assert binding.status_string(1) == "PERQ_ERR_INVALID_ARG"
+    assert binding.status_string(2) == "PERQ_ERR_UNSUPPORTED"
+    assert binding.status_string(3) == "PERQ_ERR_LAUNCH"
+
+
+@pytest.mark.parametrize("d,b,seed", [(256, 16, 0), (256, 32, 1), (8192, 16, 2), (8192, 128, 3),
+                                      (14336, 2048, 4), (4096, 4096, 5), (96, 8, 6)])
+def test_greedy_matches_oracle_bit_exactly(d, b, seed):
+    rng = np.random.default_rng(seed)
+    a = np.abs(rng.standard_t(3, size=d)).astype(np.float32)
+    a[rng.choice(d, size=max(1, d // 100), replace=False)] *= 50
+    if seed % 2:
+        a[rng.choice(d, size=d // 4, replace=False)] = a[0]          # plenty of ties
+    got = binding.perq_massdiff_perm(a, b)
+    want = orc.massdiff_greedy(a.astype(np.float64), b)
+    assert np.array_equal(got, want)
+    assert binding.perq_perm_validate(got)
+
+
+def test_greedy_on_calibration_statistic_of_tiny_workload():
+    wl = synth.tiny()
+    a = orc.colabs_mean(orc.bf16_bits_to_f64(wl.calib_rows())).astype(np.float32)
+    assert np.array_equal(binding.perq_massdiff_perm(a, 16), orc.massdiff_greedy(a.astype(np.float64), 16))
+
+
+def test_greedy_rejects_bad_arguments(lib):
+    a = np.ones(64, dtype=np.float32)
+    perm = np.empty(64, dtype=np.int32)
+    pa, pp = a.ctypes.data_as(ctypes.c_void_p), perm.ctypes.data_as(ctypes.c_void_p)
+    assert lib.perq_massdiff_perm(None, 64, 16, pp) == binding.PERQ_ERR_INVALID_ARG
+    assert lib.perq_massdiff_perm(pa, 64, 16, None) == binding.PERQ_ERR_INVALID_ARG
+    assert lib.perq_massdiff_perm(pa, 64, 24, pp) == binding.PERQ_ERR_INVALID_ARG
+    assert lib.perq_massdiff_perm(pa, 0, 16, pp) == binding.PERQ_ERR_INVALID_ARG
+    a[3] = np.nan
+    assert lib.perq_massdiff_perm(pa, 64, 16, pp) == binding.PERQ_ERR_INVALID_ARG
+    a[3] = -1.0
+    assert lib.perq_massdiff_perm(pa, 64, 16, pp) == binding.PERQ_ERR_INVALID_ARG
+
+
+def test_perm_validate():
+    assert binding.perq_perm_validate(np.arange(100)[::-1])
+    assert not binding.perq_perm_validate(np.array([0, 1, 1, 3]))
+    assert not binding.perq_perm_validate(np.array([0, 1, 2, 4]))
+    assert not binding.perq_perm_validate(np.array([0, -1, 2, 3]))
+
+
+def test_apply_argument_checks_happen_before_any_launch(lib):
+    """Bad shapes are refused on the host; the fake non-null pointers are never dereferenced."""
+    fake = ctypes.c_void_p(0x1000)
+    bad16 = ctypes.c_void_p(0x1008)
+    INV, UNS = binding.PERQ_ERR_INVALID_ARG, binding.PERQ_ERR_UNSUPPORTED
+
+    def q(x=fake, T=4, d=256, ldx=256, perm=None, b=16, fmt=0, codes=fake, scales=fake):
+        return lib.perq_permute_rotate_quant(x, T, d, ldx, perm, b, fmt, codes, scales, None)
+
+    assert q(x=None) == INV and q(codes=None) == INV and q(scales=None) == INV
+    assert q(T=-1) == INV and q(d=0) == INV and q(ldx=128) == INV
+    assert q(b=8) == INV and q(b=24) == INV and q(b=512) == INV and q(d=96, ldx=96, b=64) == INV
+    assert q(d=48, ldx=48, b=16) == INV          # d % 32
+    assert q(fmt=7) == INV
+    assert q(d=65536, ldx=65536, b=16) == UNS
+    assert q(x=bad16) == UNS and q(ldx=260) == UNS and q(codes=bad16) == UNS
+    assert q(T=0) == binding.PERQ_OK
+    assert lib.perq_permute_rotate_quant_algo(fake, 4, 256, 256, None, 16, 0, 9, fake, fake, None) == INV
+    assert lib.perq_permute_rotate_f32(fake, 4, 256, 256, None, 16, 0, None, None) == INV
+    assert lib.perq_permute_rotate_f32(fake, 0, 256, 256, None, 16, 0, fake, None) == binding.PERQ_OK
+    # colabs
+    assert lib.perq_colabs_mean(None, 4, 256, 256, fake, fake, 1 << 20, None) == INV
+    assert lib.perq_colabs_mean(fake, 0, 256, 256, fake, fake, 1 << 20, None) == INV
+    assert lib.perq_colabs_mean(fake, 4, 256, 256, fake, fake, 16, None) == INV      # workspace too small
+    assert lib.perq_colabs_mean(fake, 4, 256, 256, fake, None, 0, None) == INV
+    assert lib.perq_colabs_mean_workspace_bytes(4096, 8192) >= 8192 * 4
+    assert lib.perq_colabs_mean_workspace_bytes(0, 8192) == 0
