@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Throughput of the fused permute + block-Hadamard + quantize path on one MI355X.
+
+A step is one call of perq_permute_rotate_quant on a T-token batch already resident in HBM
+(gather through the calibrated permutation, rotation, scale, round, pack).  The calibration
+that produces the permutation (perq_colabs_mean on the device, the greedy on the host) runs
+once before the timed region, as it does once per layer in the method, and is reported in
+its own field.  Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+
+WORKLOADS = {
+    # name: (generator key, b, fmt, use calibrated perm)
+    "llama8b_d4096_b128_int4_perm": ("llama8b_d4096", 128, "int4", True),
+    "llama8b_d4096_b4096_int4_perm": ("llama8b_d4096", 4096, "int4", True),
+    "llama8b_d14336_b128_int4_perm": ("llama8b_d14336", 128, "int4", True),
+    "llama8b_d14336_b2048_int4_perm": ("llama8b_d14336", 2048, "int4", True),
+    "llama1b_down_b32_int4_perm": ("llama1b_down", 32, "int4", True),
+    "block_vs_full_b32_mxfp4": ("block_vs_full", 32, "mxfp4", False),
+    "block_vs_full_b2048_mxfp4": ("block_vs_full", 2048, "mxfp4", False),
+    "calib_apply_b32_mxfp4_perm": ("calib_apply", 32, "mxfp4", True),
+    "calib_apply_b16_mxfp4_perm": ("calib_apply", 16, "mxfp4", True),
+}
+DEFAULT = "llama8b_d4096_b128_int4_perm"
+
+
+def algorithmic_bytes(T: int, d: int, fmt: str) -> int:
+    """What the method itself must move per launch: bf16 in, nibbles out, scales out."""
+    scales = 4 * T if fmt == "int4" else T * d // 32
+    return T * d * 2 + T * d // 2 + scales
+
+
+def gen_rows_parallel(wl, r0, r1, threads=8):
+    """Apply-time rows [r0, r1) generated chunk by chunk on a few threads (NumPy releases the GIL)."""
+    from concurrent.futures import ThreadPoolExecutor
+    from paper_2601_22347_amd import synth
+    edges = list(range(r0 - r0 % synth.CHUNK, r1, synth.CHUNK))
+    spans = [(max(e, r0), min(e + synth.CHUNK, r1)) for e in edges]
+    out = np.empty((r1 - r0, wl.d), dtype=np.uint16)
+
+    def work(span):
+        a, b_ = span
+        out[a - r0:b_ - r0] = wl.apply_rows(a, b_)
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(work, spans))
+    return out
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("HBM_BYTES_PER_LAUNCH="):
+            return float(line.split("=", 1)[1])
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=DEFAULT, choices=sorted(WORKLOADS))
+    ap.add_argument("--algo", default="auto", choices=["auto", "butterfly", "mfma"])
+    ap.add_argument("--pool-bytes", type=float, default=1.5e9,
+                    help="input+output bytes cycled through so that no step re-reads cached data")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (token rows would be sharded across GPUs "
+              "with no exchange; nothing here uses a second device). Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2601_22347_amd import binding, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.load()
+
+    key, b, fmt, use_perm = WORKLOADS[args.workload]
+    wl = synth.ALL[key]()
+    T, d = wl.T, wl.d
+    dev = torch.device("cuda:0")
+
+    t0 = time.perf_counter()
+    x_bits = gen_rows_parallel(wl, 0, T)
+    gen_s = time.perf_counter() - t0
+
+    # ---- calibration: colabs mean on the device, greedy on the host (once, untimed region) ----
+    calib = None
+    perm_np = perm_t = None
+    if use_perm:
+        xc = binding.bits_to_device(wl.calib_rows())
+        a_t = binding.perq_colabs_mean(xc)           # warm-up
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            a_t = binding.perq_colabs_mean(xc, out=a_t)
+        e1.record()
+        torch.cuda.synchronize()
+        a_np = a_t.cpu().numpy()
+        h0 = time.perf_counter()
+        perm_np = binding.perq_massdiff_perm(a_np, b)
+        greedy_ms = (time.perf_counter() - h0) * 1e3
+        assert binding.perq_perm_validate(perm_np)
+        perm_t = torch.from_numpy(perm_np).to(dev)
+        calib = {"colabs_mean_tokens": wl.calib_tokens, "colabs_mean_ms": e0.elapsed_time(e1) / 10,
+                 "greedy_host_ms": greedy_ms}
+        del xc
+
+    # ---- buffer pool larger than the last-level cache ----------------------------------------
+    per_set = T * d * 2 + T * d // 2
+    nsets = max(2, int(np.ceil(args.pool_bytes / per_set)))
+    x0 = binding.bits_to_device(x_bits, dev)
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    outs = [binding.alloc_outputs(T, d, fmt, dev) for _ in range(nsets)]
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        k = i % nsets
+        binding.perq_permute_rotate_quant(xs[k], perm_t, b, fmt, codes=outs[k][0], scales=outs[k][1],
+                                          stream=stream, algo=args.algo)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        step(i)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - w0
+    kern_ms = ev0.elapsed_time(ev1) / args.steps        # one kernel per step, back to back
+    ms_per_step = wall_s * 1e3 / args.steps
+    tokens_per_s = T / (ms_per_step * 1e-3)
+
+    alg_bytes = algorithmic_bytes(T, d, fmt)
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+
+    # ---- self-check of the timed configuration on sampled rows --------------------------------
+    check = None
+    if not args.no_check:
+        import parity
+        rng = np.random.default_rng(0)
+        rows = np.unique(np.concatenate([np.arange(32), T - 1 - np.arange(32),
+                                         rng.choice(T, size=64, replace=False), wl.massive_rows[:8]]))
+        codes = outs[(args.steps - 1) % nsets][0][torch.from_numpy(rows).to(dev)].cpu().numpy()
+        sc = outs[(args.steps - 1) % nsets][1][torch.from_numpy(rows).to(dev)].cpu().numpy()
+        rep = parity.compare_apply(x_bits[rows], perm_np, b, fmt, codes, sc)
+        check = dict(rep.summary(), rows=int(rows.size), ok=rep.ok())
+
+    # ---- the oracle on the host cores, bounded sample --------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import perq_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        n = 256
+        c0 = time.perf_counter()
+        orc.perq_apply(x_bits[:n], perm_np, b, fmt)
+        per_row = (time.perf_counter() - c0) / n
+        n2 = int(min(T, max(n, 12.0 / max(per_row, 1e-9))))
+        c0 = time.perf_counter()
+        for s in range(0, n2, 2048):
+            orc.perq_apply(x_bits[s:min(n2, s + 2048)], perm_np, b, fmt)
+        cpu_s = time.perf_counter() - c0
+        cpu = {"value": n2 / cpu_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"first {n2} tokens of the workload, fp64 NumPy, explicit H_b product, {cpu_s:.1f} s"}
+
+    line = {
+        "metric": "fused permute+block-Hadamard+quant tokens/s",
+        "value": tokens_per_s,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "T": T, "d": d, "b": b, "fmt": fmt,
+                   "perm": "greedy-calibrated, gather fused" if use_perm else "identity",
+                   "algo": args.algo, "buffer_sets": nsets, "input_gen_s": round(gen_s, 1)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
+                     "algorithmic_bytes": alg_bytes, "kernel_ms": kern_ms},
+        "cpu_baseline": cpu,
+        "calibration": calib,
+        "check": check,
+    }
+    print(json.dumps(line))
+    return 0 if (check is None or check["ok"]) else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

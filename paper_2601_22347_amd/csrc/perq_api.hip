@@ -36,11 +36,13 @@ bool is_pow2(int32_t v) { return v > 0 && (v & (v - 1)) == 0; }
 // Shared checks of the apply entry points; fills the kernel parameters.
 perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, const int32_t* perm,
                           int32_t b, ApplyParams* p) {
-    if (x == nullptr) return PERQ_ERR_INVALID_ARG;
     if (T < 0 || d <= 0 || ldx < d) return PERQ_ERR_INVALID_ARG;
     if (!is_pow2(b) || b < 16 || b > d || d % b != 0) return PERQ_ERR_INVALID_ARG;
     if (d % 32 != 0) return PERQ_ERR_INVALID_ARG;
     if (d > PERQ_MAX_D) return PERQ_ERR_UNSUPPORTED;
+    p->T = T;
+    if (T == 0) return PERQ_OK;               // nothing to read or write: pointers may be null
+    if (x == nullptr) return PERQ_ERR_INVALID_ARG;
     if (ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     if (perm != nullptr && (reinterpret_cast<uintptr_t>(perm) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     int log2b = 0;
@@ -86,10 +88,12 @@ extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, 
                                                         perq_fmt_t fmt, perq_algo_t algo, uint8_t* codes,
                                                         void* scales, void* hip_stream) {
     perq::ApplyParams p;
-    if (codes == nullptr || scales == nullptr) return PERQ_ERR_INVALID_ARG;
     if (fmt != PERQ_FMT_INT4_SYM_TOKEN && fmt != PERQ_FMT_MXFP4) return PERQ_ERR_INVALID_ARG;
+    if (algo != PERQ_ALGO_AUTO && algo != PERQ_ALGO_BUTTERFLY && algo != PERQ_ALGO_MFMA)
+        return PERQ_ERR_INVALID_ARG;
     const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
-    if (st != PERQ_OK) return st;
+    if (st != PERQ_OK || p.T == 0) return st;
+    if (codes == nullptr || scales == nullptr) return PERQ_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(codes) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     if (fmt == PERQ_FMT_INT4_SYM_TOKEN && (reinterpret_cast<uintptr_t>(scales) & 3u) != 0)
         return PERQ_ERR_UNSUPPORTED;
@@ -110,9 +114,11 @@ extern "C" perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t
                                                  const int32_t* perm, int32_t b, perq_algo_t algo, float* y,
                                                  void* hip_stream) {
     perq::ApplyParams p;
-    if (y == nullptr) return PERQ_ERR_INVALID_ARG;
+    if (algo != PERQ_ALGO_AUTO && algo != PERQ_ALGO_BUTTERFLY && algo != PERQ_ALGO_MFMA)
+        return PERQ_ERR_INVALID_ARG;
     const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
-    if (st != PERQ_OK) return st;
+    if (st != PERQ_OK || p.T == 0) return st;
+    if (y == nullptr) return PERQ_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(y) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     p.y = y;
     return perq::dispatch(p, perq::OUT_F32, algo, static_cast<hipStream_t>(hip_stream));

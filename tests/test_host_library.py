@@ -91,7 +91,10 @@ def test_apply_argument_checks_happen_before_any_launch(lib):
     assert q(T=0) == binding.PERQ_OK
     assert lib.perq_permute_rotate_quant_algo(fake, 4, 256, 256, None, 16, 0, 9, fake, fake, None) == INV
     assert lib.perq_permute_rotate_f32(fake, 4, 256, 256, None, 16, 0, None, None) == INV
-    assert lib.perq_permute_rotate_f32(fake, 0, 256, 256, None, 16, 0, fake, None) == binding.PERQ_OK
+    assert lib.perq_permute_rotate_f32(fake, 4, 256, 256, None, 16, 5, fake, None) == INV
+    assert lib.perq_permute_rotate_f32(None, 0, 256, 256, None, 16, 0, None, None) == binding.PERQ_OK
+    assert q(x=None, T=0, codes=None, scales=None) == binding.PERQ_OK
+    assert q(x=None, T=0, b=24) == INV            # shape errors are still reported for T == 0
     # colabs
     assert lib.perq_colabs_mean(None, 4, 256, 256, fake, fake, 1 << 20, None) == INV
     assert lib.perq_colabs_mean(fake, 0, 256, 256, fake, fake, 1 << 20, None) == INV
