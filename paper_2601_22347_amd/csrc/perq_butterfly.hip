@@ -36,8 +36,8 @@ struct BflyGeom {
     uint32_t red_off;    // byte offset of the reduction scratch in LDS
 };
 
-template <int OUT, bool PERM>
-__global__ void __launch_bounds__(1024)
+template <int OUT, bool PERM, int MAXT>
+__global__ void __launch_bounds__(MAXT)
 butterfly_kernel(ApplyParams p, BflyGeom g) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x;
@@ -45,6 +45,7 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
     const int r = tid / g.nt < g.rows ? tid / g.nt : g.rows - 1;   // row slot of this thread
     const int t = g.rows > 1 ? tid % g.nt : tid;                   // lane index inside the row
     const bool active = t < g.nt && tid < g.rows * g.nt;
+    const int ta = active ? t : 0;
     const int d = p.d, b = p.b;
 
     // -1 / +1 per butterfly distance, in lane units
@@ -57,8 +58,7 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
     if constexpr (PERM) {
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            int4 e4 = make_int4(0, 0, 0, 0);
-            if (active) e4 = *reinterpret_cast<const int4*>(p.perm + 32 * t + 4 * q);
+            const int4 e4 = *reinterpret_cast<const int4*>(p.perm + 32 * (active ? t : 0) + 4 * q);
             const int e[4] = {e4.x, e4.y, e4.z, e4.w};
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -77,7 +77,7 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
         for (int k = 0; k < 4; ++k) {
             buf[k] = make_uint4(0, 0, 0, 0);
             if (active && row < p.T)
-                buf[k] = *reinterpret_cast<const uint4*>(p.x + row * p.ldx + (int64_t)(t + k * g.nt) * 8);
+                buf[k] = load_stream16(p.x + row * p.ldx + (int64_t)(t + k * g.nt) * 8);
         }
     };
 
@@ -98,18 +98,18 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
         if (grp + gridDim.x < ngroups) load_group(grp + gridDim.x, stage);   // prefetch next rows
 
         // ---- this lane's 32 permuted elements -> fp32 --------------------------------------
+        // (lanes past the end of the row read slot 0 and are never stored)
         float v[32];
         if constexpr (PERM) {
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
-                const uint32_t h = active ? *reinterpret_cast<const uint16_t*>(my_row + src_addr[i]) : 0u;
+                const uint32_t h = *reinterpret_cast<const uint16_t*>(my_row + src_addr[i]);
                 v[i] = __uint_as_float(h << 16);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint4 w = make_uint4(0, 0, 0, 0);
-                if (active) w = *reinterpret_cast<const uint4*>(my_row + (granule_slot((uint32_t)(4 * t + j)) << 4));
+                const uint4 w = *reinterpret_cast<const uint4*>(my_row + (granule_slot((uint32_t)(4 * ta + j)) << 4));
                 const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -174,12 +174,12 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
             if (live) {
                 const uint4 c = make_uint4(mxfp4_pack8(v, scale), mxfp4_pack8(v + 8, scale),
                                            mxfp4_pack8(v + 16, scale), mxfp4_pack8(v + 24, scale));
-                *reinterpret_cast<uint4*>(p.codes + row * (int64_t)(d >> 1) + 16 * t) = c;
+                store_stream16(p.codes + row * (int64_t)(d >> 1) + 16 * t, c);
                 static_cast<uint8_t*>(p.scales)[row * (int64_t)(d >> 5) + t] = (uint8_t)E;
             }
         } else {
             // per-token maximum: lanes of the row inside this wave, then the row's waves
-            float m = absmax(v);
+            float m = active ? absmax(v) : 0.0f;
             if (g.nt > 1) m = fmaxf(m, lane_xor<1>(m));
             if (g.nt > 2) m = fmaxf(m, lane_xor<2>(m));
             if (g.nt > 4) m = fmaxf(m, lane_xor<4>(m));
@@ -199,7 +199,7 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
             if (live) {
                 const uint4 c = make_uint4(int4_pack8(v, inv), int4_pack8(v + 8, inv),
                                            int4_pack8(v + 16, inv), int4_pack8(v + 24, inv));
-                *reinterpret_cast<uint4*>(p.codes + row * (int64_t)(d >> 1) + 16 * t) = c;
+                store_stream16(p.codes + row * (int64_t)(d >> 1) + 16 * t, c);
                 if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m * p.inv_7sqrt_b);
             }
         }
@@ -227,7 +227,11 @@ hipError_t launch_butterfly_out(const ApplyParams& p, hipStream_t stream) {
     g.red_off = stage_bytes > xchg_bytes ? stage_bytes : xchg_bytes;
     const uint32_t lds_bytes = g.red_off + 64u * sizeof(float);
 
-    auto kern = p.perm ? butterfly_kernel<OUT, true> : butterfly_kernel<OUT, false>;
+    // register budget follows the workgroup size: 256 threads for rows up to 8192, 512 up to
+    // 16384, 1024 beyond
+    auto kern = threads <= 256   ? (p.perm ? butterfly_kernel<OUT, true, 256> : butterfly_kernel<OUT, false, 256>)
+                : threads <= 512 ? (p.perm ? butterfly_kernel<OUT, true, 512> : butterfly_kernel<OUT, false, 512>)
+                                 : (p.perm ? butterfly_kernel<OUT, true, 1024> : butterfly_kernel<OUT, false, 1024>);
     if (lds_bytes > 64u * 1024u) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
