@@ -73,7 +73,9 @@ perq_status_t dispatch(const ApplyParams& p, int out_kind, perq_algo_t algo, hip
             e = launch_butterfly(p, out_kind, stream);
             break;
         case PERQ_ALGO_MFMA:
-            return PERQ_ERR_UNSUPPORTED;
+            if (!mfma_supports(p)) return PERQ_ERR_UNSUPPORTED;
+            e = launch_mfma(p, out_kind, stream);
+            break;
         default:
             return PERQ_ERR_INVALID_ARG;
     }

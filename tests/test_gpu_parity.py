@@ -12,7 +12,12 @@ from paper_2601_22347_amd import binding, synth  # noqa: E402
 
 pytestmark = pytest.mark.gpu
 
-ALGOS = ["butterfly", "auto"]
+ALGOS = ["butterfly", "mfma", "auto"]
+
+
+def mfma_covers(d, b):
+    """Shapes the matrix-core kernel accepts; everything else must come back UNSUPPORTED."""
+    return d % 512 == 0 and b <= 4096
 
 
 def _torch():
@@ -40,6 +45,11 @@ def run_gpu(x_bits, perm, b, fmt, algo="auto", want_y=True, ldx=None):
 def assert_parity(x_bits, perm, b, fmt, algo="auto", rotate=None, ldx=None, label=""):
     print(f"[case] {label} T={x_bits.shape[0]} d={x_bits.shape[1]} b={b} fmt={fmt} algo={algo} "
           f"perm={'yes' if perm is not None else 'no'}", flush=True)
+    if algo == "mfma" and not mfma_covers(x_bits.shape[1], b):
+        with pytest.raises(binding.PerqError) as ei:
+            run_gpu(x_bits, perm, b, fmt, algo=algo, ldx=ldx)
+        assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED
+        return None
     codes, scales, y = run_gpu(x_bits, perm, b, fmt, algo=algo, ldx=ldx)
     rep = parity.compare_apply(x_bits, perm, b, fmt, codes, scales, y, rotate=rotate)
     print("       ", rep.summary(), flush=True)
@@ -73,6 +83,8 @@ def test_structured_rows(d, b, algo):
     rows += [base, -base, base * 2.0 ** 10, base * 2.0 ** -10]        # sign flip, power-of-two scaling
     rows.append(np.where(np.arange(d) % 2 == 0, 1.0, -1.0))           # alternating signs
     x = synth.f64_to_bf16_bits(np.array(rows))
+    if algo == "mfma" and not mfma_covers(d, b):
+        pytest.skip("shape not covered by the matrix-core kernel")
     for fmt in ("int4", "mxfp4"):
         codes, scales, y = run_gpu(x, None, b, fmt, algo)
         rep = parity.compare_apply(x, None, b, fmt, codes, scales, y)
@@ -133,6 +145,8 @@ def test_row_stride_and_special_perms(algo):
     assert_parity(x, np.arange(d, dtype=np.int32)[::-1].copy(), 64, "mxfp4", algo, ldx=d + 8, label="reverse")
     # a permutation followed by its inverse is the identity path on the un-permuted data
     perm = rng.permutation(d).astype(np.int32)
+    if algo == "mfma" and not mfma_covers(d, 128):
+        return
     xp = x[:, perm]
     c1, s1, y1 = run_gpu(xp, np.argsort(perm).astype(np.int32), 128, "int4", algo)
     c2, s2, y2 = run_gpu(x, None, 128, "int4", algo)
