@@ -128,16 +128,17 @@ __device__ __forceinline__ float absmax(const float (&v)[N]) {
 }
 
 // ---- INT4: 8 values -> one dword of two's-complement nibbles, element 0 in bits 3:0 ------
-// fma(y, inv, 1.5*2^23) rounds y*inv to an integer with ties to even in one step; the low
-// mantissa bits of the sum are the integer in two's complement.
+// fma(y, inv, 1.5*2^23 + 8) rounds y*inv to an integer c (ties to even) in one step and leaves
+// the word 0x4B400000 + (c + 8): the low nibble is c in offset binary (1..15, so nothing
+// carries out of it) and every higher bit is the same constant for all elements.  Eight such
+// words are merged with shift-adds; the constant parts add up to kInt4Bias, which is removed
+// once, and flipping bit 3 of every nibble turns offset binary into two's complement.
+constexpr uint32_t kInt4Bias = (uint32_t)(0x4B400000ull * 0x11111111ull);
 __device__ __forceinline__ uint32_t int4_pack8(const float* v, float inv) {
-    uint32_t w = 0;
+    uint32_t acc = __float_as_uint(__builtin_fmaf(v[7], inv, 12582920.0f));
 #pragma unroll
-    for (int i = 7; i >= 0; --i) {
-        const uint32_t t = __float_as_uint(__builtin_fmaf(v[i], inv, 12582912.0f));
-        w = (w << 4) | (t & 0xFu);
-    }
-    return w;
+    for (int i = 6; i >= 0; --i) acc = (acc << 4) + __float_as_uint(__builtin_fmaf(v[i], inv, 12582920.0f));
+    return (acc - kInt4Bias) ^ 0x88888888u;
 }
 
 // ---- MXFP4: 8 values -> one dword of e2m1 nibbles ----------------------------------------

@@ -11,8 +11,10 @@
 // so column c of D is the rotated sub-block.  sigma is chosen so that the 16 accumulators of
 // lane (c,h) are the contiguous outputs 16h .. 16h+15 of the sub-block.  bf16 x (+-1) products
 // are exact and accumulate in fp32.
-//     b = 64, 128     : butterflies between the lane's four accumulator tiles (registers only)
-//     b = 256 .. 4096 : butterflies across lanes on c (DPP / swizzle / permlane swap)
+//     b = 64, 128     : the product is widened to H_64 / H_128: accumulator tile q sums the
+//                       +-H_32 products of the 2 / 4 sub-blocks of its block (more MFMAs, no VALU)
+//     b = 256 .. 4096 : H_128 as above, then butterflies across lanes on c (DPP / swizzle /
+//                       permlane swap)
 //
 // Data movement.  The raw bf16 rows go global -> LDS with 16-byte direct-to-LDS loads (no
 // registers, no ds_write), streaming policy; they are the only HBM reads.  The B operands are
@@ -22,6 +24,8 @@
 // over all banks; the swizzle is applied on the global side of the direct-to-LDS load.
 #include "perq_device.h"
 #include "perq_launch.h"
+
+#include <type_traits>
 
 namespace perq {
 namespace {
@@ -38,6 +42,7 @@ struct MfmaGeom {
     int nload;           // direct-to-LDS load instructions per lane per iteration
     uint32_t row_bytes;  // d * 2
     uint32_t red_off;    // byte offset of the cross-wave reduction scratch
+    uint32_t out_off;    // byte offset of the per-wave output staging (2 KiB per wave)
 };
 
 // granule -> slot inside a row (an involution: bits 4..6 select the xor pattern for bits 0..2)
@@ -48,10 +53,19 @@ __device__ __forceinline__ uint32_t granule_slot(uint32_t g) {
 
 __device__ __forceinline__ uint32_t popc_parity(uint32_t v) { return __builtin_popcount(v) & 1u; }
 
-template <int OUT, bool PERM, int NWAVES>
-__global__ void __launch_bounds__(NWAVES * 64)
+// STAGES = number of +-1 butterfly stages after the matrix product: log2(b) - 5, 0 for b <= 32.
+// A template parameter so that the accumulators stay in registers along one straight path.
+template <int OUT, bool PERM, int NWAVES, int STAGES>
+// (two 4-wave workgroups fit a CU's LDS, so the register budget is that of 2 waves per SIMD)
+__global__ void __launch_bounds__(NWAVES * 64, NWAVES == 4 ? 2 : 1)
 mfma_kernel(ApplyParams p, MfmaGeom g) {
     extern __shared__ __align__(16) unsigned char lds[];
+    // Two staging buffers when a row group fits 32 KiB (4 waves): the loads of the next group are
+    // in flight during the whole of the current one.  The buffer is selected by a compile-time
+    // offset on the LDS instructions (loop unrolled by two).  8-wave groups use one buffer.
+    constexpr bool kDouble = NWAVES == 4;
+    constexpr uint32_t kBufStride = 32768;
+
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -61,10 +75,11 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     const int tile_base = (wave % g.tiles_per_row) * kTile;
     int tile_len = d - tile_base;
     tile_len = tile_len < 0 ? 0 : (tile_len > kTile ? kTile : tile_len);
-    const bool full_tile = tile_len == kTile;
+    // one tile per row: every wave stages and consumes its own row, no workgroup barrier needed
+    const bool wave_local = g.tiles_per_row == 1;
 
     // ---- A operand: rows sigma(i) of the +-1 matrix, two K steps of 16 ---------------------
-    bf16x8_t afrag[2];
+    bf16x8_t afrag[2], afrag_neg[2];
     {
         const uint32_t i = (uint32_t)lane & 31u;
         const uint32_t n = 16u * ((i >> 2) & 1u) + 4u * (i >> 3) + (i & 3u);
@@ -80,11 +95,16 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 if (e & 1) w[e >> 1] |= bits << 16; else w[e >> 1] = bits;
             }
             afrag[kt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+            afrag_neg[kt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0] ^ 0x80008000u, w[1] ^ 0x80008000u,
+                                                                   w[2] ^ 0x80008000u, w[3] ^ 0x80008000u));
         }
     }
 
     // ---- LDS addresses of this lane's operands (fixed for the whole launch) ----------------
     // PERM: one address per element; identity: one per 16-byte fragment.
+    // Sub-blocks past the end of a ragged last tile read a 16-byte slot that is kept at zero
+    // (the last 16 bytes of each staging buffer; a ragged row never fills its buffer).
+    constexpr uint32_t kZeroSlot = (kDouble ? kBufStride : 65536u) - 16u;
     uint32_t src[PERM ? 64 : 8];
     bool qvalid[kQ];
 #pragma unroll
@@ -105,9 +125,10 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     src[(q * 2 + kt) * 8 + e] =
-                        (uint32_t)rr * g.row_bytes + ((granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1));
+                        qvalid[q] ? (uint32_t)rr * g.row_bytes + ((granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1))
+                                  : kZeroSlot;
             } else {
-                src[q * 2 + kt] = (uint32_t)rr * g.row_bytes + (qvalid[q] ? (granule_slot(pos >> 3) << 4) : 0u);
+                src[q * 2 + kt] = qvalid[q] ? (uint32_t)rr * g.row_bytes + (granule_slot(pos >> 3) << 4) : kZeroSlot;
             }
         }
     }
@@ -120,28 +141,76 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
 
-    // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.
-    auto issue_loads = [&](int64_t grp) {
-        for (int k = 0; k < g.nload; ++k) {
-            const uint32_t s0 = (uint32_t)(k * NWAVES + wave) * 64u;         // first slot, wave-uniform
-            const uint32_t rslot = s0 / gpr;
-            const int64_t row = grp * g.rows + rslot;
-            if (rslot < (uint32_t)g.rows && row < p.T) {
-                const uint32_t gs = s0 - rslot * gpr + (uint32_t)lane;          // slot inside the row
-                const uint16_t* src_g = p.x + row * p.ldx + (int64_t)granule_slot(gs) * 8;
-                __builtin_amdgcn_global_load_lds(src_g, lds + (size_t)s0 * 16u, 16, 0, 2 /* nt */);
+    // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  In wave-local
+    // mode wave w fills row slot w, otherwise the instructions are dealt round-robin to the waves.
+    // Everything but the row number is fixed for the launch: per instruction k a per-lane byte
+    // offset inside the row (the swizzle lives here) and a uniform LDS offset and row slot.
+    constexpr int kMaxLoad = 8;
+    uint32_t ld_lane_off[kMaxLoad];
+    uint32_t ld_lds[kMaxLoad];
+    int ld_rslot[kMaxLoad];
+#pragma unroll
+    for (int k = 0; k < kMaxLoad; ++k) {
+        uint32_t s0, rslot;
+        bool ok;
+        if (wave_local) {
+            rslot = (uint32_t)wave;
+            s0 = rslot * gpr + (uint32_t)k * 64u;
+            ok = (uint32_t)k * 64u < gpr;
+        } else {
+            s0 = (uint32_t)(k * NWAVES + wave) * 64u;
+            rslot = s0 / gpr;
+            ok = rslot < (uint32_t)g.rows;
+        }
+        ok = ok && k < g.nload;
+        ld_rslot[k] = ok ? (int)rslot : -1;
+        ld_lds[k] = s0 * 16u;
+        ld_lane_off[k] = granule_slot(s0 - rslot * gpr + (uint32_t)lane) * 16u;
+    }
+    const unsigned char* xbytes = reinterpret_cast<const unsigned char*>(p.x);
+    const int64_t ldx_bytes = p.ldx * 2;
+    auto issue_loads = [&](int64_t grp, uint32_t buf_off) -> int {
+        int issued = 0;
+        const int64_t row0 = grp * g.rows;
+#pragma unroll
+        for (int k = 0; k < kMaxLoad; ++k) {
+            const int64_t row = row0 + ld_rslot[k];
+            if (ld_rslot[k] >= 0 && row < p.T) {
+                __builtin_amdgcn_global_load_lds(xbytes + row * ldx_bytes + ld_lane_off[k],
+                                                 lds + buf_off + ld_lds[k], 16, 0, 2 /* nt */);
+                ++issued;
             }
         }
+        return issued;
     };
 
-    if ((int64_t)blockIdx.x < ngroups) issue_loads(blockIdx.x);
+    // Wait until at most n of this wave's vector-memory operations are outstanding.  Loads
+    // complete in issue order, so once no more than the n loads issued after a group remain,
+    // that group has landed whatever the stores in between have done.
+    auto wait_vm_le = [&](int n) {
+        switch (n) {
+            case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+            case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+            case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+            case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+            case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+            case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+            case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+            case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+            default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+        }
+    };
+    int n_behind = 0;      // loads of the group after the current one, already in flight
 
-    for (int64_t grp = blockIdx.x; grp < ngroups; grp += gridDim.x) {
+    // ---- one row group out of staging buffer BUF -------------------------------------------
+    auto do_group = [&](int64_t grp, auto buf_const) {
+        constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
         const int64_t row = grp * g.rows + rr;
-        const bool row_live = rr < g.rows && row < p.T;
+        const bool row_live = row < p.T;
+        const bool more = grp + gridDim.x < ngroups;
 
-        __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): this wave's direct-to-LDS loads have landed
-        __syncthreads();
+        wait_vm_le(kDouble ? n_behind : 0);      // this wave's direct-to-LDS loads of the group have landed
+        if (!wave_local) __syncthreads();
 
         // ---- B operands out of LDS ----------------------------------------------------------
         uint4 bfrag[kQ][2];
@@ -153,55 +222,52 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     uint32_t w[4];
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
-                        const uint32_t lo = *reinterpret_cast<const uint16_t*>(lds + src[(q * 2 + kt) * 8 + e]);
-                        const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds + src[(q * 2 + kt) * 8 + e + 1]);
+                        const uint32_t lo = *reinterpret_cast<const uint16_t*>(lds + kOff + src[(q * 2 + kt) * 8 + e]);
+                        const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds + kOff + src[(q * 2 + kt) * 8 + e + 1]);
                         w[e >> 1] = lo | (hi << 16);
                     }
                     bfrag[q][kt] = make_uint4(w[0], w[1], w[2], w[3]);
                 } else {
-                    bfrag[q][kt] = *reinterpret_cast<const uint4*>(lds + src[q * 2 + kt]);
+                    bfrag[q][kt] = *reinterpret_cast<const uint4*>(lds + kOff + src[q * 2 + kt]);
                 }
             }
         }
-        if (!full_tile) {
-#pragma unroll
-            for (int q = 0; q < kQ; ++q)
-                if (!qvalid[q]) bfrag[q][0] = bfrag[q][1] = make_uint4(0, 0, 0, 0);
+        // The operands are in registers: refill this buffer right away.  With two buffers the
+        // group after next goes here, so two groups of loads are in flight during the arithmetic.
+        if (!wave_local) __syncthreads();
+        if constexpr (kDouble) {
+            n_behind = grp + 2 * (int64_t)gridDim.x < ngroups ? issue_loads(grp + 2 * (int64_t)gridDim.x, kOff) : 0;
+        } else {
+            if (more) issue_loads(grp + gridDim.x, 0u);
         }
-        __syncthreads();                          // every wave has its operands: LDS may be refilled
-        if (grp + gridDim.x < ngroups) issue_loads(grp + gridDim.x);
 
-        // ---- low five bits on the matrix cores ------------------------------------------------
+        // ---- H_32 (b <= 32), H_64 or H_128 on the matrix cores ----------------------------------
+        // accumulator tile qo = sum over the sub-blocks qi of its block of (+-H_32) * X_qi, the sign
+        // being entry (qo, qi) of the Sylvester matrix of order kDense
+        constexpr int kDense = STAGES == 0 ? 1 : (STAGES == 1 ? 2 : 4);
         float v[64];
 #pragma unroll
-        for (int q = 0; q < kQ; ++q) {
+        for (int qo = 0; qo < kQ; ++qo) {
             f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[0], __builtin_bit_cast(bf16x8_t, bfrag[q][0]), acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[1], __builtin_bit_cast(bf16x8_t, bfrag[q][1]), acc, 0, 0, 0);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) v[q * 16 + r] = acc[r];
+            for (int j = 0; j < kDense; ++j) {
+                const int qi = (qo & ~(kDense - 1)) | j;
+                const bool neg = __builtin_popcount(qo & qi & (kDense - 1)) & 1;
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(neg ? afrag_neg[kt] : afrag[kt],
+                                                                  __builtin_bit_cast(bf16x8_t, bfrag[qi][kt]), acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) v[qo * 16 + r] = acc[r];
         }
 
-        // ---- remaining butterflies --------------------------------------------------------------
-        if (b >= 64) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float a0 = v[r], a1 = v[16 + r], a2 = v[32 + r], a3 = v[48 + r];
-                v[r] = a0 + a1; v[16 + r] = a0 - a1; v[32 + r] = a2 + a3; v[48 + r] = a2 - a3;
-            }
-        }
-        if (b >= 128) {
-#pragma unroll
-            for (int r = 0; r < 32; ++r) {
-                const float a0 = v[r], a2 = v[32 + r];
-                v[r] = a0 + a2; v[32 + r] = a0 - a2;
-            }
-        }
-        if (b >= 256) lane_stage<1>(v, sgn[0]);
-        if (b >= 512) lane_stage<2>(v, sgn[1]);
-        if (b >= 1024) lane_stage<4>(v, sgn[2]);
-        if (b >= 2048) lane_stage<8>(v, sgn[3]);
-        if (b >= 4096) lane_stage<16>(v, sgn[4]);
+        // ---- butterflies across lanes for b >= 256 ----------------------------------------------
+        if constexpr (STAGES >= 3) lane_stage<1>(v, sgn[0]);
+        if constexpr (STAGES >= 4) lane_stage<2>(v, sgn[1]);
+        if constexpr (STAGES >= 5) lane_stage<4>(v, sgn[2]);
+        if constexpr (STAGES >= 6) lane_stage<8>(v, sgn[3]);
+        if constexpr (STAGES >= 7) lane_stage<16>(v, sgn[4]);
 
         // ---- epilogue: lane (c,h) holds outputs 16h..16h+15 of sub-blocks 4c..4c+3 -------------
         if constexpr (OUT == OUT_F32) {
@@ -244,8 +310,10 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 m = fmaxf(m, lane_xor<8>(m));
                 m = fmaxf(m, lane_xor<16>(m));
                 m = fmaxf(m, lane_xor<32>(m));
-                if (g.tiles_per_row > 1) {
-                    float* red = reinterpret_cast<float*>(lds + g.red_off);
+                if (!wave_local) {
+                    // row maximum across the row's waves; scratch alternates with the group parity so
+                    // that one barrier per group is enough
+                    float* red = reinterpret_cast<float*>(lds + g.red_off) + decltype(buf_const)::value * 16;
                     if (lane == 0) red[wave] = m;
                     __syncthreads();
                     const int w0 = rr * g.tiles_per_row;
@@ -271,11 +339,22 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     out[q][2 + j] = s[1];
                 }
             }
+            // The wave's 2 KiB of codes take one trip through LDS so that each store instruction
+            // writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of 16-byte
+            // pieces at a 32-byte pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
+            unsigned char* ob = lds + g.out_off + (uint32_t)wave * 2048u;
+            {
+                const uint32_t s0 = (uint32_t)(c * kQ + 2 * h), s1 = s0 + 1u;
+                *reinterpret_cast<uint4*>(ob + ((s0 ^ ((s0 >> 3) & 7u)) << 4)) = make_uint4(out[0][0], out[0][1], out[0][2], out[0][3]);
+                *reinterpret_cast<uint4*>(ob + ((s1 ^ ((s1 >> 3) & 7u)) << 4)) = make_uint4(out[1][0], out[1][1], out[1][2], out[1][3]);
+            }
+            const uint32_t r0 = (uint32_t)lane, r1 = 64u + (uint32_t)lane;
+            const uint4 o0 = *reinterpret_cast<const uint4*>(ob + ((r0 ^ ((r0 >> 3) & 7u)) << 4));
+            const uint4 o1 = *reinterpret_cast<const uint4*>(ob + ((r1 ^ ((r1 >> 3) & 7u)) << 4));
             if (row_live) {
-                uint8_t* crow = p.codes + row * (int64_t)(d >> 1) + ((tile_base + (c * kQ + 2 * h) * 32) >> 1);
-                const bool ok0 = (c * kQ + 2 * h) * 32 < tile_len, ok1 = (c * kQ + 2 * h + 1) * 32 < tile_len;
-                if (ok0) store_stream16(crow, make_uint4(out[0][0], out[0][1], out[0][2], out[0][3]));
-                if (ok1) store_stream16(crow + 16, make_uint4(out[1][0], out[1][1], out[1][2], out[1][3]));
+                uint8_t* crow = p.codes + row * (int64_t)(d >> 1) + (tile_base >> 1) + lane * 16;
+                if (lane * 32 < tile_len) store_stream16(crow, o0);
+                if (2048 + lane * 32 < tile_len) store_stream16(crow + 1024, o1);
                 if constexpr (OUT == OUT_MXFP4) {
                     if (h == 0 && qvalid[0])
                         *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.scales) + row * (int64_t)(d >> 5) +
@@ -286,11 +365,25 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 }
             }
         }
+    };
+
+    if (tid < 4) {
+        *reinterpret_cast<uint32_t*>(lds + kZeroSlot + 4 * tid) = 0u;
+        if constexpr (kDouble) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
+    }
+    __syncthreads();
+    if ((int64_t)blockIdx.x < ngroups) issue_loads(blockIdx.x, 0u);
+    if constexpr (kDouble) {
+        if ((int64_t)blockIdx.x + gridDim.x < ngroups) n_behind = issue_loads((int64_t)blockIdx.x + gridDim.x, kBufStride);
+    }
+    for (int64_t grp = blockIdx.x; grp < ngroups; grp += 2 * (int64_t)gridDim.x) {
+        do_group(grp, std::integral_constant<uint32_t, 0>{});
+        if (grp + gridDim.x < ngroups) do_group(grp + gridDim.x, std::integral_constant<uint32_t, 1>{});
     }
 }
 
-template <int OUT, int NWAVES>
-hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
+template <int OUT, int NWAVES, int STAGES>
+hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
     MfmaGeom g;
     const int tiles = (p.d + kTile - 1) / kTile;
     g.tiles_per_row = 1;
@@ -298,12 +391,14 @@ hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
     g.rows = NWAVES / g.tiles_per_row;
     g.row_bytes = (uint32_t)p.d * 2u;
     const uint32_t stage_bytes = (uint32_t)g.rows * g.row_bytes;
-    const uint32_t slots = stage_bytes / 16u;
-    g.nload = (int)((slots + NWAVES * 64u - 1u) / (NWAVES * 64u));
-    g.red_off = stage_bytes;
-    const uint32_t lds_bytes = stage_bytes + 64u * sizeof(float);
+    const uint32_t gpr = (uint32_t)p.d / 8u;
+    g.nload = g.tiles_per_row == 1 ? (int)(gpr / 64u)
+                                   : (int)((stage_bytes / 16u + NWAVES * 64u - 1u) / (NWAVES * 64u));
+    g.red_off = 65536u;                                 // staging (incl. the zero slot) ends here
+    g.out_off = g.red_off + 32u * sizeof(float);
+    const uint32_t lds_bytes = g.out_off + NWAVES * 2048u;
 
-    auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES> : mfma_kernel<OUT, false, NWAVES>;
+    auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES> : mfma_kernel<OUT, false, NWAVES, STAGES>;
     if (lds_bytes > 64u * 1024u) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -318,6 +413,20 @@ hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
     if (grid > ngroups) grid = ngroups;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NWAVES * 64), lds_bytes, stream, p, g);
     return hipGetLastError();
+}
+
+template <int OUT, int NWAVES>
+hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
+    switch (p.log2b <= 5 ? 0 : p.log2b - 5) {
+        case 0: return launch_mfma_st<OUT, NWAVES, 0>(p, stream);
+        case 1: return launch_mfma_st<OUT, NWAVES, 1>(p, stream);
+        case 2: return launch_mfma_st<OUT, NWAVES, 2>(p, stream);
+        case 3: return launch_mfma_st<OUT, NWAVES, 3>(p, stream);
+        case 4: return launch_mfma_st<OUT, NWAVES, 4>(p, stream);
+        case 5: return launch_mfma_st<OUT, NWAVES, 5>(p, stream);
+        case 6: return launch_mfma_st<OUT, NWAVES, 6>(p, stream);
+        default: return launch_mfma_st<OUT, NWAVES, 7>(p, stream);
+    }
 }
 
 }  // namespace
