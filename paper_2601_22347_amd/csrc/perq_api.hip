@@ -69,6 +69,11 @@ perq_status_t dispatch(const ApplyParams& p, int out_kind, perq_algo_t algo, hip
     hipError_t e;
     switch (algo) {
         case PERQ_ALGO_AUTO:
+            // The matrix-core kernel wins wherever its 4096-wide wave tiles are filled (measured:
+            // rocprofv3 summaries under profiles/); narrow rows and b > 4096 take the butterflies.
+            e = (mfma_supports(p) && p.d >= 4096) ? launch_mfma(p, out_kind, stream)
+                                                  : launch_butterfly(p, out_kind, stream);
+            break;
         case PERQ_ALGO_BUTTERFLY:
             e = launch_butterfly(p, out_kind, stream);
             break;

@@ -58,14 +58,30 @@ colabs_partial_kernel(const uint16_t* __restrict__ x, int64_t M, int32_t d, int6
     out[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
 }
 
+// Pass 2: 32 columns per workgroup, 8 lanes per column.  Lane j of a column adds slices
+// j, j+8, ... in double; the 8 sub-sums are then added in lane order.  Fixed order throughout.
+constexpr int kFinishCols = 32;
+constexpr int kFinishWays = kThreads / kFinishCols;   // 8
+
 __global__ void __launch_bounds__(kThreads)
 colabs_finish_kernel(const float* __restrict__ part, int slices, int32_t d, float m_rows,
                      float* __restrict__ out) {
-    const int col = blockIdx.x * kThreads + threadIdx.x;
-    if (col >= d) return;
-    double s = 0.0;   // the slice partials are combined in double: only pass 1 rounds in fp32
-    for (int k = 0; k < slices; ++k) s += (double)part[(int64_t)k * d + col];
-    out[col] = (float)(s / (double)m_rows);
+    __shared__ double red[kFinishWays][kFinishCols];
+    const int cl = threadIdx.x % kFinishCols, way = threadIdx.x / kFinishCols;
+    const int col = blockIdx.x * kFinishCols + cl;
+    double s = 0.0;
+    if (col < d) {
+#pragma unroll 8
+        for (int k = way; k < slices; k += kFinishWays) s += (double)part[(int64_t)k * d + col];
+    }
+    red[way][cl] = s;
+    __syncthreads();
+    if (way == 0 && col < d) {
+        double t = red[0][cl];
+#pragma unroll
+        for (int j = 1; j < kFinishWays; ++j) t += red[j][cl];
+        out[col] = (float)(t / (double)m_rows);
+    }
 }
 
 }  // namespace
@@ -94,7 +110,7 @@ extern "C" perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int
     hipLaunchKernelGGL(perq::colabs_partial_kernel, dim3(pl.col_tiles, pl.slices), dim3(perq::kThreads),
                        0, stream, x_bf16, M, d, ldx, pl.rows_per_slice, part);
     if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(perq::colabs_finish_kernel, dim3((d + perq::kThreads - 1) / perq::kThreads),
+    hipLaunchKernelGGL(perq::colabs_finish_kernel, dim3((d + perq::kFinishCols - 1) / perq::kFinishCols),
                        dim3(perq::kThreads), 0, stream, part, pl.slices, d, (float)M,
                        out_mean);
     if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
