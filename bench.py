@@ -44,23 +44,6 @@ def algorithmic_bytes(T: int, d: int, fmt: str) -> int:
     return T * d * 2 + T * d // 2 + scales
 
 
-def gen_rows_parallel(wl, r0, r1, threads=8):
-    """Apply-time rows [r0, r1) generated chunk by chunk on a few threads (NumPy releases the GIL)."""
-    from concurrent.futures import ThreadPoolExecutor
-    from paper_2601_22347_amd import synth
-    edges = list(range(r0 - r0 % synth.CHUNK, r1, synth.CHUNK))
-    spans = [(max(e, r0), min(e + synth.CHUNK, r1)) for e in edges]
-    out = np.empty((r1 - r0, wl.d), dtype=np.uint16)
-
-    def work(span):
-        a, b_ = span
-        out[a - r0:b_ - r0] = wl.apply_rows(a, b_)
-
-    with ThreadPoolExecutor(max_workers=threads) as ex:
-        list(ex.map(work, spans))
-    return out
-
-
 def read_traffic(name: str):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
@@ -102,7 +85,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
 
     t0 = time.perf_counter()
-    x_bits = gen_rows_parallel(wl, 0, T)
+    x_bits = wl.apply_rows_parallel()
     gen_s = time.perf_counter() - t0
 
     # ---- calibration: colabs mean on the device, greedy on the host (once, untimed region) ----

@@ -81,6 +81,22 @@ class Workload:
         r1 = self.T if r1 is None else r1
         return self._rows(self.data_seed, r0, r1, self.T, massive=True)
 
+    def apply_rows_parallel(self, r0: int = 0, r1: int | None = None, threads: int = 8) -> np.ndarray:
+        """Same rows as apply_rows, generated chunk by chunk on a few threads (NumPy's generators
+        release the GIL); for the full-size workloads."""
+        from concurrent.futures import ThreadPoolExecutor
+        r1 = self.T if r1 is None else r1
+        out = np.empty((r1 - r0, self.d), dtype=np.uint16)
+        spans = [(max(e, r0), min(e + CHUNK, r1)) for e in range(r0 - r0 % CHUNK, r1, CHUNK)]
+
+        def work(span):
+            a, b_ = span
+            out[a - r0:b_ - r0] = self.apply_rows(a, b_)
+
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(work, spans))
+        return out
+
     def calib_rows(self) -> np.ndarray:
         """bf16 bits [calib_tokens, d] of the calibration stream (same outlier channels)."""
         return self._rows(self.calib_seed, 0, self.calib_tokens, self.calib_tokens, massive=False)

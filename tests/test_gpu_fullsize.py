@@ -1,0 +1,100 @@
+"""Full-size runs of the BASELINE configurations in the launch configuration bench.py times,
+checked on sampled rows the oracle can compute one by one, plus properties that hold at any size."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import parity  # noqa: E402
+from oracle import perq_oracle as orc  # noqa: E402
+from paper_2601_22347_amd import binding, synth  # noqa: E402
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # workload, b list, rows sampled for the explicit-matrix oracle
+    ("llama1b_down", (16, 32, 64, 128), 2048),
+    ("block_vs_full", (32, 2048), 640),
+    ("llama8b_d4096", (128, 4096), 192),
+    ("llama8b_d14336", (128, 2048), 96),
+    ("calib_apply", (16, 32), 256),
+]
+
+
+def _sample_rows(wl, count):
+    rng = np.random.default_rng(7)
+    head = np.arange(min(count // 4, wl.T))
+    tail = wl.T - 1 - np.arange(min(count // 4, wl.T))
+    mid = rng.choice(wl.T, size=min(count, wl.T), replace=False)
+    rows = np.unique(np.concatenate([head, tail, mid, wl.massive_rows]))
+    return rows[:max(count, wl.massive_rows.size + count // 2)] if rows.size > 2 * count else rows
+
+
+@pytest.mark.parametrize("name,bs,count", CASES)
+def test_full_size_config(name, bs, count):
+    import torch
+    wl = synth.ALL[name]()
+    print(f"[full] {name}: generating T={wl.T} d={wl.d}", flush=True)
+    x_bits = wl.apply_rows_parallel()
+    x = binding.bits_to_device(x_bits)
+    rows = _sample_rows(wl, count) if count < wl.T else np.arange(wl.T)
+    rows_t = torch.from_numpy(rows).cuda()
+    a_dev = None
+    if wl.calib_tokens:
+        a_dev = binding.perq_colabs_mean(binding.bits_to_device(wl.calib_rows())).cpu().numpy()
+        a_orc = orc.colabs_mean(orc.bf16_bits_to_f64(wl.calib_rows()))
+        assert np.all(np.abs(a_dev - a_orc) <= 2e-6 * a_orc)
+    for b in bs:
+        perm = perm_t = None
+        if a_dev is not None:
+            perm = binding.perq_massdiff_perm(a_dev, b)
+            assert np.array_equal(perm, orc.massdiff_greedy(a_dev.astype(np.float64), b))
+            perm_t = torch.from_numpy(perm).cuda()
+        print(f"[full] {name} b={b} fmt={wl.fmt} rows checked={rows.size}", flush=True)
+        codes, scales = binding.perq_permute_rotate_quant(x, perm_t, b, wl.fmt)
+        codes2, scales2 = binding.perq_permute_rotate_quant(x, perm_t, b, wl.fmt)
+        torch.cuda.synchronize()
+        assert torch.equal(codes, codes2) and torch.equal(scales, scales2)      # deterministic
+        # properties at full size
+        if wl.fmt == "int4":
+            assert bool(torch.isfinite(scales).all()) and bool((scales >= 0).all())
+            lo, hi = codes & 0xF, codes >> 4
+            assert not bool(((lo == 8) | (hi == 8)).any())                      # -8 is never produced
+        else:
+            lo, hi = codes & 0xF, codes >> 4
+            assert not bool(((lo == 8) | (hi == 8)).any())                      # zero is always +0
+            assert int(scales.max()) < 255
+        rep = parity.compare_apply(x_bits[rows], perm, b, wl.fmt, codes[rows_t].cpu().numpy(),
+                                   scales[rows_t].cpu().numpy())
+        print("       ", rep.summary(), flush=True)
+        assert rep.ok(), (rep.summary(), rep.notes[:5])
+        del codes, scales, codes2, scales2
+
+
+def test_calibration_equalises_block_mass_and_lowers_the_rotated_maximum():
+    """configs[4]: blockwise l1 spread and post-rotation maximum, greedy permutation vs identity."""
+    import torch
+    wl = synth.calib_apply()
+    a = binding.perq_colabs_mean(binding.bits_to_device(wl.calib_rows())).cpu().numpy()
+    x_bits = wl.apply_rows(0, 512)
+    X = orc.bf16_bits_to_f64(x_bits)
+    x = binding.bits_to_device(x_bits)
+    for b in wl.block_sizes:
+        perm = binding.perq_massdiff_perm(a, b)
+        Lg, Li = orc.block_masses(a, perm, b), orc.block_masses(a, None, b)
+        assert Lg.max() - Lg.min() < 0.1 * (Li.max() - Li.min())
+        assert Lg.max() / Lg.mean() < Li.max() / Li.mean()
+        yg = binding.perq_permute_rotate_f32(x, torch.from_numpy(perm).cuda(), b).cpu().numpy()
+        yi = binding.perq_permute_rotate_f32(x, None, b).cpu().numpy()
+        bound_g = np.abs(X[:, perm]).reshape(512, -1, b).sum(axis=2).max(axis=1) / np.sqrt(b)
+        bound_i = np.abs(X).reshape(512, -1, b).sum(axis=2).max(axis=1) / np.sqrt(b)
+        # Proposition 2 on the device output, and the permutation lowers both bound and maximum
+        assert np.all(np.abs(yg).max(axis=1) <= bound_g * (1 + 1e-5))
+        assert np.all(np.abs(yi).max(axis=1) <= bound_i * (1 + 1e-5))
+        assert bound_g.mean() < bound_i.mean()
+        assert np.abs(yg).max(axis=1).mean() < np.abs(yi).max(axis=1).mean()
+        print(f"[calib] b={b}: block-mass spread {Li.max()-Li.min():.3f} -> {Lg.max()-Lg.min():.5f}; "
+              f"mean bound {bound_i.mean():.2f} -> {bound_g.mean():.2f}; "
+              f"mean |y|max {np.abs(yi).max(axis=1).mean():.2f} -> {np.abs(yg).max(axis=1).mean():.2f}", flush=True)
