@@ -84,8 +84,11 @@ def test_calibration_equalises_block_mass_and_lowers_the_rotated_maximum():
     for b in wl.block_sizes:
         perm = binding.perq_massdiff_perm(a, b)
         Lg, Li = orc.block_masses(a, perm, b), orc.block_masses(a, None, b)
-        assert Lg.max() - Lg.min() < 0.1 * (Li.max() - Li.min())
+        # one outlier channel alone outweighs an average block, so max_j L_j cannot go below a_max;
+        # the greedy reaches that floor (the heaviest channel is joined by the b-1 lightest ones)
+        assert Lg.max() - Lg.min() < Li.max() - Li.min()
         assert Lg.max() / Lg.mean() < Li.max() / Li.mean()
+        assert Lg.max() <= max(a.max() + (b - 1) * np.median(a), 1.01 * a.sum() / Lg.size)
         yg = binding.perq_permute_rotate_f32(x, torch.from_numpy(perm).cuda(), b).cpu().numpy()
         yi = binding.perq_permute_rotate_f32(x, None, b).cpu().numpy()
         bound_g = np.abs(X[:, perm]).reshape(512, -1, b).sum(axis=2).max(axis=1) / np.sqrt(b)
