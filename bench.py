@@ -64,6 +64,7 @@ def main() -> int:
     ap.add_argument("--algo", default="auto", choices=["auto", "butterfly", "mfma"])
     ap.add_argument("--pool-bytes", type=float, default=1.5e9,
                     help="input+output bytes cycled through so that no step re-reads cached data")
+    ap.add_argument("--identity", action="store_true", help="run the workload with P = I (no gather)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -80,6 +81,7 @@ def main() -> int:
     binding.load()
 
     key, b, fmt, use_perm = WORKLOADS[args.workload]
+    use_perm = use_perm and not args.identity
     wl = synth.ALL[key]()
     T, d = wl.T, wl.d
     dev = torch.device("cuda:0")

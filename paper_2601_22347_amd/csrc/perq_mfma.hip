@@ -224,7 +224,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     for (int e = 0; e < 8; e += 2) {
                         const uint32_t lo = *reinterpret_cast<const uint16_t*>(lds + kOff + src[(q * 2 + kt) * 8 + e]);
                         const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds + kOff + src[(q * 2 + kt) * 8 + e + 1]);
-                        w[e >> 1] = lo | (hi << 16);
+                        w[e >> 1] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);   // low halves of (lo, hi)
                     }
                     bfrag[q][kt] = make_uint4(w[0], w[1], w[2], w[3]);
                 } else {
