@@ -107,31 +107,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     constexpr uint32_t kZeroSlot = (kDouble ? kBufStride : 65536u) - 16u;
     uint32_t src[PERM ? 64 : 8];
     bool qvalid[kQ];
-#pragma unroll
-    for (int q = 0; q < kQ; ++q) {
-        const int sb = c * kQ + q;
-        qvalid[q] = sb * 32 < tile_len;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            const uint32_t pos = (uint32_t)tile_base + (uint32_t)sb * 32u + 16u * kt + 8u * h;
-            if constexpr (PERM) {
-                int4 e0 = make_int4(0, 0, 0, 0), e1 = make_int4(0, 0, 0, 0);
-                if (qvalid[q]) {
-                    e0 = *reinterpret_cast<const int4*>(p.perm + pos);
-                    e1 = *reinterpret_cast<const int4*>(p.perm + pos + 4);
-                }
-                const uint32_t ch[8] = {(uint32_t)e0.x, (uint32_t)e0.y, (uint32_t)e0.z, (uint32_t)e0.w,
-                                        (uint32_t)e1.x, (uint32_t)e1.y, (uint32_t)e1.z, (uint32_t)e1.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    src[(q * 2 + kt) * 8 + e] =
-                        qvalid[q] ? (uint32_t)rr * g.row_bytes + ((granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1))
-                                  : kZeroSlot;
-            } else {
-                src[q * 2 + kt] = qvalid[q] ? (uint32_t)rr * g.row_bytes + (granule_slot(pos >> 3) << 4) : kZeroSlot;
-            }
-        }
-    }
+    // (filled in after the first loads have been issued, see the end of the kernel)
 
     // -1 / +1 of the cross-lane butterflies on c
     float sgn[5];
@@ -376,6 +352,43 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     if constexpr (kDouble) {
         if ((int64_t)blockIdx.x + gridDim.x < ngroups) n_behind = issue_loads((int64_t)blockIdx.x + gridDim.x, kBufStride);
     }
+
+    // The operand addresses (and with them the reads of `perm`) are computed while the first row
+    // groups are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued
+    // together (absent sub-blocks re-read position 0 and are redirected to the zero slot).
+    {
+        int4 pe[kQ * 2][2];
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) {
+            const int sb = c * kQ + q;
+            qvalid[q] = sb * 32 < tile_len;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                const uint32_t pos = (uint32_t)tile_base + (uint32_t)sb * 32u + 16u * kt + 8u * h;
+                if constexpr (PERM) {
+                    const int32_t* pp = p.perm + (qvalid[q] ? pos : 0u);
+                    pe[q * 2 + kt][0] = *reinterpret_cast<const int4*>(pp);
+                    pe[q * 2 + kt][1] = *reinterpret_cast<const int4*>(pp + 4);
+                } else {
+                    src[q * 2 + kt] = qvalid[q] ? (uint32_t)rr * g.row_bytes + (granule_slot(pos >> 3) << 4) : kZeroSlot;
+                }
+            }
+        }
+        if constexpr (PERM) {
+#pragma unroll
+            for (int f = 0; f < kQ * 2; ++f) {
+                const int4 e0 = pe[f][0], e1 = pe[f][1];
+                const uint32_t ch[8] = {(uint32_t)e0.x, (uint32_t)e0.y, (uint32_t)e0.z, (uint32_t)e0.w,
+                                        (uint32_t)e1.x, (uint32_t)e1.y, (uint32_t)e1.z, (uint32_t)e1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    src[f * 8 + e] =
+                        qvalid[f >> 1] ? (uint32_t)rr * g.row_bytes + ((granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1))
+                                       : kZeroSlot;
+            }
+        }
+    }
+
     for (int64_t grp = blockIdx.x; grp < ngroups; grp += 2 * (int64_t)gridDim.x) {
         do_group(grp, std::integral_constant<uint32_t, 0>{});
         if (grp + gridDim.x < ngroups) do_group(grp + gridDim.x, std::integral_constant<uint32_t, 1>{});
