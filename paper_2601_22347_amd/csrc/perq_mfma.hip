@@ -13,8 +13,15 @@
 // are exact and accumulate in fp32.
 //     b = 64, 128     : the product is widened to H_64 / H_128: accumulator tile q sums the
 //                       +-H_32 products of the 2 / 4 sub-blocks of its block (more MFMAs, no VALU)
-//     b = 256 .. 4096 : H_128 as above, then butterflies across lanes on c (DPP / swizzle /
-//                       permlane swap)
+//     b = 256, 512    : H_128 as above, then one or two butterfly stages across lanes on c
+//                       (DPP quad_perm)
+//     b = 1024 .. 4096: the roles are turned round.  The data become the A operand, read with
+//                       a stride of 32 elements: A[m][K] = x[32 K + m], and the product with the
+//                       +-1 matrix I (x) H_{b/32} contracts the HIGH index bits K (up to 128 of
+//                       them: 8 K-steps x 4 column tiles, 8 .. 32 MFMAs per tile).  A lane then
+//                       holds, for 4 transformed high indices, 16 contiguous low positions m, and
+//                       the low five bits are finished by four in-register butterfly stages and
+//                       one half-wave swap: 5.5 VALU per element instead of 2 per cross-lane stage.
 //
 // Data movement.  The raw bf16 rows go global -> LDS with 16-byte direct-to-LDS loads (no
 // registers, no ds_write), streaming policy; they are the only HBM reads.  The B operands are
@@ -79,10 +86,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     const bool wave_local = g.tiles_per_row == 1;
 
     // ---- A operand: rows sigma(i) of the +-1 matrix, two K steps of 16 ---------------------
+    // high-K mode (b >= 1024): the constant is the B operand, column j = lane & 31 unpermuted
+    constexpr bool kHighK = STAGES >= 5;
+    constexpr bool kElem = PERM || kHighK;          // operands gathered element by element
     bf16x8_t afrag[2], afrag_neg[2];
+    const uint32_t sigma_i = 16u * ((((uint32_t)lane & 31u) >> 2) & 1u) + 4u * (((uint32_t)lane & 31u) >> 3) +
+                             ((uint32_t)lane & 3u);
     {
-        const uint32_t i = (uint32_t)lane & 31u;
-        const uint32_t n = 16u * ((i >> 2) & 1u) + 4u * (i >> 3) + (i & 3u);
+        const uint32_t n = kHighK ? ((uint32_t)lane & 31u) : sigma_i;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             uint32_t w[4];
@@ -90,7 +101,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             for (int e = 0; e < 8; ++e) {
                 const uint32_t k = 16u * kt + 8u * h + e;
                 uint32_t bits;
-                if (b >= 32) bits = popc_parity(n & k) ? 0xBF80u : 0x3F80u;
+                if (b >= 32) bits = popc_parity(n & k) ? 0xBF80u : 0x3F80u;   // H_32 is symmetric
                 else bits = (n >> 4) != (k >> 4) ? 0u : (popc_parity(n & k & 15u) ? 0xBF80u : 0x3F80u);
                 if (e & 1) w[e >> 1] |= bits << 16; else w[e >> 1] = bits;
             }
@@ -105,9 +116,11 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // Sub-blocks past the end of a ragged last tile read a 16-byte slot that is kept at zero
     // (the last 16 bytes of each staging buffer; a ragged row never fills its buffer).
     constexpr uint32_t kZeroSlot = (kDouble ? kBufStride : 65536u) - 16u;
-    uint32_t src[PERM ? 64 : 8];
+    uint32_t src[kElem ? 64 : 8];
     bool qvalid[kQ];
     // (filled in after the first loads have been issued, see the end of the kernel)
+    // sub-block (32 positions) of the tile that accumulator tile q of this lane ends up holding
+    auto sbq = [&](int q) -> int { return kHighK ? q * 32 + c : c * kQ + q; };
 
     // -1 / +1 of the cross-lane butterflies on c
     float sgn[5];
@@ -194,7 +207,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         for (int q = 0; q < kQ; ++q) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt) {
-                if constexpr (PERM) {
+                if constexpr (kElem) {
                     uint32_t w[4];
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
@@ -217,40 +230,72 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             if (more) issue_loads(grp + gridDim.x, 0u);
         }
 
-        // ---- H_32 (b <= 32), H_64 or H_128 on the matrix cores ----------------------------------
-        // accumulator tile qo = sum over the sub-blocks qi of its block of (+-H_32) * X_qi, the sign
-        // being entry (qo, qi) of the Sylvester matrix of order kDense
-        constexpr int kDense = STAGES == 0 ? 1 : (STAGES == 1 ? 2 : 4);
+        // ---- the matrix product ------------------------------------------------------------------
         float v[64];
+        if constexpr (!kHighK) {
+            // H_32 (b <= 32), H_64 or H_128: accumulator tile qo = sum over the sub-blocks qi of its
+            // block of (+-H_32) * X_qi, the sign being entry (qo, qi) of the Sylvester matrix of
+            // order kDense
+            constexpr int kDense = STAGES == 0 ? 1 : (STAGES == 1 ? 2 : 4);
 #pragma unroll
-        for (int qo = 0; qo < kQ; ++qo) {
-            f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            for (int qo = 0; qo < kQ; ++qo) {
+                f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-            for (int j = 0; j < kDense; ++j) {
-                const int qi = (qo & ~(kDense - 1)) | j;
-                const bool neg = __builtin_popcount(qo & qi & (kDense - 1)) & 1;
+                for (int j = 0; j < kDense; ++j) {
+                    const int qi = (qo & ~(kDense - 1)) | j;
+                    const bool neg = __builtin_popcount(qo & qi & (kDense - 1)) & 1;
 #pragma unroll
-                for (int kt = 0; kt < 2; ++kt)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(neg ? afrag_neg[kt] : afrag[kt],
-                                                                  __builtin_bit_cast(bf16x8_t, bfrag[qi][kt]), acc, 0, 0, 0);
+                    for (int kt = 0; kt < 2; ++kt)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(neg ? afrag_neg[kt] : afrag[kt],
+                                                                      __builtin_bit_cast(bf16x8_t, bfrag[qi][kt]), acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[qo * 16 + r] = acc[r];
             }
+        } else {
+            // D[m][n] = sum_K X[m][K] * S[K][n], S = I (x) H_{b/32} on the 128 high indices of the
+            // tile.  With K = 32 Kh + Kl and n = 32 nt + j the entry is H_{b/1024}[Kh][nt] (zero off
+            // the block diagonal) times H_32[Kl][j]; the latter is the constant fragment.
+            constexpr int kHi = 1 << (STAGES - 5);            // b / 1024: order of the outer factor
 #pragma unroll
-            for (int r = 0; r < 16; ++r) v[qo * 16 + r] = acc[r];
+            for (int nt = 0; nt < kQ; ++nt) {
+                f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                for (int kt = 0; kt < 8; ++kt) {
+                    const int Kh = kt >> 1;
+                    if ((Kh / kHi) != (nt / kHi)) continue;
+                    const bool neg = __builtin_popcount((Kh % kHi) & (nt % kHi)) & 1;
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bfrag[kt >> 1][kt & 1]),
+                                                                  neg ? afrag_neg[kt & 1] : afrag[kt & 1], acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[nt * 16 + r] = acc[r];
+            }
+            // low five bits: positions m = 16 h + r of every sub-block
+#pragma unroll
+            for (int hh = 1; hh < 16; hh <<= 1) {
+#pragma unroll
+                for (int i = 0; i < 64; ++i) {
+                    if ((i & hh) == 0) {
+                        const float a0 = v[i], a1 = v[i | hh];
+                        v[i] = a0 + a1;
+                        v[i | hh] = a0 - a1;
+                    }
+                }
+            }
+            lane_stage<32>(v, 0.0f);
         }
 
-        // ---- butterflies across lanes for b >= 256 ----------------------------------------------
-        if constexpr (STAGES >= 3) lane_stage<1>(v, sgn[0]);
-        if constexpr (STAGES >= 4) lane_stage<2>(v, sgn[1]);
-        if constexpr (STAGES >= 5) lane_stage<4>(v, sgn[2]);
-        if constexpr (STAGES >= 6) lane_stage<8>(v, sgn[3]);
-        if constexpr (STAGES >= 7) lane_stage<16>(v, sgn[4]);
+        // ---- butterflies across lanes for b = 256, 512 ------------------------------------------
+        if constexpr (STAGES == 3 || STAGES == 4) lane_stage<1>(v, sgn[0]);
+        if constexpr (STAGES == 4) lane_stage<2>(v, sgn[1]);
 
         // ---- epilogue: lane (c,h) holds outputs 16h..16h+15 of sub-blocks 4c..4c+3 -------------
         if constexpr (OUT == OUT_F32) {
 #pragma unroll
             for (int q = 0; q < kQ; ++q) {
                 if (row_live && qvalid[q]) {
-                    float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + tile_base + (c * kQ + q) * 32 + 16 * h);
+                    float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + tile_base + sbq(q) * 32 + 16 * h);
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         yo[j] = make_float4(v[q * 16 + 4 * j] * p.rsqrt_b, v[q * 16 + 4 * j + 1] * p.rsqrt_b,
@@ -303,7 +348,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     pk[q][1] = int4_pack8(v + q * 16 + 8, inv);
                 }
             }
-            // Give lane (c,0) the whole of sub-blocks 4c, 4c+1 and lane (c,1) the whole of 4c+2, 4c+3:
+            // Give lane (c,0) the whole of its sub-blocks q = 0, 1 and lane (c,1) the whole of q = 2, 3:
             // the half-wave swap exchanges (q, h=1) of the low lanes' tiles with (q+2, h=0).
             uint32_t out[2][4];
 #pragma unroll
@@ -320,7 +365,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             // pieces at a 32-byte pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
             unsigned char* ob = lds + g.out_off + (uint32_t)wave * 2048u;
             {
-                const uint32_t s0 = (uint32_t)(c * kQ + 2 * h), s1 = s0 + 1u;
+                const uint32_t s0 = (uint32_t)sbq(2 * h), s1 = (uint32_t)sbq(2 * h + 1);
                 *reinterpret_cast<uint4*>(ob + ((s0 ^ ((s0 >> 3) & 7u)) << 4)) = make_uint4(out[0][0], out[0][1], out[0][2], out[0][3]);
                 *reinterpret_cast<uint4*>(ob + ((s1 ^ ((s1 >> 3) & 7u)) << 4)) = make_uint4(out[1][0], out[1][1], out[1][2], out[1][3]);
             }
@@ -332,9 +377,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 if (lane * 32 < tile_len) store_stream16(crow, o0);
                 if (2048 + lane * 32 < tile_len) store_stream16(crow + 1024, o1);
                 if constexpr (OUT == OUT_MXFP4) {
-                    if (h == 0 && qvalid[0])
-                        *reinterpret_cast<uint32_t*>(static_cast<uint8_t*>(p.scales) + row * (int64_t)(d >> 5) +
-                                                     (tile_base >> 5) + c * kQ) = ebytes;
+                    uint8_t* srow = static_cast<uint8_t*>(p.scales) + row * (int64_t)(d >> 5) + (tile_base >> 5);
+                    if constexpr (!kHighK) {
+                        if (h == 0 && qvalid[0]) *reinterpret_cast<uint32_t*>(srow + c * kQ) = ebytes;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < kQ; ++q)
+                            if (h == 0 && qvalid[q]) srow[sbq(q)] = (uint8_t)(ebytes >> (8 * q));
+                    }
                 } else {
                     if (lane == 0 && tile_base == 0)
                         static_cast<float*>(p.scales)[row] = (float)((double)row_max * p.inv_7sqrt_b);
@@ -356,7 +406,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // The operand addresses (and with them the reads of `perm`) are computed while the first row
     // groups are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued
     // together (absent sub-blocks re-read position 0 and are redirected to the zero slot).
-    {
+    if constexpr (!kHighK) {
         int4 pe[kQ * 2][2];
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
@@ -385,6 +435,32 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     src[f * 8 + e] =
                         qvalid[f >> 1] ? (uint32_t)rr * g.row_bytes + ((granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1))
                                        : kZeroSlot;
+            }
+        }
+    } else {
+        // high-K mode: fragment kt, element e of lane (i, h) is position 32 K + sigma(i) of the tile,
+        // K = 16 kt + 8 h + e; all 64 channel numbers are fetched before any is used
+#pragma unroll
+        for (int q = 0; q < kQ; ++q) qvalid[q] = sbq(q) * 32 < tile_len;
+        uint32_t ch[64];
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t K = 16u * f + 8u * h + e;
+                const uint32_t pos = (uint32_t)tile_base + 32u * K + sigma_i;
+                const bool ok = (int)(32u * K) < tile_len;
+                if constexpr (PERM) ch[f * 8 + e] = (uint32_t)p.perm[ok ? pos : 0u];
+                else ch[f * 8 + e] = pos;
+            }
+        }
+#pragma unroll
+        for (int f = 0; f < 8; ++f) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = (int)(32u * (16u * f + 8u * h + e)) < tile_len;
+                const uint32_t cc = ch[f * 8 + e];
+                src[f * 8 + e] = ok ? (uint32_t)rr * g.row_bytes + ((granule_slot(cc >> 3) << 4) | ((cc & 7u) << 1)) : kZeroSlot;
             }
         }
     }

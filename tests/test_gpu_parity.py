@@ -114,9 +114,10 @@ SHAPES = [
     (19, 1024, [16, 32, 256, 512, 1024]),
     (13, 3072, [16, 32, 64, 1024]),          # nt = 96: not a power of two
     (21, 2048, [32, 2048]),
-    (9, 8192, [16, 32, 64, 128, 2048, 8192]),
-    (5, 14336, [32, 128, 512, 2048]),
-    (3, 32768, [16, 32768]),
+    (9, 8192, [16, 32, 64, 128, 2048, 4096, 8192]),
+    (5, 14336, [32, 128, 512, 1024, 2048]),
+    (6, 20480, [256, 1024, 4096]),           # 8-wave groups, ragged last tile
+    (3, 32768, [16, 2048, 4096, 32768]),
 ]
 
 
