@@ -62,7 +62,9 @@ __device__ __forceinline__ uint32_t popc_parity(uint32_t v) { return __builtin_p
 
 // STAGES = number of +-1 butterfly stages after the matrix product: log2(b) - 5, 0 for b <= 32.
 // A template parameter so that the accumulators stay in registers along one straight path.
-template <int OUT, bool PERM, int NWAVES, int STAGES>
+// SHARED: the four waves of a workgroup build one table of operand addresses together (see below);
+// chosen by the host for d = 4096 with a permutation.
+template <int OUT, bool PERM, int NWAVES, int STAGES, bool SHARED>
 // (two 4-wave workgroups fit a CU's LDS, so the register budget is that of 2 waves per SIMD)
 __global__ void __launch_bounds__(NWAVES * 64, NWAVES == 4 ? 2 : 1)
 mfma_kernel(ApplyParams p, MfmaGeom g) {
@@ -128,6 +130,18 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     for (int k = 0; k < 5; ++k) sgn[k] = (c >> k) & 1 ? -1.0f : 1.0f;
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
+    // Row group of this workgroup's it-th iteration.  Round `it` covers groups it*G .. it*G+G-1
+    // (G = grid size); the workgroup's place inside a round moves by kRot each round, so that no
+    // workgroup (and no XCD: they are dealt round-robin by workgroup index) stays on one residue
+    // class of row addresses for the whole launch.
+#ifndef PERQ_ROT
+#define PERQ_ROT 0
+#endif
+    auto group_of = [&](int it) -> int64_t {
+        const uint32_t G = gridDim.x;
+        const uint32_t slot = PERQ_ROT ? (blockIdx.x + (uint32_t)it * (uint32_t)PERQ_ROT) % G : blockIdx.x;
+        return (int64_t)it * G + slot;
+    };
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
 
     // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  In wave-local
@@ -173,9 +187,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         return issued;
     };
 
-    // Wait until at most n of this wave's vector-memory operations are outstanding.  Loads
-    // complete in issue order, so once no more than the n loads issued after a group remain,
-    // that group has landed whatever the stores in between have done.
+    // Wait until at most n of this wave's vector-memory operations are outstanding.  They retire
+    // in issue order, so once no more than the n operations issued after a group's loads remain,
+    // that group has landed.  n must not exceed the true count; a smaller n only waits longer.
     auto wait_vm_le = [&](int n) {
         switch (n) {
             case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
@@ -186,19 +200,27 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
             case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
             case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-            default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+            case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+            case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
+            case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
+            case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
+            case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+            case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
+            default: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
         }
     };
-    int n_behind = 0;      // loads of the group after the current one, already in flight
+    // Loads of the group after the current one, already in flight.  (The stores issued in between
+    // are not counted: that only makes the wait stricter, and counting them measured no faster.)
+    int n_behind = 0;
 
     // ---- one row group out of staging buffer BUF -------------------------------------------
-    auto do_group = [&](int64_t grp, auto buf_const) {
+    auto do_group = [&](int it, auto buf_const) {
         constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
+        const int64_t grp = group_of(it);
         const int64_t row = grp * g.rows + rr;
         const bool row_live = row < p.T;
-        const bool more = grp + gridDim.x < ngroups;
 
-        wait_vm_le(kDouble ? n_behind : 0);      // this wave's direct-to-LDS loads of the group have landed
+        wait_vm_le(kDouble ? n_behind : 0);   // this wave's direct-to-LDS loads of the group have landed
         if (!wave_local) __syncthreads();
 
         // ---- B operands out of LDS ----------------------------------------------------------
@@ -224,10 +246,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         // The operands are in registers: refill this buffer right away.  With two buffers the
         // group after next goes here, so two groups of loads are in flight during the arithmetic.
         if (!wave_local) __syncthreads();
-        if constexpr (kDouble) {
-            n_behind = grp + 2 * (int64_t)gridDim.x < ngroups ? issue_loads(grp + 2 * (int64_t)gridDim.x, kOff) : 0;
-        } else {
-            if (more) issue_loads(grp + gridDim.x, 0u);
+        {
+            const int64_t nxt = group_of(it + (kDouble ? 2 : 1));
+            n_behind = nxt < ngroups ? issue_loads(nxt, kOff) : 0;
         }
 
         // ---- the matrix product ------------------------------------------------------------------
@@ -393,20 +414,83 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         }
     };
 
+    // Operand addresses through `perm`, shared case: when every wave of the workgroup owns a whole
+    // row of exactly one tile (d = 4096), all four waves need the same 64 addresses per lane up to
+    // the row's base.  Wave w then looks up only fragments 2w and 2w+1 (16 channels per lane),
+    // leaves their byte offsets inside a row in LDS as 16-bit numbers (fragment f of lane l: 16
+    // bytes at f * 1024 + 16 l of the output staging area, idle until the first epilogue), and
+    // after the barrier below every lane collects its eight fragments.  The reads of `perm` and
+    // their arithmetic come before the first row loads so that nothing queues behind those.
+    constexpr bool shared_src = SHARED;
+    static_assert(!SHARED || (PERM && NWAVES == 4), "the shared table needs four waves with the same tile");
+    if constexpr (SHARED) {
+        {
+            uint32_t ch[16];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const uint32_t f = 2u * (uint32_t)wave + j;
+                if constexpr (!kHighK) {
+                    const uint32_t pos = ((uint32_t)c * kQ + (f >> 1)) * 32u + 16u * (f & 1u) + 8u * h;
+                    const int4 e0 = *reinterpret_cast<const int4*>(p.perm + pos);
+                    const int4 e1 = *reinterpret_cast<const int4*>(p.perm + pos + 4);
+                    ch[8 * j + 0] = e0.x; ch[8 * j + 1] = e0.y; ch[8 * j + 2] = e0.z; ch[8 * j + 3] = e0.w;
+                    ch[8 * j + 4] = e1.x; ch[8 * j + 5] = e1.y; ch[8 * j + 6] = e1.z; ch[8 * j + 7] = e1.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ch[8 * j + e] = (uint32_t)p.perm[32u * (16u * f + 8u * h + e) + sigma_i];
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const uint32_t a0 = ch[8 * j + e], a1 = ch[8 * j + e + 1];
+                    const uint32_t o0 = (granule_slot(a0 >> 3) << 4) | ((a0 & 7u) << 1);
+                    const uint32_t o1 = (granule_slot(a1 >> 3) << 4) | ((a1 & 7u) << 1);
+                    w[e >> 1] = o0 | (o1 << 16);
+                }
+                *reinterpret_cast<uint4*>(lds + g.out_off + (2u * (uint32_t)wave + j) * 1024u + 16u * (uint32_t)lane) =
+                    make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    }
+
     if (tid < 4) {
         *reinterpret_cast<uint32_t*>(lds + kZeroSlot + 4 * tid) = 0u;
         if constexpr (kDouble) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
     }
     __syncthreads();
-    if ((int64_t)blockIdx.x < ngroups) issue_loads(blockIdx.x, 0u);
+    if (group_of(0) < ngroups) issue_loads(group_of(0), 0u);
     if constexpr (kDouble) {
-        if ((int64_t)blockIdx.x + gridDim.x < ngroups) n_behind = issue_loads((int64_t)blockIdx.x + gridDim.x, kBufStride);
+        if (group_of(1) < ngroups) n_behind = issue_loads(group_of(1), kBufStride);
     }
 
-    // The operand addresses (and with them the reads of `perm`) are computed while the first row
-    // groups are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued
-    // together (absent sub-blocks re-read position 0 and are redirected to the zero slot).
-    if constexpr (!kHighK) {
+    // Shared case: collect the eight fragments of addresses the four waves have left in LDS.
+    if constexpr (SHARED) {
+        {
+            const uint32_t base = (uint32_t)rr * g.row_bytes;
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) qvalid[q] = true;
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                const uint4 t = *reinterpret_cast<const uint4*>(lds + g.out_off + (uint32_t)f * 1024u + 16u * (uint32_t)lane);
+                const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    src[f * 8 + e] = base + (w[e >> 1] & 0xFFFFu);
+                    src[f * 8 + e + 1] = base + (w[e >> 1] >> 16);
+                }
+            }
+            __syncthreads();      // the table's place is the output staging of the first epilogue
+        }
+    }
+    // Otherwise every wave builds its own addresses (and reads `perm`) while the first row groups
+    // are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued together
+    // (absent sub-blocks re-read position 0 and are redirected to the zero slot).
+    if constexpr (shared_src) {
+        // done above
+    } else if constexpr (!kHighK) {
         int4 pe[kQ * 2][2];
 #pragma unroll
         for (int q = 0; q < kQ; ++q) {
@@ -465,9 +549,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         }
     }
 
-    for (int64_t grp = blockIdx.x; grp < ngroups; grp += 2 * (int64_t)gridDim.x) {
-        do_group(grp, std::integral_constant<uint32_t, 0>{});
-        if (grp + gridDim.x < ngroups) do_group(grp + gridDim.x, std::integral_constant<uint32_t, 1>{});
+    for (int it = 0; group_of(it) < ngroups; it += 2) {
+        do_group(it, std::integral_constant<uint32_t, 0>{});
+        if (group_of(it + 1) < ngroups) do_group(it + 1, std::integral_constant<uint32_t, 1>{});
     }
 }
 
@@ -487,7 +571,10 @@ hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
     g.out_off = g.red_off + 32u * sizeof(float);
     const uint32_t lds_bytes = g.out_off + NWAVES * 2048u;
 
-    auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES> : mfma_kernel<OUT, false, NWAVES, STAGES>;
+    auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
+    if constexpr (NWAVES == 4) {
+        if (p.perm && p.d == kTile) kern = mfma_kernel<OUT, true, NWAVES, STAGES, true>;
+    }
     if (lds_bytes > 64u * 1024u) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
