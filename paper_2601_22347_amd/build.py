@@ -15,6 +15,9 @@ SOURCES = ["perq_host.cpp", "perq_colabs.hip", "perq_butterfly.hip", "perq_mfma.
 # -packed-fp32-ops: keep the compiler from fusing fp32 pairs into packed VALU instructions.
 HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",
              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             # keep the one-lane ticket atomic of the matrix-core kernel as written: the wave-level
+             # rewrite of uniform atomics reads the result back at once and stalls on it
+             "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
              "-Wall", "-Wno-unused-command-line-argument"]
 
 

@@ -32,6 +32,7 @@
 #include "perq_device.h"
 #include "perq_launch.h"
 
+#include <atomic>
 #include <type_traits>
 
 namespace perq {
@@ -48,9 +49,15 @@ struct MfmaGeom {
     int rows;            // rows per workgroup iteration = waves / tiles_per_row
     int nload;           // direct-to-LDS load instructions per lane per iteration
     uint32_t row_bytes;  // d * 2
-    uint32_t red_off;    // byte offset of the cross-wave reduction scratch
-    uint32_t out_off;    // byte offset of the per-wave output staging (2 KiB per wave)
+    uint32_t ctr_set;    // which set of ticket counters this launch draws from (D4K kernels)
 };
+
+// Ticket counters of the run-time row schedule: kWorkSets sets (consecutive launches rotate through
+// them, so launches that overlap on different streams do not share one) of kWorkQueues counters,
+// each on a 256-byte line of its own.  Zero at load; every launch leaves its set at zero again.
+constexpr uint32_t kWorkQueues = 32;
+constexpr uint32_t kWorkSets = 64;
+__device__ uint32_t work_ctr[kWorkSets][kWorkQueues][64];
 
 // granule -> slot inside a row (an involution: bits 4..6 select the xor pattern for bits 0..2)
 __device__ __forceinline__ uint32_t granule_slot(uint32_t g) {
@@ -60,15 +67,54 @@ __device__ __forceinline__ uint32_t granule_slot(uint32_t g) {
 
 __device__ __forceinline__ uint32_t popc_parity(uint32_t v) { return __builtin_popcount(v) & 1u; }
 
+// Stores to LDS and workgroup barriers of the main loop, written as instructions.  The compiler
+// makes every LDS store it knows of wait until no direct-to-LDS load is outstanding (it cannot
+// tell that the staging buffers and these small scratch areas are disjoint), and its barrier waits
+// for all memory traffic; either would drain the loads that are meant to stay in flight across
+// iterations.  LDS instructions of one wave execute in order, so a later read of the same wave
+// sees the store without a wait; across waves the barrier below waits for the wave's own LDS
+// traffic first.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+__device__ __forceinline__ void lds_store16(void* p, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    const u32x4_t v = {a, b, c, d};
+    asm volatile("ds_write_b128 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_store4(void* p, float v) {
+    asm volatile("ds_write_b32 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
+}
+// two 16-byte reads, complete on return
+__device__ __forceinline__ void lds_load16x2(const void* p0, const void* p1, uint4& v0, uint4& v1) {
+    u32x4_t a, b;
+    asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&v"(a), "=&v"(b)
+                 : "v"(lds_addr(p0)), "v"(lds_addr(p1))
+                 : "memory");
+    v0 = make_uint4(a.x, a.y, a.z, a.w);
+    v1 = make_uint4(b.x, b.y, b.z, b.w);
+}
+__device__ __forceinline__ void workgroup_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // STAGES = number of +-1 butterfly stages after the matrix product: log2(b) - 5, 0 for b <= 32.
 // A template parameter so that the accumulators stay in registers along one straight path.
-// SHARED: the four waves of a workgroup build one table of operand addresses together (see below);
-// chosen by the host for d = 4096 with a permutation.
-template <int OUT, bool PERM, int NWAVES, int STAGES, bool SHARED>
+// D4K: the variant for d = 4096 exactly (one full tile per row, every wave on rows of its own) and
+// enough rows to go round.  With a permutation the four waves of a workgroup build one table of
+// operand addresses together, and the rows are dealt to the waves at run time (see below).
+template <int OUT, bool PERM, int NWAVES, int STAGES, bool D4K>
 // (two 4-wave workgroups fit a CU's LDS, so the register budget is that of 2 waves per SIMD)
 __global__ void __launch_bounds__(NWAVES * 64, NWAVES == 4 ? 2 : 1)
 mfma_kernel(ApplyParams p, MfmaGeom g) {
+    // The dynamic array holds nothing but the row staging buffers, the targets of the
+    // direct-to-LDS loads.  Everything the kernel writes to LDS with ordinary stores lives in
+    // arrays of its own: the compiler makes a store to LDS wait for every direct-to-LDS load
+    // that may write the same memory, and with one shared array that was all loads in flight.
     extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ __align__(16) unsigned char out_stage[NWAVES * 2048];   // per-wave output staging
+    __shared__ float red_scratch[32];                                  // row maxima across waves
     // Two staging buffers when a row group fits 32 KiB (4 waves): the loads of the next group are
     // in flight during the whole of the current one.  The buffer is selected by a compile-time
     // offset on the LDS instructions (loop unrolled by two).  8-wave groups use one buffer.
@@ -85,7 +131,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     int tile_len = d - tile_base;
     tile_len = tile_len < 0 ? 0 : (tile_len > kTile ? kTile : tile_len);
     // one tile per row: every wave stages and consumes its own row, no workgroup barrier needed
-    const bool wave_local = g.tiles_per_row == 1;
+    const bool wave_local = D4K || g.tiles_per_row == 1;
 
     // ---- A operand: rows sigma(i) of the +-1 matrix, two K steps of 16 ---------------------
     // high-K mode (b >= 1024): the constant is the B operand, column j = lane & 31 unpermuted
@@ -130,18 +176,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     for (int k = 0; k < 5; ++k) sgn[k] = (c >> k) & 1 ? -1.0f : 1.0f;
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
-    // Row group of this workgroup's it-th iteration.  Round `it` covers groups it*G .. it*G+G-1
-    // (G = grid size); the workgroup's place inside a round moves by kRot each round, so that no
-    // workgroup (and no XCD: they are dealt round-robin by workgroup index) stays on one residue
-    // class of row addresses for the whole launch.
-#ifndef PERQ_ROT
-#define PERQ_ROT 0
-#endif
-    auto group_of = [&](int it) -> int64_t {
-        const uint32_t G = gridDim.x;
-        const uint32_t slot = PERQ_ROT ? (blockIdx.x + (uint32_t)it * (uint32_t)PERQ_ROT) % G : blockIdx.x;
-        return (int64_t)it * G + slot;
-    };
+    // Static schedule: the workgroup's it-th row group.
+    auto group_of = [&](int it) -> int64_t { return (int64_t)it * gridDim.x + blockIdx.x; };
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
 
     // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  In wave-local
@@ -214,14 +250,15 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     int n_behind = 0;
 
     // ---- one row group out of staging buffer BUF -------------------------------------------
-    auto do_group = [&](int it, auto buf_const) {
+    // `row` is this wave's row of the group; `refill` issues the loads that reuse the buffer.
+    auto do_group = [&](int64_t row, auto buf_const, auto&& refill) {
         constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
-        const int64_t grp = group_of(it);
-        const int64_t row = grp * g.rows + rr;
         const bool row_live = row < p.T;
 
-        wait_vm_le(kDouble ? n_behind : 0);   // this wave's direct-to-LDS loads of the group have landed
-        if (!wave_local) __syncthreads();
+        // this wave's direct-to-LDS loads of the group have landed
+        if constexpr (D4K) __builtin_amdgcn_s_waitcnt(0x0F78);     // all but the 8 loads behind it
+        else wait_vm_le(kDouble ? n_behind : 0);
+        if (!wave_local) workgroup_barrier_lds();
 
         // ---- B operands out of LDS ----------------------------------------------------------
         uint4 bfrag[kQ][2];
@@ -245,11 +282,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         }
         // The operands are in registers: refill this buffer right away.  With two buffers the
         // group after next goes here, so two groups of loads are in flight during the arithmetic.
-        if (!wave_local) __syncthreads();
-        {
-            const int64_t nxt = group_of(it + (kDouble ? 2 : 1));
-            n_behind = nxt < ngroups ? issue_loads(nxt, kOff) : 0;
-        }
+        if (!wave_local) workgroup_barrier_lds();
+        refill();
 
         // ---- the matrix product ------------------------------------------------------------------
         float v[64];
@@ -355,9 +389,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 if (!wave_local) {
                     // row maximum across the row's waves; scratch alternates with the group parity so
                     // that one barrier per group is enough
-                    float* red = reinterpret_cast<float*>(lds + g.red_off) + decltype(buf_const)::value * 16;
-                    if (lane == 0) red[wave] = m;
-                    __syncthreads();
+                    float* red = red_scratch + decltype(buf_const)::value * 16;
+                    if (lane == 0) lds_store4(red + wave, m);
+                    workgroup_barrier_lds();
                     const int w0 = rr * g.tiles_per_row;
                     for (int w = 0; w < g.tiles_per_row; ++w) m = fmaxf(m, red[w0 + w]);
                 }
@@ -384,15 +418,15 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             // The wave's 2 KiB of codes take one trip through LDS so that each store instruction
             // writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of 16-byte
             // pieces at a 32-byte pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
-            unsigned char* ob = lds + g.out_off + (uint32_t)wave * 2048u;
+            unsigned char* ob = out_stage + (uint32_t)wave * 2048u;
             {
                 const uint32_t s0 = (uint32_t)sbq(2 * h), s1 = (uint32_t)sbq(2 * h + 1);
-                *reinterpret_cast<uint4*>(ob + ((s0 ^ ((s0 >> 3) & 7u)) << 4)) = make_uint4(out[0][0], out[0][1], out[0][2], out[0][3]);
-                *reinterpret_cast<uint4*>(ob + ((s1 ^ ((s1 >> 3) & 7u)) << 4)) = make_uint4(out[1][0], out[1][1], out[1][2], out[1][3]);
+                lds_store16(ob + ((s0 ^ ((s0 >> 3) & 7u)) << 4), out[0][0], out[0][1], out[0][2], out[0][3]);
+                lds_store16(ob + ((s1 ^ ((s1 >> 3) & 7u)) << 4), out[1][0], out[1][1], out[1][2], out[1][3]);
             }
             const uint32_t r0 = (uint32_t)lane, r1 = 64u + (uint32_t)lane;
-            const uint4 o0 = *reinterpret_cast<const uint4*>(ob + ((r0 ^ ((r0 >> 3) & 7u)) << 4));
-            const uint4 o1 = *reinterpret_cast<const uint4*>(ob + ((r1 ^ ((r1 >> 3) & 7u)) << 4));
+            uint4 o0, o1;
+            lds_load16x2(ob + ((r0 ^ ((r0 >> 3) & 7u)) << 4), ob + ((r1 ^ ((r1 >> 3) & 7u)) << 4), o0, o1);
             if (row_live) {
                 uint8_t* crow = p.codes + row * (int64_t)(d >> 1) + (tile_base >> 1) + lane * 16;
                 if (lane * 32 < tile_len) store_stream16(crow, o0);
@@ -418,11 +452,13 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // row of exactly one tile (d = 4096), all four waves need the same 64 addresses per lane up to
     // the row's base.  Wave w then looks up only fragments 2w and 2w+1 (16 channels per lane),
     // leaves their byte offsets inside a row in LDS as 16-bit numbers (fragment f of lane l: 16
-    // bytes at f * 1024 + 16 l of the output staging area, idle until the first epilogue), and
-    // after the barrier below every lane collects its eight fragments.  The reads of `perm` and
-    // their arithmetic come before the first row loads so that nothing queues behind those.
+    // bytes at f * 1024 + 16 l of the second staging buffer, not yet in use), and after the
+    // barrier below every lane collects its eight fragments.  All of this comes before the first
+    // row loads: nothing queues behind those, and no ordinary LDS access meets a pending
+    // direct-to-LDS load.
+    constexpr bool SHARED = D4K && PERM;
     constexpr bool shared_src = SHARED;
-    static_assert(!SHARED || (PERM && NWAVES == 4), "the shared table needs four waves with the same tile");
+    static_assert(!D4K || NWAVES == 4, "d = 4096 runs on four-wave workgroups");
     if constexpr (SHARED) {
         {
             uint32_t ch[16];
@@ -450,7 +486,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     const uint32_t o1 = (granule_slot(a1 >> 3) << 4) | ((a1 & 7u) << 1);
                     w[e >> 1] = o0 | (o1 << 16);
                 }
-                *reinterpret_cast<uint4*>(lds + g.out_off + (2u * (uint32_t)wave + j) * 1024u + 16u * (uint32_t)lane) =
+                *reinterpret_cast<uint4*>(lds + kBufStride + (2u * (uint32_t)wave + j) * 1024u + 16u * (uint32_t)lane) =
                     make_uint4(w[0], w[1], w[2], w[3]);
             }
         }
@@ -461,9 +497,40 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         if constexpr (kDouble) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
     }
     __syncthreads();
-    if (group_of(0) < ngroups) issue_loads(group_of(0), 0u);
-    if constexpr (kDouble) {
-        if (group_of(1) < ngroups) n_behind = issue_loads(group_of(1), kBufStride);
+    // ---- state of the run-time row schedule (D4K kernels; see the main loop) -----------------
+    constexpr uint32_t kQueues = kWorkQueues;
+    const uint32_t W = gridDim.x * NWAVES;
+    const uint32_t qid = (blockIdx.x >> 3) & (kQueues - 1u);
+    uint32_t* ctr = &work_ctr[g.ctr_set][qid][0];
+    const uint32_t T32 = (uint32_t)p.T;                       // the host sends at most 2^30 rows here
+    const uint32_t dyn0 = 2u * W + qid;
+    const uint32_t rows_q = T32 > dyn0 ? (T32 - dyn0 + kQueues - 1u) / kQueues : 0u;
+    const uint32_t last_ticket = rows_q + W / kQueues - 1u;
+    auto draw = [&]() -> uint32_t {
+        uint32_t t = 0;
+        if (lane == 0) t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return t;
+    };
+    // (d = 4096: wave w fills row slot w with 8 loads of 1 KiB; the swizzle of load k depends on
+    // k & 1 only, so two per-lane offsets serve all eight)
+    const uint32_t d4k_off0 = granule_slot((uint32_t)lane) * 16u;
+    const uint32_t d4k_off1 = granule_slot(64u + (uint32_t)lane) * 16u - 1024u;
+    auto load_row = [&](uint32_t row, uint32_t buf_off) {
+        const bool ok = row < (uint32_t)p.T;
+        const unsigned char* rp = xbytes + (ok ? (int64_t)row * ldx_bytes : 0);
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            __builtin_amdgcn_global_load_lds(rp + (ok ? k * 1024 : 0) + ((k & 1) ? d4k_off1 : d4k_off0),
+                                             lds + buf_off + (uint32_t)wave * 8192u + k * 1024, 16, 0, 2 /* nt */);
+    };
+    uint32_t row_cur = blockIdx.x * NWAVES + (uint32_t)wave, row_nxt = row_cur + W;
+    bool drawing = true;
+    uint32_t ticket = 0;
+    if constexpr (!D4K) {
+        if (group_of(0) < ngroups) issue_loads(group_of(0), 0u);
+        if constexpr (kDouble) {
+            if (group_of(1) < ngroups) n_behind = issue_loads(group_of(1), kBufStride);
+        }
     }
 
     // Shared case: collect the eight fragments of addresses the four waves have left in LDS.
@@ -474,7 +541,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             for (int q = 0; q < kQ; ++q) qvalid[q] = true;
 #pragma unroll
             for (int f = 0; f < 8; ++f) {
-                const uint4 t = *reinterpret_cast<const uint4*>(lds + g.out_off + (uint32_t)f * 1024u + 16u * (uint32_t)lane);
+                const uint4 t = *reinterpret_cast<const uint4*>(lds + kBufStride + (uint32_t)f * 1024u + 16u * (uint32_t)lane);
                 const uint32_t w[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
                 for (int e = 0; e < 8; e += 2) {
@@ -482,8 +549,13 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     src[f * 8 + e + 1] = base + (w[e >> 1] >> 16);
                 }
             }
-            __syncthreads();      // the table's place is the output staging of the first epilogue
+            __syncthreads();      // the table's place is about to be loaded over
         }
+    }
+    if constexpr (D4K) {
+        load_row(row_cur, 0u);
+        ticket = draw();
+        load_row(row_nxt, kBufStride);
     }
     // Otherwise every wave builds its own addresses (and reads `perm`) while the first row groups
     // are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued together
@@ -549,9 +621,56 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         }
     }
 
-    for (int it = 0; group_of(it) < ngroups; it += 2) {
-        do_group(it, std::integral_constant<uint32_t, 0>{});
-        if (group_of(it + 1) < ngroups) do_group(it + 1, std::integral_constant<uint32_t, 1>{});
+    if constexpr (!D4K) {
+        auto run = [&](int it, auto buf_const) {
+            constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
+            do_group(group_of(it) * g.rows + rr, buf_const, [&]() {
+                const int64_t nxt = group_of(it + (kDouble ? 2 : 1));
+                n_behind = nxt < ngroups ? issue_loads(nxt, kOff) : 0;
+            });
+        };
+        for (int it = 0; group_of(it) < ngroups; it += 2) {
+            run(it, std::integral_constant<uint32_t, 0>{});
+            if (group_of(it + 1) < ngroups) run(it + 1, std::integral_constant<uint32_t, 1>{});
+        }
+    } else {
+        // Rows dealt at run time.  The XCDs of the chip do not get equal shares of the memory
+        // bandwidth, and which of them falls behind changes from launch to launch; with a fixed
+        // split the launch lasts as long as the slowest one.  Every wave takes its first two rows
+        // by its index; every further row it draws from one of kQueues ticket counters (queue q
+        // owns rows 2W + q + kQueues * t, W = number of waves).  A queue is shared by workgroups
+        // 8k .. 8k+7 for two values of k, one per XCD each, so every queue balances across XCDs
+        // while one counter sees only 1/kQueues of the atomics (same-address atomics from
+        // different XCDs retire at roughly 90 per microsecond).  A ticket is drawn one iteration
+        // before it is needed, just ahead of the 8 loads of that iteration, so the wait at the top
+        // of the next iteration (all but the last 8 operations) covers it.  Loads are issued
+        // unconditionally (a wave out of rows re-reads the start of row 0) to keep that count fixed.
+        // A wave stops drawing at its first ticket past the end, so queue q hands out exactly
+        // rows_q + waves_q tickets per launch, and the wave that draws the last one puts the counter
+        // back to zero for the next launch.
+        auto run = [&](auto buf_const) {
+            constexpr uint32_t kOff = decltype(buf_const)::value * kBufStride;
+            const int64_t row = row_cur;
+            do_group(row, buf_const, [&]() {
+                uint32_t row_new = T32;
+                if (drawing) {
+                    const uint32_t t = __builtin_amdgcn_readfirstlane(ticket);
+                    if (t == last_ticket && lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    // (a ticket past the end may be large: saturate instead of wrapping)
+                    row_new = t < rows_q ? dyn0 + kQueues * t : T32;
+                    drawing = t < rows_q;
+                    if (drawing) ticket = draw();
+                }
+                load_row(row_new, kOff);
+                row_cur = row_nxt;
+                row_nxt = row_new;
+            });
+        };
+        while (row_cur < T32) {
+            run(std::integral_constant<uint32_t, 0>{});
+            if (row_cur < T32) run(std::integral_constant<uint32_t, 1>{});
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // the filler loads of the last two iterations
     }
 }
 
@@ -567,26 +686,48 @@ hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
     const uint32_t gpr = (uint32_t)p.d / 8u;
     g.nload = g.tiles_per_row == 1 ? (int)(gpr / 64u)
                                    : (int)((stage_bytes / 16u + NWAVES * 64u - 1u) / (NWAVES * 64u));
-    g.red_off = 65536u;                                 // staging (incl. the zero slot) ends here
-    g.out_off = g.red_off + 32u * sizeof(float);
-    const uint32_t lds_bytes = g.out_off + NWAVES * 2048u;
+    const uint32_t lds_bytes = 65536u;                  // dynamic part: the staging buffers (incl. the zero slot)
+    g.ctr_set = 0;
 
+    const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
+    // The d = 4096 variant wants four-wave workgroups in multiples of 256 (its ticket queues are
+    // dealt by workgroup index) and at least two rows per wave.
+    auto grid_of = [&](const void* k, int64_t* grid) -> hipError_t {
+        int per_cu = 0;
+        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k, NWAVES * 64, lds_bytes);
+        if (e != hipSuccess) return e;
+        if (per_cu < 1) per_cu = 1;
+        *grid = (int64_t)launch_info().num_cus * per_cu;
+        if (*grid > ngroups) *grid = ngroups;
+        return hipSuccess;
+    };
     auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
+    int64_t grid = 0;
+    bool picked = false;
     if constexpr (NWAVES == 4) {
-        if (p.perm && p.d == kTile) kern = mfma_kernel<OUT, true, NWAVES, STAGES, true>;
+        if (p.d == kTile) {
+            auto k4 = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, true> : mfma_kernel<OUT, false, NWAVES, STAGES, true>;
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k4),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+            e = grid_of(reinterpret_cast<const void*>(k4), &grid);
+            if (e != hipSuccess) return e;
+            if (grid % 256 == 0 && p.T >= 2 * grid * NWAVES && p.T <= (int64_t)1 << 30) {
+                static std::atomic<uint32_t> launch_seq{0};
+                g.ctr_set = launch_seq.fetch_add(1, std::memory_order_relaxed) % kWorkSets;
+                kern = k4;
+                picked = true;
+            }
+        }
     }
-    if (lds_bytes > 64u * 1024u) {
+    if (!picked) {
+        // (static and dynamic LDS together pass 64 KiB)
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
+        e = grid_of(reinterpret_cast<const void*>(kern), &grid);
+        if (e != hipSuccess) return e;
     }
-    int per_cu = 0;
-    hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NWAVES * 64, lds_bytes);
-    if (oe != hipSuccess) return oe;
-    if (per_cu < 1) per_cu = 1;
-    const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
-    int64_t grid = (int64_t)launch_info().num_cus * per_cu;
-    if (grid > ngroups) grid = ngroups;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NWAVES * 64), lds_bytes, stream, p, g);
     return hipGetLastError();
 }
