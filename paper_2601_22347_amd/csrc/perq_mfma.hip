@@ -49,7 +49,8 @@ struct MfmaGeom {
     int rows;            // rows per workgroup iteration = waves / tiles_per_row
     int nload;           // direct-to-LDS load instructions per lane per iteration
     uint32_t row_bytes;  // d * 2
-    uint32_t ctr_set;    // which set of ticket counters this launch draws from (D4K kernels)
+    uint32_t ctr_set;    // which set of ticket counters this launch draws from
+    uint32_t dynamic;    // 1: units dealt at run time through the ticket counters; 0: fixed stride
 };
 
 // Ticket counters of the run-time row schedule: kWorkSets sets (consecutive launches rotate through
@@ -58,6 +59,7 @@ struct MfmaGeom {
 constexpr uint32_t kWorkQueues = 32;
 constexpr uint32_t kWorkSets = 64;
 __device__ uint32_t work_ctr[kWorkSets][kWorkQueues][64];
+std::atomic<uint32_t> launch_seq{0};     // host side: launches of this process so far
 
 // granule -> slot inside a row (an involution: bits 4..6 select the xor pattern for bits 0..2)
 __device__ __forceinline__ uint32_t granule_slot(uint32_t g) {
@@ -95,18 +97,22 @@ __device__ __forceinline__ void lds_load16x2(const void* p0, const void* p1, uin
     v0 = make_uint4(a.x, a.y, a.z, a.w);
     v1 = make_uint4(b.x, b.y, b.z, b.w);
 }
+__device__ __forceinline__ uint32_t lds_load4(const void* p) {
+    uint32_t v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr(p)) : "memory");
+    return v;
+}
 __device__ __forceinline__ void workgroup_barrier_lds() {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 // STAGES = number of +-1 butterfly stages after the matrix product: log2(b) - 5, 0 for b <= 32.
 // A template parameter so that the accumulators stay in registers along one straight path.
-// D4K: the variant for d = 4096 exactly (one full tile per row, every wave on rows of its own) and
-// enough rows to go round.  With a permutation the four waves of a workgroup build one table of
-// operand addresses together, and the rows are dealt to the waves at run time (see below).
-template <int OUT, bool PERM, int NWAVES, int STAGES, bool D4K>
+// SHARED: d = 4096 exactly with a permutation: the four waves of a workgroup, each on whole rows of
+// its own, build one table of operand addresses together (see below).
+template <int OUT, bool PERM, int NWAVES, int STAGES, bool SHARED>
 // (two 4-wave workgroups fit a CU's LDS, so the register budget is that of 2 waves per SIMD)
-__global__ void __launch_bounds__(NWAVES * 64, NWAVES == 4 ? 2 : 1)
+__global__ void __launch_bounds__(NWAVES * 64, NWAVES == 4 ? 2 : 1) __attribute__((amdgpu_num_vgpr(248)))
 mfma_kernel(ApplyParams p, MfmaGeom g) {
     // The dynamic array holds nothing but the row staging buffers, the targets of the
     // direct-to-LDS loads.  Everything the kernel writes to LDS with ordinary stores lives in
@@ -115,6 +121,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     extern __shared__ __align__(16) unsigned char lds[];
     __shared__ __align__(16) unsigned char out_stage[NWAVES * 2048];   // per-wave output staging
     __shared__ float red_scratch[32];                                  // row maxima across waves
+    __shared__ uint32_t unit_box[1];                                   // next unit of the workgroup
     // Two staging buffers when a row group fits 32 KiB (4 waves): the loads of the next group are
     // in flight during the whole of the current one.  The buffer is selected by a compile-time
     // offset on the LDS instructions (loop unrolled by two).  8-wave groups use one buffer.
@@ -131,7 +138,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     int tile_len = d - tile_base;
     tile_len = tile_len < 0 ? 0 : (tile_len > kTile ? kTile : tile_len);
     // one tile per row: every wave stages and consumes its own row, no workgroup barrier needed
-    const bool wave_local = D4K || g.tiles_per_row == 1;
+    const bool wave_local = SHARED || g.tiles_per_row == 1;
 
     // ---- A operand: rows sigma(i) of the +-1 matrix, two K steps of 16 ---------------------
     // high-K mode (b >= 1024): the constant is the B operand, column j = lane & 31 unpermuted
@@ -175,9 +182,6 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
     for (int k = 0; k < 5; ++k) sgn[k] = (c >> k) & 1 ? -1.0f : 1.0f;
 
-    const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
-    // Static schedule: the workgroup's it-th row group.
-    auto group_of = [&](int it) -> int64_t { return (int64_t)it * gridDim.x + blockIdx.x; };
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
 
     // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  In wave-local
@@ -208,12 +212,13 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     }
     const unsigned char* xbytes = reinterpret_cast<const unsigned char*>(p.x);
     const int64_t ldx_bytes = p.ldx * 2;
-    auto issue_loads = [&](int64_t grp, uint32_t buf_off) -> int {
+    // unit = what one worker takes at a time: a row for a wave on rows of its own, else a row group
+    // of the workgroup
+    auto issue_loads = [&](uint32_t unit, uint32_t buf_off) -> int {
         int issued = 0;
-        const int64_t row0 = grp * g.rows;
 #pragma unroll
         for (int k = 0; k < kMaxLoad; ++k) {
-            const int64_t row = row0 + ld_rslot[k];
+            const int64_t row = wave_local ? (int64_t)unit : (int64_t)unit * g.rows + ld_rslot[k];
             if (ld_rslot[k] >= 0 && row < p.T) {
                 __builtin_amdgcn_global_load_lds(xbytes + row * ldx_bytes + ld_lane_off[k],
                                                  lds + buf_off + ld_lds[k], 16, 0, 2 /* nt */);
@@ -245,20 +250,72 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             default: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
         }
     };
-    // Loads of the group after the current one, already in flight.  (The stores issued in between
-    // are not counted: that only makes the wait stricter, and counting them measured no faster.)
+    // Loads issued after those of the unit about to be consumed.  (The stores issued in between are
+    // not counted: that only makes the wait stricter, and counting them measured no faster.)
     int n_behind = 0;
 
-    // ---- one row group out of staging buffer BUF -------------------------------------------
-    // `row` is this wave's row of the group; `refill` issues the loads that reuse the buffer.
-    auto do_group = [&](int64_t row, auto buf_const, auto&& refill) {
+    // ---- schedule ----------------------------------------------------------------------------
+    // The XCDs of the chip do not get equal shares of the memory bandwidth, and which of them falls
+    // behind changes from launch to launch; with a fixed split the launch lasts as long as the
+    // slowest one.  So, given enough units, only the first two of every worker are fixed (worker w
+    // takes w and w + W); every further unit is drawn from one of kWorkQueues ticket counters
+    // (queue q owns units 2W + q + kWorkQueues * t).  A queue is shared by the workgroups 8k .. 8k+7
+    // for a few k, one per XCD each, so every queue balances across XCDs, while one counter sees
+    // only 1/kWorkQueues of the atomics (same-address atomics from different XCDs retire at roughly
+    // 90 per microsecond).
+    //   A ticket is drawn right before the loads of an iteration are issued and read at the end of
+    // that iteration, after the wait that leaves only those loads outstanding: vector-memory
+    // operations retire in order, so the wait covers the atomic, and the ticket comes for free.
+    // The atomic is written as an instruction with its result in v255, a register the compiler is
+    // told nothing about and cannot allocate (the kernel is limited to 248 VGPRs): its own atomic
+    // would wait for everything in flight, and a result it knew of it might move while pending.
+    //   A worker stops drawing at its first ticket past the end, so queue q hands out exactly
+    // units_q + workers_q tickets per launch; whoever draws the last one puts the counter back to
+    // zero for the next launch.
+    const bool dyn = g.dynamic != 0;
+    const uint32_t unit_rows = wave_local ? 1u : (uint32_t)g.rows;
+    const uint32_t n_workers = wave_local ? gridDim.x * NWAVES : gridDim.x;
+    const uint32_t worker = wave_local ? blockIdx.x * NWAVES + (uint32_t)wave : blockIdx.x;
+    const uint32_t n_units = (uint32_t)((p.T + unit_rows - 1) / unit_rows);      // (T < 2^31 here)
+    const uint32_t qid = (blockIdx.x >> 3) & (kWorkQueues - 1u);
+    const uint32_t dyn0 = 2u * n_workers + qid;
+    const uint32_t units_q = n_units > dyn0 ? (n_units - dyn0 + kWorkQueues - 1u) / kWorkQueues : 0u;
+    const uint32_t last_ticket = units_q + n_workers / kWorkQueues - 1u;
+    uint32_t* ctr = &work_ctr[g.ctr_set][qid][0];
+    bool drawing = dyn && (wave_local || wave == 0);     // one wave draws for a workgroup
+    uint32_t own_next = 2;                               // fixed stride: place in the worker's own sequence
+    auto draw = [&]() {
+        if (lane == 0) asm volatile("global_atomic_add v255, %0, %1, off sc0" ::"v"(ctr), "v"(1u) : "v255", "memory");
+    };
+    // the worker's next unit (n_units: none); call once per iteration, after the wait
+    auto fetch_next = [&]() -> uint32_t {
+        if (dyn) {
+            if (!drawing) return n_units;
+            uint32_t t;
+            asm volatile("v_readfirstlane_b32 %0, v255" : "=s"(t)::"memory");
+            if (t == last_ticket && lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t < units_q) return dyn0 + kWorkQueues * t;
+            drawing = false;
+            return n_units;
+        }
+        const uint32_t u = worker + own_next * n_workers;
+        ++own_next;
+        return u < n_units ? u : n_units;
+    };
+    const bool boxed = dyn && !wave_local;               // the drawing wave passes the unit on through LDS
+    uint32_t u_cur = worker, u_nxt = worker + n_workers, u_new = n_units;
+
+    // ---- one unit out of staging buffer BUF --------------------------------------------------
+    // On entry the unit's loads have landed (waited for at the end of the iteration before).
+    auto body = [&](auto buf_const) {
         constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
+        const int64_t row = wave_local ? (int64_t)u_cur : (int64_t)u_cur * g.rows + rr;
         const bool row_live = row < p.T;
 
-        // this wave's direct-to-LDS loads of the group have landed
-        if constexpr (D4K) __builtin_amdgcn_s_waitcnt(0x0F78);     // all but the 8 loads behind it
-        else wait_vm_le(kDouble ? n_behind : 0);
-        if (!wave_local) workgroup_barrier_lds();
+        if (!wave_local) {
+            workgroup_barrier_lds();
+            if (boxed) u_new = __builtin_amdgcn_readfirstlane(lds_load4(unit_box));   // (uniform: keep it scalar)
+        }
 
         // ---- B operands out of LDS ----------------------------------------------------------
         uint4 bfrag[kQ][2];
@@ -281,9 +338,13 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             }
         }
         // The operands are in registers: refill this buffer right away.  With two buffers the
-        // group after next goes here, so two groups of loads are in flight during the arithmetic.
+        // unit after next goes here, so two units' loads are in flight during the arithmetic.
         if (!wave_local) workgroup_barrier_lds();
-        refill();
+        {
+            const uint32_t u_load = kDouble ? u_new : u_nxt;
+            if (drawing) draw();
+            n_behind = u_load < n_units ? issue_loads(u_load, kOff) : 0;
+        }
 
         // ---- the matrix product ------------------------------------------------------------------
         float v[64];
@@ -446,6 +507,13 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 }
             }
         }
+
+        // ---- the next unit's loads have landed, and the ticket with them -----------------------
+        wait_vm_le(kDouble ? n_behind : 0);
+        u_cur = u_nxt;
+        u_nxt = u_new;
+        u_new = fetch_next();
+        if (boxed && wave == 0 && lane == 0) lds_store4(unit_box, __uint_as_float(u_new));
     };
 
     // Operand addresses through `perm`, shared case: when every wave of the workgroup owns a whole
@@ -456,9 +524,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // barrier below every lane collects its eight fragments.  All of this comes before the first
     // row loads: nothing queues behind those, and no ordinary LDS access meets a pending
     // direct-to-LDS load.
-    constexpr bool SHARED = D4K && PERM;
     constexpr bool shared_src = SHARED;
-    static_assert(!D4K || NWAVES == 4, "d = 4096 runs on four-wave workgroups");
+    static_assert(!SHARED || (PERM && NWAVES == 4), "the shared table is for four waves with the same tile");
     if constexpr (SHARED) {
         {
             uint32_t ch[16];
@@ -497,41 +564,12 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         if constexpr (kDouble) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
     }
     __syncthreads();
-    // ---- state of the run-time row schedule (D4K kernels; see the main loop) -----------------
-    constexpr uint32_t kQueues = kWorkQueues;
-    const uint32_t W = gridDim.x * NWAVES;
-    const uint32_t qid = (blockIdx.x >> 3) & (kQueues - 1u);
-    uint32_t* ctr = &work_ctr[g.ctr_set][qid][0];
-    const uint32_t T32 = (uint32_t)p.T;                       // the host sends at most 2^30 rows here
-    const uint32_t dyn0 = 2u * W + qid;
-    const uint32_t rows_q = T32 > dyn0 ? (T32 - dyn0 + kQueues - 1u) / kQueues : 0u;
-    const uint32_t last_ticket = rows_q + W / kQueues - 1u;
-    auto draw = [&]() -> uint32_t {
-        uint32_t t = 0;
-        if (lane == 0) t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return t;
+    auto first_loads = [&]() {
+        if (u_cur < n_units) issue_loads(u_cur, 0u);
+        if (drawing) draw();
+        if constexpr (kDouble) n_behind = u_nxt < n_units ? issue_loads(u_nxt, kBufStride) : 0;
     };
-    // (d = 4096: wave w fills row slot w with 8 loads of 1 KiB; the swizzle of load k depends on
-    // k & 1 only, so two per-lane offsets serve all eight)
-    const uint32_t d4k_off0 = granule_slot((uint32_t)lane) * 16u;
-    const uint32_t d4k_off1 = granule_slot(64u + (uint32_t)lane) * 16u - 1024u;
-    auto load_row = [&](uint32_t row, uint32_t buf_off) {
-        const bool ok = row < (uint32_t)p.T;
-        const unsigned char* rp = xbytes + (ok ? (int64_t)row * ldx_bytes : 0);
-#pragma unroll
-        for (int k = 0; k < 8; ++k)
-            __builtin_amdgcn_global_load_lds(rp + (ok ? k * 1024 : 0) + ((k & 1) ? d4k_off1 : d4k_off0),
-                                             lds + buf_off + (uint32_t)wave * 8192u + k * 1024, 16, 0, 2 /* nt */);
-    };
-    uint32_t row_cur = blockIdx.x * NWAVES + (uint32_t)wave, row_nxt = row_cur + W;
-    bool drawing = true;
-    uint32_t ticket = 0;
-    if constexpr (!D4K) {
-        if (group_of(0) < ngroups) issue_loads(group_of(0), 0u);
-        if constexpr (kDouble) {
-            if (group_of(1) < ngroups) n_behind = issue_loads(group_of(1), kBufStride);
-        }
-    }
+    if constexpr (!SHARED) first_loads();
 
     // Shared case: collect the eight fragments of addresses the four waves have left in LDS.
     if constexpr (SHARED) {
@@ -552,11 +590,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             __syncthreads();      // the table's place is about to be loaded over
         }
     }
-    if constexpr (D4K) {
-        load_row(row_cur, 0u);
-        ticket = draw();
-        load_row(row_nxt, kBufStride);
-    }
+    if constexpr (SHARED) first_loads();
     // Otherwise every wave builds its own addresses (and reads `perm`) while the first row groups
     // are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued together
     // (absent sub-blocks re-read position 0 and are redirected to the zero slot).
@@ -621,56 +655,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         }
     }
 
-    if constexpr (!D4K) {
-        auto run = [&](int it, auto buf_const) {
-            constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
-            do_group(group_of(it) * g.rows + rr, buf_const, [&]() {
-                const int64_t nxt = group_of(it + (kDouble ? 2 : 1));
-                n_behind = nxt < ngroups ? issue_loads(nxt, kOff) : 0;
-            });
-        };
-        for (int it = 0; group_of(it) < ngroups; it += 2) {
-            run(it, std::integral_constant<uint32_t, 0>{});
-            if (group_of(it + 1) < ngroups) run(it + 1, std::integral_constant<uint32_t, 1>{});
-        }
-    } else {
-        // Rows dealt at run time.  The XCDs of the chip do not get equal shares of the memory
-        // bandwidth, and which of them falls behind changes from launch to launch; with a fixed
-        // split the launch lasts as long as the slowest one.  Every wave takes its first two rows
-        // by its index; every further row it draws from one of kQueues ticket counters (queue q
-        // owns rows 2W + q + kQueues * t, W = number of waves).  A queue is shared by workgroups
-        // 8k .. 8k+7 for two values of k, one per XCD each, so every queue balances across XCDs
-        // while one counter sees only 1/kQueues of the atomics (same-address atomics from
-        // different XCDs retire at roughly 90 per microsecond).  A ticket is drawn one iteration
-        // before it is needed, just ahead of the 8 loads of that iteration, so the wait at the top
-        // of the next iteration (all but the last 8 operations) covers it.  Loads are issued
-        // unconditionally (a wave out of rows re-reads the start of row 0) to keep that count fixed.
-        // A wave stops drawing at its first ticket past the end, so queue q hands out exactly
-        // rows_q + waves_q tickets per launch, and the wave that draws the last one puts the counter
-        // back to zero for the next launch.
-        auto run = [&](auto buf_const) {
-            constexpr uint32_t kOff = decltype(buf_const)::value * kBufStride;
-            const int64_t row = row_cur;
-            do_group(row, buf_const, [&]() {
-                uint32_t row_new = T32;
-                if (drawing) {
-                    const uint32_t t = __builtin_amdgcn_readfirstlane(ticket);
-                    if (t == last_ticket && lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    // (a ticket past the end may be large: saturate instead of wrapping)
-                    row_new = t < rows_q ? dyn0 + kQueues * t : T32;
-                    drawing = t < rows_q;
-                    if (drawing) ticket = draw();
-                }
-                load_row(row_new, kOff);
-                row_cur = row_nxt;
-                row_nxt = row_new;
-            });
-        };
-        while (row_cur < T32) {
-            run(std::integral_constant<uint32_t, 0>{});
-            if (row_cur < T32) run(std::integral_constant<uint32_t, 1>{});
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // the filler loads of the last two iterations
+    // the first unit has landed; the ticket drawn behind its loads says which unit comes third
+    wait_vm_le(kDouble ? n_behind : 0);
+    u_new = fetch_next();
+    if (boxed && wave == 0 && lane == 0) lds_store4(unit_box, __uint_as_float(u_new));
+
+    while (u_cur < n_units) {
+        body(std::integral_constant<uint32_t, 0>{});
+        if (u_cur < n_units) body(std::integral_constant<uint32_t, 1>{});
     }
 }
 
@@ -688,45 +680,33 @@ hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
                                    : (int)((stage_bytes / 16u + NWAVES * 64u - 1u) / (NWAVES * 64u));
     const uint32_t lds_bytes = 65536u;                  // dynamic part: the staging buffers (incl. the zero slot)
     g.ctr_set = 0;
+    g.dynamic = 0;
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
-    // The d = 4096 variant wants four-wave workgroups in multiples of 256 (its ticket queues are
-    // dealt by workgroup index) and at least two rows per wave.
-    auto grid_of = [&](const void* k, int64_t* grid) -> hipError_t {
-        int per_cu = 0;
-        hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k, NWAVES * 64, lds_bytes);
-        if (e != hipSuccess) return e;
-        if (per_cu < 1) per_cu = 1;
-        *grid = (int64_t)launch_info().num_cus * per_cu;
-        if (*grid > ngroups) *grid = ngroups;
-        return hipSuccess;
-    };
     auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
-    int64_t grid = 0;
-    bool picked = false;
     if constexpr (NWAVES == 4) {
-        if (p.d == kTile) {
-            auto k4 = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, true> : mfma_kernel<OUT, false, NWAVES, STAGES, true>;
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k4),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-            if (e != hipSuccess) return e;
-            e = grid_of(reinterpret_cast<const void*>(k4), &grid);
-            if (e != hipSuccess) return e;
-            if (grid % 256 == 0 && p.T >= 2 * grid * NWAVES && p.T <= (int64_t)1 << 30) {
-                static std::atomic<uint32_t> launch_seq{0};
-                g.ctr_set = launch_seq.fetch_add(1, std::memory_order_relaxed) % kWorkSets;
-                kern = k4;
-                picked = true;
-            }
-        }
+        if (p.perm && p.d == kTile) kern = mfma_kernel<OUT, true, NWAVES, STAGES, true>;
     }
-    if (!picked) {
-        // (static and dynamic LDS together pass 64 KiB)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        e = grid_of(reinterpret_cast<const void*>(kern), &grid);
-        if (e != hipSuccess) return e;
+    // (static and dynamic LDS together pass 64 KiB)
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    int per_cu = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NWAVES * 64, lds_bytes);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) per_cu = 1;
+    int64_t grid = (int64_t)launch_info().num_cus * per_cu;
+    if (grid > ngroups) grid = ngroups;
+    // Units are dealt at run time when every worker (a wave on rows of its own, else a workgroup)
+    // gets at least its two fixed ones and the workgroups fill the ticket queues evenly.
+    {
+        const bool wave_local = g.tiles_per_row == 1;
+        const int64_t workers = wave_local ? grid * NWAVES : grid;
+        const int64_t units = wave_local ? p.T : ngroups;
+        g.dynamic = (grid % (8 * kWorkQueues) == 0 && units >= 2 * workers) ? 1u : 0u;
+        if (g.dynamic) {
+            g.ctr_set = launch_seq.fetch_add(1, std::memory_order_relaxed) % kWorkSets;
+        }
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NWAVES * 64), lds_bytes, stream, p, g);
     return hipGetLastError();
@@ -748,7 +728,9 @@ hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
 
 }  // namespace
 
-bool mfma_supports(const ApplyParams& p) { return p.b <= kTile && p.d % 512 == 0 && p.d <= 32768; }
+bool mfma_supports(const ApplyParams& p) {
+    return p.b <= kTile && p.d % 512 == 0 && p.d <= 32768 && p.T < ((int64_t)1 << 31);   // (32-bit unit numbers)
+}
 
 hipError_t launch_mfma(const ApplyParams& p, int out_kind, hipStream_t stream) {
     const bool wide = p.d > 4 * kTile;        // up to 8 tiles per row -> 8 waves

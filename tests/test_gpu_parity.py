@@ -209,3 +209,49 @@ def test_colabs_mean(M, d):
     const = synth.f64_to_bf16_bits(np.sign(rng.standard_normal((M, d))) * (1 + np.arange(d) % 7))
     got = binding.perq_colabs_mean(binding.bits_to_device(const)).cpu().numpy()
     assert np.array_equal(got, (1 + np.arange(d) % 7).astype(np.float32))
+
+
+# ---- enough rows for the run-time schedule of the matrix-core kernel --------------------------
+# With at least two units per worker (a wave for d <= 4096, else a workgroup) the kernel deals its
+# rows through ticket counters; every row is checked against the oracle, ragged tails included.
+DYNAMIC_SHAPES = [
+    # (T, d, b, fmt, perm)
+    (4099, 4096, 128, "int4", True),      # a wave per row, shared address table
+    (4099, 4096, 32, "mxfp4", False),
+    (4500, 4096, 4096, "int4", True),
+    (4611, 2048, 64, "mxfp4", True),      # a wave per row, half tiles
+    (2051, 8192, 32, "mxfp4", True),      # two rows per workgroup
+    (1030, 14336, 128, "int4", True),     # one row per workgroup, ragged last tile, row maximum across waves
+    (1030, 14336, 2048, "int4", False),
+    (530, 20480, 1024, "int4", True),     # eight-wave workgroups, one staging buffer
+]
+
+
+@pytest.mark.parametrize("T,d,b,fmt,with_perm", DYNAMIC_SHAPES)
+def test_run_time_schedule_all_rows(T, d, b, fmt, with_perm):
+    rng = np.random.default_rng(T + d + b)
+    x = synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d)) * np.exp(rng.uniform(-2, 2, size=(T, 1))))
+    perm = rng.permutation(d).astype(np.int32) if with_perm else None
+    print(f"[case] run-time schedule T={T} d={d} b={b} fmt={fmt} perm={with_perm}", flush=True)
+    codes, scales, _ = run_gpu(x, perm, b, fmt, "mfma", want_y=False)
+    rep = parity.compare_apply(x, perm, b, fmt, codes, scales, None)
+    print("       ", rep.summary(), flush=True)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
+
+
+def test_run_time_schedule_counters_come_back_to_zero():
+    """More launches in a row than there are sets of ticket counters: a counter that a launch
+    left non-zero would hand the next user of its set the wrong rows."""
+    torch = _torch()
+    T, d = 4200, 4096
+    rng = np.random.default_rng(99)
+    x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_normal((T, d))))
+    perm = torch.from_numpy(rng.permutation(d).astype(np.int32)).cuda()
+    ref = None
+    for i in range(150):
+        codes, scales = binding.perq_permute_rotate_quant(x, perm, 128, "int4", algo="mfma")
+        if ref is None:
+            ref = (codes.clone(), scales.clone())
+        elif i % 10 == 9 or i >= 140:
+            assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"launch {i} differs"
+    torch.cuda.synchronize()
