@@ -184,48 +184,50 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
 
-    // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  In wave-local
-    // mode wave w fills row slot w, otherwise the instructions are dealt round-robin to the waves.
-    // Everything but the row number is fixed for the launch: per instruction k a per-lane byte
-    // offset inside the row (the swizzle lives here) and a uniform LDS offset and row slot.
+    // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  On rows of its
+    // own, wave w fills row slot w; otherwise the instructions are dealt round-robin to the waves
+    // (a row group is then one or two rows).  Everything but the unit is fixed for the launch: per
+    // instruction k a per-lane byte offset from the unit's first row (the swizzle lives here, and
+    // the row stride for a load of the second row), an LDS offset lds_base0 + k * lds_stride, and
+    // two bit masks saying which k belong to the first and to the second row.
     constexpr int kMaxLoad = 8;
     uint32_t ld_lane_off[kMaxLoad];
-    uint32_t ld_lds[kMaxLoad];
-    int ld_rslot[kMaxLoad];
+    uint32_t mask_row0 = 0, mask_row1 = 0;
+    const uint32_t lds_base0 = wave_local ? (uint32_t)wave * g.row_bytes : (uint32_t)wave * 1024u;
+    const uint32_t lds_stride = wave_local ? 1024u : NWAVES * 1024u;
 #pragma unroll
     for (int k = 0; k < kMaxLoad; ++k) {
-        uint32_t s0, rslot;
+        uint32_t in_row, rslot;
         bool ok;
         if (wave_local) {
-            rslot = (uint32_t)wave;
-            s0 = rslot * gpr + (uint32_t)k * 64u;
-            ok = (uint32_t)k * 64u < gpr;
+            rslot = 0;
+            in_row = (uint32_t)k * 64u;
+            ok = in_row < gpr;
         } else {
-            s0 = (uint32_t)(k * NWAVES + wave) * 64u;
+            const uint32_t s0 = (uint32_t)(k * NWAVES + wave) * 64u;
             rslot = s0 / gpr;
+            in_row = s0 - rslot * gpr;
             ok = rslot < (uint32_t)g.rows;
         }
         ok = ok && k < g.nload;
-        ld_rslot[k] = ok ? (int)rslot : -1;
-        ld_lds[k] = s0 * 16u;
-        ld_lane_off[k] = granule_slot(s0 - rslot * gpr + (uint32_t)lane) * 16u;
+        ld_lane_off[k] = granule_slot(in_row + (uint32_t)lane) * 16u + rslot * (uint32_t)(p.ldx * 2);
+        if (ok) (rslot == 0 ? mask_row0 : mask_row1) |= 1u << k;
     }
     const unsigned char* xbytes = reinterpret_cast<const unsigned char*>(p.x);
     const int64_t ldx_bytes = p.ldx * 2;
     // unit = what one worker takes at a time: a row for a wave on rows of its own, else a row group
     // of the workgroup
     auto issue_loads = [&](uint32_t unit, uint32_t buf_off) -> int {
-        int issued = 0;
+        const int64_t row0 = wave_local ? (int64_t)unit : (int64_t)unit * g.rows;
+        const unsigned char* rp = xbytes + row0 * ldx_bytes;
+        const uint32_t m = row0 + 1 < p.T ? (mask_row0 | mask_row1) : mask_row0;
 #pragma unroll
         for (int k = 0; k < kMaxLoad; ++k) {
-            const int64_t row = wave_local ? (int64_t)unit : (int64_t)unit * g.rows + ld_rslot[k];
-            if (ld_rslot[k] >= 0 && row < p.T) {
-                __builtin_amdgcn_global_load_lds(xbytes + row * ldx_bytes + ld_lane_off[k],
-                                                 lds + buf_off + ld_lds[k], 16, 0, 2 /* nt */);
-                ++issued;
-            }
+            if ((m >> k) & 1u)
+                __builtin_amdgcn_global_load_lds(rp + ld_lane_off[k], lds + buf_off + lds_base0 + (uint32_t)k * lds_stride,
+                                                 16, 0, 2 /* nt */);
         }
-        return issued;
+        return __builtin_popcount(m);
     };
 
     // Wait until at most n of this wave's vector-memory operations are outstanding.  They retire
@@ -729,7 +731,8 @@ hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
 }  // namespace
 
 bool mfma_supports(const ApplyParams& p) {
-    return p.b <= kTile && p.d % 512 == 0 && p.d <= 32768 && p.T < ((int64_t)1 << 31);   // (32-bit unit numbers)
+    // (32-bit unit numbers and row strides)
+    return p.b <= kTile && p.d % 512 == 0 && p.d <= 32768 && p.T < ((int64_t)1 << 31) && p.ldx < ((int64_t)1 << 30);
 }
 
 hipError_t launch_mfma(const ApplyParams& p, int out_kind, hipStream_t stream) {
