@@ -44,8 +44,12 @@ def algorithmic_bytes(T: int, d: int, fmt: str) -> int:
     return T * d * 2 + T * d // 2 + scales
 
 
-def read_traffic(name: str):
+def read_traffic(name: str, algo: str = "auto", identity: bool = False):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    if identity:
+        name = name.replace("_perm", "_identity")
+    if algo == "butterfly":
+        name += "_butterfly"
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
     if not os.path.exists(path):
         return None
@@ -202,7 +206,7 @@ def main() -> int:
                    "perm": "greedy-calibrated, gather fused" if use_perm else "identity",
                    "algo": args.algo, "buffer_sets": nsets, "input_gen_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload, args.algo, args.identity),
                      "algorithmic_bytes": alg_bytes, "kernel_ms": kern_ms},
         "cpu_baseline": cpu,
         "calibration": calib,
