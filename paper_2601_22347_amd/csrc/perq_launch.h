@@ -17,6 +17,8 @@ const LaunchInfo& launch_info();
 // Kernel families behind perq_permute_rotate_quant / perq_permute_rotate_f32.
 hipError_t launch_butterfly(const ApplyParams& p, int out_kind, hipStream_t stream);
 bool mfma_supports(const ApplyParams& p);
+// Whether the matrix-core kernel is the faster of the two for this call (measured crossovers).
+bool mfma_preferred(const ApplyParams& p, int out_kind);
 hipError_t launch_mfma(const ApplyParams& p, int out_kind, hipStream_t stream);
 
 }  // namespace perq

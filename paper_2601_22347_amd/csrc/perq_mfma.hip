@@ -51,6 +51,7 @@ struct MfmaGeom {
     uint32_t row_bytes;  // d * 2
     uint32_t ctr_set;    // which set of ticket counters this launch draws from
     uint32_t dynamic;    // 1: units dealt at run time through the ticket counters; 0: fixed stride
+    uint32_t fold_mask;  // rows folded into 4096-wide ones: width of a real row - 1; else all ones
 };
 
 // Ticket counters of the run-time row schedule: kWorkSets sets (consecutive launches rotate through
@@ -536,13 +537,17 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 const uint32_t f = 2u * (uint32_t)wave + j;
                 if constexpr (!kHighK) {
                     const uint32_t pos = ((uint32_t)c * kQ + (f >> 1)) * 32u + 16u * (f & 1u) + 8u * h;
-                    const int4 e0 = *reinterpret_cast<const int4*>(p.perm + pos);
-                    const int4 e1 = *reinterpret_cast<const int4*>(p.perm + pos + 4);
-                    ch[8 * j + 0] = e0.x; ch[8 * j + 1] = e0.y; ch[8 * j + 2] = e0.z; ch[8 * j + 3] = e0.w;
-                    ch[8 * j + 4] = e1.x; ch[8 * j + 5] = e1.y; ch[8 * j + 6] = e1.z; ch[8 * j + 7] = e1.w;
+                    const int4 e0 = *reinterpret_cast<const int4*>(p.perm + (pos & g.fold_mask));
+                    const int4 e1 = *reinterpret_cast<const int4*>(p.perm + (pos & g.fold_mask) + 4);
+                    const uint32_t fb = pos & ~g.fold_mask;          // first channel of the real row
+                    ch[8 * j + 0] = fb + e0.x; ch[8 * j + 1] = fb + e0.y; ch[8 * j + 2] = fb + e0.z; ch[8 * j + 3] = fb + e0.w;
+                    ch[8 * j + 4] = fb + e1.x; ch[8 * j + 5] = fb + e1.y; ch[8 * j + 6] = fb + e1.z; ch[8 * j + 7] = fb + e1.w;
                 } else {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) ch[8 * j + e] = (uint32_t)p.perm[32u * (16u * f + 8u * h + e) + sigma_i];
+                    for (int e = 0; e < 8; ++e) {
+                        const uint32_t pos = 32u * (16u * f + 8u * h + e) + sigma_i;
+                        ch[8 * j + e] = (uint32_t)p.perm[pos & g.fold_mask] + (pos & ~g.fold_mask);
+                    }
                 }
             }
 #pragma unroll
@@ -608,7 +613,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             for (int kt = 0; kt < 2; ++kt) {
                 const uint32_t pos = (uint32_t)tile_base + (uint32_t)sb * 32u + 16u * kt + 8u * h;
                 if constexpr (PERM) {
-                    const int32_t* pp = p.perm + (qvalid[q] ? pos : 0u);
+                    const int32_t* pp = p.perm + (qvalid[q] ? (pos & g.fold_mask) : 0u);
                     pe[q * 2 + kt][0] = *reinterpret_cast<const int4*>(pp);
                     pe[q * 2 + kt][1] = *reinterpret_cast<const int4*>(pp + 4);
                 } else {
@@ -620,8 +625,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
             for (int f = 0; f < kQ * 2; ++f) {
                 const int4 e0 = pe[f][0], e1 = pe[f][1];
-                const uint32_t ch[8] = {(uint32_t)e0.x, (uint32_t)e0.y, (uint32_t)e0.z, (uint32_t)e0.w,
-                                        (uint32_t)e1.x, (uint32_t)e1.y, (uint32_t)e1.z, (uint32_t)e1.w};
+                const uint32_t fb = ((uint32_t)tile_base + ((uint32_t)c * kQ + (f >> 1)) * 32u) & ~g.fold_mask;
+                const uint32_t ch[8] = {fb + e0.x, fb + e0.y, fb + e0.z, fb + e0.w, fb + e1.x, fb + e1.y, fb + e1.z, fb + e1.w};
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     src[f * 8 + e] =
@@ -642,7 +647,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 const uint32_t K = 16u * f + 8u * h + e;
                 const uint32_t pos = (uint32_t)tile_base + 32u * K + sigma_i;
                 const bool ok = (int)(32u * K) < tile_len;
-                if constexpr (PERM) ch[f * 8 + e] = (uint32_t)p.perm[ok ? pos : 0u];
+                if constexpr (PERM) ch[f * 8 + e] = (uint32_t)p.perm[ok ? (pos & g.fold_mask) : 0u] + (pos & ~g.fold_mask);
                 else ch[f * 8 + e] = pos;
             }
         }
@@ -669,7 +674,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 }
 
 template <int OUT, int NWAVES, int STAGES>
-hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
+hipError_t launch_mfma_st(const ApplyParams& p, uint32_t fold_mask, hipStream_t stream) {
     MfmaGeom g;
     const int tiles = (p.d + kTile - 1) / kTile;
     g.tiles_per_row = 1;
@@ -683,6 +688,7 @@ hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
     const uint32_t lds_bytes = 65536u;                  // dynamic part: the staging buffers (incl. the zero slot)
     g.ctr_set = 0;
     g.dynamic = 0;
+    g.fold_mask = fold_mask;
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
     auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
@@ -715,16 +721,16 @@ hipError_t launch_mfma_st(const ApplyParams& p, hipStream_t stream) {
 }
 
 template <int OUT, int NWAVES>
-hipError_t launch_mfma_nw(const ApplyParams& p, hipStream_t stream) {
+hipError_t launch_mfma_nw(const ApplyParams& p, uint32_t fold_mask, hipStream_t stream) {
     switch (p.log2b <= 5 ? 0 : p.log2b - 5) {
-        case 0: return launch_mfma_st<OUT, NWAVES, 0>(p, stream);
-        case 1: return launch_mfma_st<OUT, NWAVES, 1>(p, stream);
-        case 2: return launch_mfma_st<OUT, NWAVES, 2>(p, stream);
-        case 3: return launch_mfma_st<OUT, NWAVES, 3>(p, stream);
-        case 4: return launch_mfma_st<OUT, NWAVES, 4>(p, stream);
-        case 5: return launch_mfma_st<OUT, NWAVES, 5>(p, stream);
-        case 6: return launch_mfma_st<OUT, NWAVES, 6>(p, stream);
-        default: return launch_mfma_st<OUT, NWAVES, 7>(p, stream);
+        case 0: return launch_mfma_st<OUT, NWAVES, 0>(p, fold_mask, stream);
+        case 1: return launch_mfma_st<OUT, NWAVES, 1>(p, fold_mask, stream);
+        case 2: return launch_mfma_st<OUT, NWAVES, 2>(p, fold_mask, stream);
+        case 3: return launch_mfma_st<OUT, NWAVES, 3>(p, fold_mask, stream);
+        case 4: return launch_mfma_st<OUT, NWAVES, 4>(p, fold_mask, stream);
+        case 5: return launch_mfma_st<OUT, NWAVES, 5>(p, fold_mask, stream);
+        case 6: return launch_mfma_st<OUT, NWAVES, 6>(p, fold_mask, stream);
+        default: return launch_mfma_st<OUT, NWAVES, 7>(p, fold_mask, stream);
     }
 }
 
@@ -735,15 +741,38 @@ bool mfma_supports(const ApplyParams& p) {
     return p.b <= kTile && p.d % 512 == 0 && p.d <= 32768 && p.T < ((int64_t)1 << 31) && p.ldx < ((int64_t)1 << 30);
 }
 
-hipError_t launch_mfma(const ApplyParams& p, int out_kind, hipStream_t stream) {
+// Narrow rows stored back to back can be folded into 4096-wide ones (a wave's tile is 4096 wide
+// whatever d is): blocks and 32-groups do not straddle rows, and codes, e8m0 bytes and fp32 outputs
+// of consecutive rows are contiguous, so only the operand addresses through `perm` know about it.
+// Not for the per-token scale, which needs one maximum per real row.
+static bool folds(const ApplyParams& p, int out_kind) {
+    return out_kind != OUT_INT4 && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 && p.T % (kTile / p.d) == 0;
+}
+
+bool mfma_preferred(const ApplyParams& p, int out_kind) {
+    if (!mfma_supports(p)) return false;
+    if (p.d >= kTile) return true;            // its 4096-wide wave tiles are filled
+    // folded narrow rows: ahead from b = 128 on, and for any b once the launch is long
+    return folds(p, out_kind) && (p.b >= 128 || p.T * (int64_t)p.d >= ((int64_t)1 << 26));
+}
+
+hipError_t launch_mfma(const ApplyParams& p0, int out_kind, hipStream_t stream) {
+    ApplyParams p = p0;
+    uint32_t fold_mask = 0xFFFFFFFFu;
+    if (folds(p, out_kind)) {
+        fold_mask = (uint32_t)p.d - 1u;
+        p.T = p.T / (kTile / p.d);
+        p.d = kTile;
+        p.ldx = kTile;
+    }
     const bool wide = p.d > 4 * kTile;        // up to 8 tiles per row -> 8 waves
     switch (out_kind) {
         case OUT_INT4:
-            return wide ? launch_mfma_nw<OUT_INT4, 8>(p, stream) : launch_mfma_nw<OUT_INT4, 4>(p, stream);
+            return wide ? launch_mfma_nw<OUT_INT4, 8>(p, fold_mask, stream) : launch_mfma_nw<OUT_INT4, 4>(p, fold_mask, stream);
         case OUT_MXFP4:
-            return wide ? launch_mfma_nw<OUT_MXFP4, 8>(p, stream) : launch_mfma_nw<OUT_MXFP4, 4>(p, stream);
+            return wide ? launch_mfma_nw<OUT_MXFP4, 8>(p, fold_mask, stream) : launch_mfma_nw<OUT_MXFP4, 4>(p, fold_mask, stream);
         default:
-            return wide ? launch_mfma_nw<OUT_F32, 8>(p, stream) : launch_mfma_nw<OUT_F32, 4>(p, stream);
+            return wide ? launch_mfma_nw<OUT_F32, 8>(p, fold_mask, stream) : launch_mfma_nw<OUT_F32, 4>(p, fold_mask, stream);
     }
 }
 

@@ -114,6 +114,9 @@ SHAPES = [
     (19, 1024, [16, 32, 256, 512, 1024]),
     (13, 3072, [16, 32, 64, 1024]),          # nt = 96: not a power of two
     (21, 2048, [32, 2048]),
+    (24, 2048, [32, 128, 1024, 2048]),       # rows of d < 4096 stored back to back: folded into 4096-wide ones
+    (40, 1024, [16, 64, 1024]),
+    (64, 512, [32, 512]),
     (9, 8192, [16, 32, 64, 128, 2048, 4096, 8192]),
     (5, 14336, [32, 128, 512, 1024, 2048]),
     (6, 20480, [256, 1024, 4096]),           # 8-wave groups, ragged last tile
@@ -220,6 +223,8 @@ DYNAMIC_SHAPES = [
     (4099, 4096, 32, "mxfp4", False),
     (4500, 4096, 4096, "int4", True),
     (4611, 2048, 64, "mxfp4", True),      # a wave per row, half tiles
+    (8200, 2048, 64, "mxfp4", True),      # two rows folded into one tile
+    (8200, 2048, 2048, "mxfp4", False),
     (2051, 8192, 32, "mxfp4", True),      # two rows per workgroup
     (1030, 14336, 128, "int4", True),     # one row per workgroup, ragged last tile, row maximum across waves
     (1030, 14336, 2048, "int4", False),
