@@ -26,7 +26,10 @@ Pins (tests/test_oracle_*.py, run without a GPU): Hadamard orthogonality and Sci
 construction, per-block l2 preservation, one-hot / all-ones closed forms, involution,
 Propositions 1, 2 and 4 and Corollary 3.3, Table 3's add/sub counts via an instrumented
 butterfly, the Section 3 worst-case INT-q error bound, the e2m1 grid/tie table by brute
-force, scale equivariance, closed forms and brute-force optimum for the greedy.
+force, scale equivariance, closed forms and brute-force optimum for the greedy; for the two
+per-token quantizers of Appendix B (asymmetric INT4, FP4) exact rational arithmetic on small
+rows, the half-step error bound, end codes, and the reduction of FP4 to the MXFP4 routine
+when the row maximum is 6 * 2^k.
 """
 from __future__ import annotations
 
@@ -38,6 +41,7 @@ import numpy as np
 __all__ = [
     "bf16_bits_to_f64", "sylvester_hadamard", "permute_channels", "block_hadamard",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
+    "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
     "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
     "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
 ]
@@ -211,6 +215,67 @@ def dequant_mxfp4(codes: np.ndarray, E: np.ndarray) -> np.ndarray:
     return np.ldexp(val, (E.astype(np.int64) - _E8M0_BIAS)[:, :, None]).reshape(T, d)
 
 
+# ----------------------------------------------------------------------------------------
+# Q: INT4, asymmetric, one step size and zero point per token   (Appendix B, INT4 paragraph)
+# ----------------------------------------------------------------------------------------
+def quant_int4_asym_token(Y: np.ndarray, z_given: np.ndarray | None = None):
+    """Returns (codes uint8 [T,d] in [0, 15], s float64 [T], z float64 [T], integer valued).
+
+    Appendix B: s = (max(Y_t) - min(Y_t)) / (2^q - 1), zero point z = min(Y_t) / s, q = 4, and
+    Eq. 4 rounds Y/s before it subtracts z, so the alphabet is met only with an integer z.
+    Reading: z = round_half_even(min / s); code = clip(round_half_even(Y / s) - z, 0, 15);
+    the value a code stands for is s * (code + z)  (Eq. 4 with its last term read as s * z).
+    A constant row has s = 0; then z = 0 and all codes are 0 (the paper is silent).
+
+    `z_given` replaces the computed zero points; the parity tests use it for a row whose
+    min / s sits on a rounding boundary.
+    """
+    lo = Y.min(axis=1)
+    hi = Y.max(axis=1)
+    s = (hi - lo) / 15.0
+    safe = np.where(s > 0.0, s, 1.0)
+    z = np.where(s > 0.0, np.rint(lo / safe), 0.0)
+    if z_given is not None:
+        z = np.asarray(z_given, dtype=np.float64)
+    codes = np.clip(np.rint(Y / safe[:, None]) - z[:, None], 0, 15)
+    codes[s == 0.0, :] = 0
+    return codes.astype(np.uint8), s, z
+
+
+def dequant_int4_asym(codes: np.ndarray, s: np.ndarray, z: np.ndarray) -> np.ndarray:
+    return (codes.astype(np.float64) + np.asarray(z, dtype=np.float64)[:, None]) * np.asarray(s, dtype=np.float64)[:, None]
+
+
+# ----------------------------------------------------------------------------------------
+# Q: FP4 (e2m1) with one real-valued scale per token   (Appendix B, (MX)FP4 paragraph)
+# ----------------------------------------------------------------------------------------
+def quant_fp4_token(Y: np.ndarray):
+    """Returns (codes uint8 [T,d], 4-bit sign|exp|mant; s float64 [T]).
+
+    Appendix B: FP4 activations take one scale per token, s = ||Y_t||_inf / c, z = 0, and the
+    elements are rounded (nearest, ties to the even code) onto the e2m1 grid.
+    Reading of c: the appendix prints c = 2^(q-1) - 1 = 7, the integer quantizer's constant,
+    which is not an e2m1 value; with it the row maximum would land on 7 and saturate to 6.
+    The largest magnitude of the alphabet, c = 6, is taken, so the row maximum maps onto the
+    largest code.  An all-zero row has s = 0 and all codes 0; zero is always emitted as +0.
+    """
+    amax = np.abs(Y).max(axis=1)
+    s = amax / 6.0
+    safe = np.where(s > 0.0, s, 1.0)
+    V = Y / safe[:, None]
+    mag = _round_to_e2m1_codes(np.abs(V))
+    sign = ((V < 0.0) & (mag != 0)).astype(np.uint8)
+    codes = (sign << 3) | mag
+    codes[s == 0.0, :] = 0
+    return codes.astype(np.uint8), s
+
+
+def dequant_fp4_token(codes: np.ndarray, s: np.ndarray) -> np.ndarray:
+    mag = E2M1_GRID[codes & 7]
+    return np.where((codes & 8) != 0, -mag, mag) * np.asarray(s, dtype=np.float64)[:, None]
+
+
+
 def pack_nibbles(codes: np.ndarray) -> np.ndarray:
     """[T, d] 4-bit codes -> [T, d/2] bytes; element 2k in the low nibble, 2k+1 in the high.
 
@@ -295,7 +360,8 @@ def brute_force_min_max_block_mass(a, b: int) -> float:
 def perq_apply(x_bits: np.ndarray, perm, b: int, fmt: str, rotate=block_hadamard):
     """bf16 bits [T,d] -> dict(y, codes, packed, scales[, s64]) following P, R~, Q in order.
 
-    fmt is "int4" (scales: float32 [T]) or "mxfp4" (scales: uint8 [T, d/32]).
+    fmt is "int4" (scales: float32 [T]), "mxfp4" (scales: uint8 [T, d/32]), "int4_asym"
+    (scales: float32 [T, 2] = step, zero point) or "fp4_token" (scales: float32 [T]).
     """
     X = bf16_bits_to_f64(x_bits)
     Y = rotate(permute_channels(X, perm), b)
@@ -306,4 +372,12 @@ def perq_apply(x_bits: np.ndarray, perm, b: int, fmt: str, rotate=block_hadamard
     if fmt == "mxfp4":
         codes, E = quant_mxfp4(Y)
         return {"y": Y, "codes": codes, "packed": pack_nibbles(codes), "scales": E}
-    raise ValueError("fmt must be 'int4' or 'mxfp4'")
+    if fmt == "int4_asym":
+        codes, s, z = quant_int4_asym_token(Y)
+        return {"y": Y, "codes": codes, "packed": pack_nibbles(codes),
+                "scales": np.stack([s, z], axis=1).astype(np.float32), "s64": s, "z": z}
+    if fmt == "fp4_token":
+        codes, s = quant_fp4_token(Y)
+        return {"y": Y, "codes": codes, "packed": pack_nibbles(codes),
+                "scales": s.astype(np.float32), "s64": s}
+    raise ValueError("fmt must be 'int4', 'mxfp4', 'int4_asym' or 'fp4_token'")

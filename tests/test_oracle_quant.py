@@ -190,3 +190,138 @@ def test_end_to_end_reconstruction(fmt):
     assert np.all(np.linalg.norm(rec - X, axis=1) <= np.ravel(tol.max(axis=1) if tol.ndim > 1 else tol))
     assert np.allclose(np.linalg.norm(out["y"], axis=1), np.linalg.norm(X, axis=1), rtol=1e-12)
     assert out["packed"].shape == (T, d // 2)
+
+
+# ---- INT4 asymmetric per token (Appendix B, INT4 paragraph) -----------------------------------
+def _rint_fraction(q):
+    """Round a Fraction to the nearest integer, ties to even (independent of numpy.rint)."""
+    from fractions import Fraction
+    fl = q.numerator // q.denominator
+    r = q - fl
+    if r > Fraction(1, 2) or (r == Fraction(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
+def test_int4_asym_exact_rational_small_rows():
+    """Integer-valued rows worked in exact rational arithmetic: step, zero point, codes."""
+    from fractions import Fraction
+    rng = _rng(11)
+    for _ in range(40):
+        row = rng.integers(-40, 60, size=12)
+        if row.max() == row.min():
+            continue
+        lo, hi = int(row.min()), int(row.max())
+        s = Fraction(hi - lo, 15)
+        z = _rint_fraction(Fraction(lo) / s)
+        want = [min(15, max(0, _rint_fraction(Fraction(int(v)) / s) - z)) for v in row]
+        c, s64, z64 = orc.quant_int4_asym_token(row[None, :].astype(np.float64))
+        assert z64[0] == z and abs(s64[0] - float(s)) <= 1e-15 * float(s)
+        # a value whose quotient is an exact tie in rationals may sit a hair off it in floating
+        # point; everything else must agree
+        ties = [(Fraction(int(v)) / s - Fraction(1, 2)).denominator == 1 for v in row]
+        for k in range(12):
+            if not ties[k]:
+                assert c[0, k] == want[k], (row, k)
+
+
+def test_int4_asym_error_bound_end_codes_and_constant_row():
+    Y = _rng(12).standard_t(3, size=(60, 128)) + _rng(13).uniform(-3, 3, size=(60, 1))
+    c, s, z = orc.quant_int4_asym_token(Y)
+    assert c.min() >= 0 and c.max() <= 15 and np.all(z == np.rint(z))
+    assert np.allclose(s, (Y.max(axis=1) - Y.min(axis=1)) / 15.0, rtol=1e-16)
+    dq = orc.dequant_int4_asym(c, s, z)
+    assert np.all(np.abs(Y - dq) <= s[:, None] / 2 * (1 + 1e-9))
+    rows = np.arange(60)
+    assert np.all(c[rows, Y.argmin(axis=1)] == 0)
+    assert np.all(c[rows, Y.argmax(axis=1)] >= 14)         # 15 unless min/s and max/s round apart
+    # constant rows: no step, no information
+    c0, s0, z0 = orc.quant_int4_asym_token(np.full((2, 8), 3.25))
+    assert np.all(c0 == 0) and np.all(s0 == 0) and np.all(z0 == 0)
+
+
+def test_int4_asym_scale_shift_and_reflection():
+    Y = _rng(14).standard_normal((10, 64))
+    c, s, z = orc.quant_int4_asym_token(Y)
+    for k in (-7, 5):
+        c2, s2, z2 = orc.quant_int4_asym_token(np.ldexp(Y, k))
+        assert np.array_equal(c, c2) and np.array_equal(np.ldexp(s, k), s2) and np.array_equal(z, z2)
+    # moving a row by a whole number of steps moves the zero point, not the codes, wherever no
+    # quotient is within rounding error of a tie
+    Yq = np.rint(Y * 8) / 8                                   # dyadic values: shifts are exact
+    cq, sq, zq = orc.quant_int4_asym_token(Yq)
+    frac = np.abs((Yq / sq[:, None]) % 1.0 - 0.5)
+    shift = 4 * sq
+    cs, ss, zs = orc.quant_int4_asym_token(Yq + shift[:, None])
+    ok = frac.min(axis=1) > 1e-9
+    assert ok.sum() >= 5
+    assert np.allclose(ss, sq, rtol=1e-12)
+    assert np.array_equal(cs[ok], cq[ok]) and np.array_equal(zs[ok], zq[ok] + 4)
+    # reflection: codes run the other way round when the two ends round to 15 steps apart
+    cn, sn, zn = orc.quant_int4_asym_token(-Y)
+    span = np.rint(Y.max(axis=1) / s) - np.rint(Y.min(axis=1) / s)
+    good = span == 15
+    assert good.sum() >= 5 and np.array_equal(cn[good], 15 - c[good])
+
+
+def test_int4_asym_given_zero_point():
+    Y = _rng(15).standard_normal((3, 32))
+    c, s, z = orc.quant_int4_asym_token(Y)
+    c1, _, z1 = orc.quant_int4_asym_token(Y, z_given=z + 1)
+    assert np.array_equal(z1, z + 1)
+    assert np.array_equal(c1, np.clip(c.astype(int) - 1, 0, 15))
+
+
+# ---- FP4 with one scale per token (Appendix B, (MX)FP4 paragraph) -----------------------------
+def test_fp4_token_reduces_to_mxfp4_when_max_is_6_times_power_of_two():
+    rng = _rng(21)
+    for k in (-5, 0, 9):
+        Y = rng.uniform(-6, 6, size=(20, 32))
+        Y[:, 3] = 6.0 * rng.choice([-1.0, 1.0], size=20)        # the row maximum, exactly 6
+        Y = np.ldexp(Y, k)
+        c, s = orc.quant_fp4_token(Y)
+        cm, E = orc.quant_mxfp4(Y)
+        assert np.all(s == 2.0 ** k) and np.all(E.astype(int) - 127 == k)
+        assert np.array_equal(c, cm)
+
+
+def test_fp4_token_grid_round_trip_error_bound_and_signs():
+    rng = _rng(22)
+    grid = orc.E2M1_GRID
+    # rows made of grid values times a per-row constant, maximum 6: reproduced exactly
+    idx = rng.integers(0, 8, size=(30, 64)); idx[:, 0] = 7
+    sgn = rng.choice([-1.0, 1.0], size=(30, 64))
+    cst = rng.uniform(0.1, 10, size=(30, 1))
+    Y = grid[idx] * sgn * cst
+    c, s = orc.quant_fp4_token(Y)
+    assert np.allclose(s[:, None], cst, rtol=1e-15)
+    assert np.allclose(orc.dequant_fp4_token(c, s), Y, rtol=1e-14, atol=0)
+    assert np.all((c & 7)[idx == 0] == 0) and np.all((c & 8)[idx == 0] == 0)     # +0 only
+    # generic rows: nothing saturates, the maximum takes the top code, error <= half the local spacing
+    Y = rng.standard_t(3, size=(40, 96))
+    c, s = orc.quant_fp4_token(Y)
+    V = np.abs(Y) / s[:, None]
+    assert V.max() <= 6 * (1 + 1e-15)
+    assert np.all((c & 7)[np.arange(40), np.abs(Y).argmax(axis=1)] == 7)
+    lo = grid[np.searchsorted(grid, np.minimum(V, 6.0), side="right") - 1]
+    hi = grid[np.minimum(np.searchsorted(grid, np.minimum(V, 6.0), side="left"), 7)]
+    half = np.where(hi > lo, (hi - lo) / 2, 0.0)
+    err = np.abs(orc.dequant_fp4_token(c, s) - Y) / s[:, None]
+    assert np.all(err <= half + 1e-12)
+    # sign flip flips the sign bit of every non-zero code; power-of-two scaling keeps the codes
+    c2, s2 = orc.quant_fp4_token(-Y)
+    nz = (c & 7) != 0
+    assert np.array_equal(c2[nz], c[nz] ^ 8) and np.array_equal(c2[~nz], c[~nz]) and np.array_equal(s, s2)
+    c3, s3 = orc.quant_fp4_token(np.ldexp(Y, 6))
+    assert np.array_equal(c3, c) and np.array_equal(s3, np.ldexp(s, 6))
+    c0, s0 = orc.quant_fp4_token(np.zeros((1, 32)))
+    assert np.all(c0 == 0) and s0[0] == 0
+
+
+def test_apply_new_formats_shapes():
+    x = np.random.default_rng(5).integers(0, 2 ** 16, size=(4, 64), dtype=np.uint16)
+    x = np.where((x & 0x7F80) == 0x7F80, 0, x).astype(np.uint16)        # no inf / nan patterns
+    r = orc.perq_apply(x, None, 16, "int4_asym")
+    assert r["scales"].shape == (4, 2) and r["packed"].shape == (4, 32) and r["codes"].max() <= 15
+    r = orc.perq_apply(x, None, 16, "fp4_token")
+    assert r["scales"].shape == (4,) and r["packed"].shape == (4, 32)
