@@ -34,13 +34,15 @@ WORKLOADS = {
     "block_vs_full_b2048_mxfp4": ("block_vs_full", 2048, "mxfp4", False),
     "calib_apply_b32_mxfp4_perm": ("calib_apply", 32, "mxfp4", True),
     "calib_apply_b16_mxfp4_perm": ("calib_apply", 16, "mxfp4", True),
+    "llama8b_d4096_b128_int4asym_perm": ("llama8b_d4096", 128, "int4_asym", True),
+    "llama8b_d4096_b128_fp4token_perm": ("llama8b_d4096", 128, "fp4_token", True),
 }
 DEFAULT = "llama8b_d4096_b128_int4_perm"
 
 
 def algorithmic_bytes(T: int, d: int, fmt: str) -> int:
     """What the method itself must move per launch: bf16 in, nibbles out, scales out."""
-    scales = 4 * T if fmt == "int4" else T * d // 32
+    scales = {"int4": 4 * T, "fp4_token": 4 * T, "int4_asym": 8 * T, "mxfp4": T * d // 32}[fmt]
     return T * d * 2 + T * d // 2 + scales
 
 

@@ -14,8 +14,11 @@
  *
  * Conventions
  *   - "device" pointers are HIP device memory on the current device, "host" pointers are
- *     ordinary host memory.  Every buffer is owned by the caller; the library keeps no state,
- *     allocates nothing and frees nothing.
+ *     ordinary host memory.  Every buffer is owned by the caller; the library allocates nothing
+ *     and frees nothing.  Its only state is a small table of scheduling counters in device
+ *     memory that every launch leaves at zero (consecutive launches rotate through 64 sets of
+ *     them, so launches overlapping on different streams do not meet in one set unless 64
+ *     launches lie between them while the older is still running).
  *   - bf16 tensors are passed as uint16_t bit patterns, row-major, leading dimension in
  *     elements.
  *   - Device entry points enqueue on `hip_stream` (a hipStream_t, NULL = default stream) and
@@ -45,7 +48,15 @@ typedef enum {
 
 typedef enum {
     PERQ_FMT_INT4_SYM_TOKEN = 0,  /* codes in [-7,7] as two's-complement nibbles; float scale per token */
-    PERQ_FMT_MXFP4 = 1            /* e2m1 nibbles (sign|exp2|mant1); e8m0 byte per 32 outputs */
+    PERQ_FMT_MXFP4 = 1,           /* e2m1 nibbles (sign|exp2|mant1); e8m0 byte per 32 outputs */
+    /* Appendix B, INT4 paragraph (the activation quantizer of the paper's INT4 results): per token
+     * step s = (max - min)/15 and integer zero point z = rne(min/s); codes rne(y/s) - z clipped to
+     * [0,15] as unsigned nibbles; a code stands for s*(code + z).  scales: float [T][2] = (s, z),
+     * 8-byte aligned.  A constant row gives s = 0, z = 0, codes 0. */
+    PERQ_FMT_INT4_ASYM_TOKEN = 2,
+    /* Appendix B, (MX)FP4 paragraph: e2m1 nibbles with one real scale per token,
+     * s = max|y| / 6 (6 = largest e2m1 magnitude); scales: float [T]. */
+    PERQ_FMT_FP4_TOKEN = 3
 } perq_fmt_t;
 
 /* Which rotation kernel runs.  AUTO picks the fastest one that covers the shape; the explicit

@@ -61,6 +61,8 @@ perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, 
     p->odd_norm = (log2b & 1) ? (float)std::sqrt(0.5) : 1.0f;
     p->half_log2b = log2b / 2;
     p->inv_7sqrt_b = 1.0 / (7.0 * std::sqrt((double)b));
+    p->inv_15sqrt_b = 1.0 / (15.0 * std::sqrt((double)b));
+    p->inv_6sqrt_b = 1.0 / (6.0 * std::sqrt((double)b));
     return PERQ_OK;
 }
 
@@ -95,19 +97,25 @@ extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, 
                                                         perq_fmt_t fmt, perq_algo_t algo, uint8_t* codes,
                                                         void* scales, void* hip_stream) {
     perq::ApplyParams p;
-    if (fmt != PERQ_FMT_INT4_SYM_TOKEN && fmt != PERQ_FMT_MXFP4) return PERQ_ERR_INVALID_ARG;
+    int out_kind;
+    switch (fmt) {
+        case PERQ_FMT_INT4_SYM_TOKEN: out_kind = perq::OUT_INT4; break;
+        case PERQ_FMT_MXFP4: out_kind = perq::OUT_MXFP4; break;
+        case PERQ_FMT_INT4_ASYM_TOKEN: out_kind = perq::OUT_INT4_ASYM; break;
+        case PERQ_FMT_FP4_TOKEN: out_kind = perq::OUT_FP4_TOKEN; break;
+        default: return PERQ_ERR_INVALID_ARG;
+    }
     if (algo != PERQ_ALGO_AUTO && algo != PERQ_ALGO_BUTTERFLY && algo != PERQ_ALGO_MFMA)
         return PERQ_ERR_INVALID_ARG;
     const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
     if (st != PERQ_OK || p.T == 0) return st;
     if (codes == nullptr || scales == nullptr) return PERQ_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(codes) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
-    if (fmt == PERQ_FMT_INT4_SYM_TOKEN && (reinterpret_cast<uintptr_t>(scales) & 3u) != 0)
-        return PERQ_ERR_UNSUPPORTED;
+    const uintptr_t scale_align = fmt == PERQ_FMT_MXFP4 ? 1u : (fmt == PERQ_FMT_INT4_ASYM_TOKEN ? 8u : 4u);
+    if ((reinterpret_cast<uintptr_t>(scales) & (scale_align - 1u)) != 0) return PERQ_ERR_UNSUPPORTED;
     p.codes = codes;
     p.scales = scales;
-    return perq::dispatch(p, fmt == PERQ_FMT_MXFP4 ? perq::OUT_MXFP4 : perq::OUT_INT4, algo,
-                          static_cast<hipStream_t>(hip_stream));
+    return perq::dispatch(p, out_kind, algo, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" perq_status_t perq_permute_rotate_quant(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,

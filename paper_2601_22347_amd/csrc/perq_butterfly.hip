@@ -178,29 +178,78 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
                 static_cast<uint8_t*>(p.scales)[row * (int64_t)(d >> 5) + t] = (uint8_t)E;
             }
         } else {
-            // per-token maximum: lanes of the row inside this wave, then the row's waves
-            float m = active ? absmax(v) : 0.0f;
-            if (g.nt > 1) m = fmaxf(m, lane_xor<1>(m));
-            if (g.nt > 2) m = fmaxf(m, lane_xor<2>(m));
-            if (g.nt > 4) m = fmaxf(m, lane_xor<4>(m));
-            if (g.nt > 8) m = fmaxf(m, lane_xor<8>(m));
-            if (g.nt > 16) m = fmaxf(m, lane_xor<16>(m));
-            if (g.nt > 32) m = fmaxf(m, lane_xor<32>(m));
+            // per-token extremes: lanes of the row inside this wave, then the row's waves.
+            // m[0] = max |y| (symmetric INT4, FP4) or max y (asymmetric INT4), m[1] = max -y.
+            constexpr int kRed = OUT == OUT_INT4_ASYM ? 2 : 1;
+            float m[2] = {0.0f, 0.0f};
+            if constexpr (OUT == OUT_INT4_ASYM) {
+                float lo, hi;
+                minmax(v, lo, hi);
+                m[0] = active ? hi : -3.0e38f;
+                m[1] = active ? -lo : -3.0e38f;
+            } else {
+                m[0] = active ? absmax(v) : 0.0f;
+            }
+#pragma unroll
+            for (int j = 0; j < kRed; ++j) {
+                if (g.nt > 1) m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
+                if (g.nt > 2) m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
+                if (g.nt > 4) m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
+                if (g.nt > 8) m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
+                if (g.nt > 16) m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
+                if (g.nt > 32) m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+            }
             if (g.waves_per_row > 1) {
                 float* red = reinterpret_cast<float*>(lds + g.red_off);
                 const int wave = tid >> 6;
                 __syncthreads();               // red[] of the previous row has been consumed
-                if (lane == 0) red[wave] = m;
+                if (lane == 0) {
+#pragma unroll
+                    for (int j = 0; j < kRed; ++j) red[2 * wave + j] = m[j];
+                }
                 __syncthreads();
                 const int w0 = (r * g.nt) >> 6;
-                for (int w = 0; w < g.waves_per_row; ++w) m = fmaxf(m, red[w0 + w]);
+                for (int w = 0; w < g.waves_per_row; ++w) {
+#pragma unroll
+                    for (int j = 0; j < kRed; ++j) m[j] = fmaxf(m[j], red[2 * (w0 + w) + j]);
+                }
             }
-            const float inv = m > 0.0f ? 7.0f / m : 0.0f;
-            if (live) {
-                const uint4 c = make_uint4(int4_pack8(v, inv), int4_pack8(v + 8, inv),
-                                           int4_pack8(v + 16, inv), int4_pack8(v + 24, inv));
-                store_stream16(p.codes + row * (int64_t)(d >> 1) + 16 * t, c);
-                if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m * p.inv_7sqrt_b);
+            uint8_t* crow = p.codes + row * (int64_t)(d >> 1) + 16 * t;
+            if constexpr (OUT == OUT_INT4) {
+                const float inv = m[0] > 0.0f ? 7.0f / m[0] : 0.0f;
+                if (live) {
+                    const uint4 c = make_uint4(int4_pack8(v, inv), int4_pack8(v + 8, inv),
+                                               int4_pack8(v + 16, inv), int4_pack8(v + 24, inv));
+                    store_stream16(crow, c);
+                    if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_7sqrt_b);
+                }
+            } else if constexpr (OUT == OUT_FP4_TOKEN) {
+                const float inv = m[0] > 0.0f ? 6.0f / m[0] : 0.0f;
+                if (live) {
+                    const uint4 c = make_uint4(fp4_pack8(v, inv), fp4_pack8(v + 8, inv),
+                                               fp4_pack8(v + 16, inv), fp4_pack8(v + 24, inv));
+                    store_stream16(crow, c);
+                    if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_6sqrt_b);
+                }
+            } else {
+                const float lo = -m[1], hi = m[0];
+                const Int4Asym q = int4_asym_row(lo, hi);
+                if (live) {
+                    uint4 c;
+                    if (!q.clamp) {
+                        const uint32_t zn = (uint32_t)q.z * 0x11111111u;
+                        c = make_uint4(int4a_pack8(v, q.inv, zn), int4a_pack8(v + 8, q.inv, zn),
+                                       int4a_pack8(v + 16, q.inv, zn), int4a_pack8(v + 24, q.inv, zn));
+                    } else {
+                        c = make_uint4(int4a_pack8_clamped(v, q.inv, q.z), int4a_pack8_clamped(v + 8, q.inv, q.z),
+                                       int4a_pack8_clamped(v + 16, q.inv, q.z), int4a_pack8_clamped(v + 24, q.inv, q.z));
+                    }
+                    store_stream16(crow, c);
+                    if (t == 0) {
+                        float2* so = static_cast<float2*>(p.scales) + row;
+                        *so = make_float2((float)((double)(hi - lo) * p.inv_15sqrt_b), (float)q.z);
+                    }
+                }
             }
         }
         __syncthreads();   // LDS is rewritten by the next iteration
@@ -255,6 +304,8 @@ hipError_t launch_butterfly(const ApplyParams& p, int out_kind, hipStream_t stre
     switch (out_kind) {
         case OUT_INT4: return launch_butterfly_out<OUT_INT4>(p, stream);
         case OUT_MXFP4: return launch_butterfly_out<OUT_MXFP4>(p, stream);
+        case OUT_INT4_ASYM: return launch_butterfly_out<OUT_INT4_ASYM>(p, stream);
+        case OUT_FP4_TOKEN: return launch_butterfly_out<OUT_FP4_TOKEN>(p, stream);
         default: return launch_butterfly_out<OUT_F32>(p, stream);
     }
 }

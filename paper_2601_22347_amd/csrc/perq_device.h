@@ -5,6 +5,8 @@
 //  - the three epilogues on a run of 32 contiguous rotated outputs held by one lane:
 //      INT4 symmetric per token   (Section 3; Appendix B Eq. 4, z = 0)
 //      MXFP4                      (Appendix B Eq. 5: e2m1 + one power-of-two scale per 32)
+//      INT4 asymmetric per token  (Appendix B, INT4 paragraph: step (max-min)/15, integer zero point)
+//      FP4 per token              (Appendix B, (MX)FP4 paragraph: e2m1 with one real scale per token)
 //      fp32 dump                  (test entry)
 #pragma once
 #include <hip/hip_runtime.h>
@@ -12,7 +14,7 @@
 
 namespace perq {
 
-enum OutKind { OUT_INT4 = 0, OUT_MXFP4 = 1, OUT_F32 = 2 };
+enum OutKind { OUT_INT4 = 0, OUT_MXFP4 = 1, OUT_F32 = 2, OUT_INT4_ASYM = 3, OUT_FP4_TOKEN = 4 };
 
 struct ApplyParams {
     const uint16_t* x;      // bf16 [T, ldx]
@@ -20,7 +22,7 @@ struct ApplyParams {
     int64_t ldx;
     const int32_t* perm;    // int32 [d] or nullptr
     uint8_t* codes;         // [T, d/2]
-    void* scales;           // float [T] or uint8 [T, d/32]
+    void* scales;           // float [T], uint8 [T, d/32] or float [T][2] (step, zero point)
     float* y;               // [T, d] (test entry only)
     int32_t d;
     int32_t b;
@@ -29,6 +31,8 @@ struct ApplyParams {
     float odd_norm;         // 1.0 if log2b even, fl32(1/sqrt(2)) if odd
     int32_t half_log2b;     // floor(log2b / 2)
     double inv_7sqrt_b;     // 1 / (7 sqrt(b)) in double
+    double inv_15sqrt_b;    // 1 / (15 sqrt(b))
+    double inv_6sqrt_b;     // 1 / (6 sqrt(b))
 };
 
 // Streaming (non-temporal) 16-byte global accesses: every input byte is read once and every
@@ -139,6 +143,70 @@ __device__ __forceinline__ uint32_t int4_pack8(const float* v, float inv) {
 #pragma unroll
     for (int i = 6; i >= 0; --i) acc = (acc << 4) + __float_as_uint(__builtin_fmaf(v[i], inv, 12582920.0f));
     return (acc - kInt4Bias) ^ 0x88888888u;
+}
+
+// ---- INT4 asymmetric: 8 values -> one dword of unsigned nibbles (code = rne(y*inv) - z) -----
+// Same rounding word as above without the +8: 0x4B400000 + c, c = rne(y*inv) (possibly negative;
+// all arithmetic is modulo 2^32 and linear).  As long as every c - z lies in [0, 15] the eight
+// words can be merged first and K + z * 0x11111111 removed once.  c - z = 16 happens only for
+// values within half a step of the row maximum, and only in rows whose two ends round 16 steps
+// apart; such rows take the second routine, which clamps element by element.
+constexpr uint32_t kInt4AsymBias = (uint32_t)(0x4B400000ull * 0x11111111ull);
+__device__ __forceinline__ int int4a_round(float y, float inv);
+__device__ __forceinline__ uint32_t int4a_pack8(const float* v, float inv, uint32_t z_nibbles) {
+    uint32_t acc = __float_as_uint(__builtin_fmaf(v[7], inv, 12582912.0f));
+#pragma unroll
+    for (int i = 6; i >= 0; --i) acc = (acc << 4) + __float_as_uint(__builtin_fmaf(v[i], inv, 12582912.0f));
+    return acc - kInt4AsymBias - z_nibbles;
+}
+__device__ __forceinline__ uint32_t int4a_pack8_clamped(const float* v, float inv, int z) {
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 7; i >= 0; --i) {
+        const int c = int4a_round(v[i], inv) - z;
+        acc = (acc << 4) | (uint32_t)(c < 0 ? 0 : (c > 15 ? 15 : c));
+    }
+    return acc;
+}
+
+// ---- FP4 with a real-valued scale: 8 values -> one dword of e2m1 nibbles --------------------
+// y * inv (inv = 6 / row maximum) is handed to the same convert with scale 1.
+__device__ __forceinline__ uint32_t fp4_pack8(const float* v, float inv) {
+    uint32_t w = 0;
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[0] * inv, v[1] * inv, 1.0f, 0);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[2] * inv, v[3] * inv, 1.0f, 1);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[4] * inv, v[5] * inv, 1.0f, 2);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, v[6] * inv, v[7] * inv, 1.0f, 3);
+    const uint32_t mag = w & 0x77777777u;
+    const uint32_t nz = (mag + 0x77777777u) & 0x88888888u;
+    return mag | (w & nz);
+}
+
+// Per-row quantities of the asymmetric INT4 quantizer from the row's extremes (unnormalised
+// rotation outputs; the missing 1/sqrt(b) cancels in every ratio).
+struct Int4Asym {
+    float inv;          // 15 / (hi - lo), 0 for a constant row
+    int z;              // rne(lo * inv), rounded by the very instruction that rounds the elements
+    bool clamp;         // the two ends round 16 steps apart
+};
+__device__ __forceinline__ int int4a_round(float y, float inv) {
+    return (int)(__float_as_uint(__builtin_fmaf(y, inv, 12582912.0f)) - 0x4B400000u);
+}
+__device__ __forceinline__ Int4Asym int4_asym_row(float lo, float hi) {
+    Int4Asym q;
+    const float range = hi - lo;
+    q.inv = range > 0.0f ? 15.0f / range : 0.0f;
+    // (the rounding is monotonic, so every element of the row lands in [z, round(hi)])
+    q.z = int4a_round(lo, q.inv);
+    q.clamp = int4a_round(hi, q.inv) - q.z > 15;
+    return q;
+}
+
+template <int N>
+__device__ __forceinline__ void minmax(const float (&v)[N], float& lo, float& hi) {
+    lo = v[0]; hi = v[0];
+#pragma unroll
+    for (int i = 1; i < N; ++i) { lo = fminf(lo, v[i]); hi = fmaxf(hi, v[i]); }
 }
 
 // ---- MXFP4: 8 values -> one dword of e2m1 nibbles ----------------------------------------

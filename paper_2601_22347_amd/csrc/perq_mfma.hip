@@ -121,7 +121,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // that may write the same memory, and with one shared array that was all loads in flight.
     extern __shared__ __align__(16) unsigned char lds[];
     __shared__ __align__(16) unsigned char out_stage[NWAVES * 2048];   // per-wave output staging
-    __shared__ float red_scratch[32];                                  // row maxima across waves
+    __shared__ float red_scratch[64];                                  // row extremes across waves
     __shared__ uint32_t unit_box[1];                                   // next unit of the workgroup
     // Two staging buffers when a row group fits 32 KiB (4 waves): the loads of the next group are
     // in flight during the whole of the current one.  The buffer is selected by a compile-time
@@ -424,7 +424,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         } else {
             uint32_t pk[kQ][2];
             uint32_t ebytes = 0;
-            float row_max = 0.0f;
+            float row_max = 0.0f;     // the row's maximum, or hi - lo for the asymmetric quantizer
+            int row_zero = 0;
             if constexpr (OUT == OUT_MXFP4) {
                 if (p.odd_norm != 1.0f) {
 #pragma unroll
@@ -443,28 +444,85 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     ebytes |= (uint32_t)E << (8 * q);
                 }
             } else {
-                float m = absmax(v);
-                m = fmaxf(m, lane_xor<1>(m));
-                m = fmaxf(m, lane_xor<2>(m));
-                m = fmaxf(m, lane_xor<4>(m));
-                m = fmaxf(m, lane_xor<8>(m));
-                m = fmaxf(m, lane_xor<16>(m));
-                m = fmaxf(m, lane_xor<32>(m));
+                // per-token extremes: m[0] = max |y| (symmetric INT4, FP4) or max y (asymmetric
+                // INT4), m[1] = max -y; the zeros read for absent sub-blocks of a ragged tile take
+                // no part in a minimum or maximum
+                constexpr int kRed = OUT == OUT_INT4_ASYM ? 2 : 1;
+                float m[2] = {0.0f, 0.0f};
+                if constexpr (OUT == OUT_INT4_ASYM) {
+                    m[0] = -3.0e38f;
+                    m[1] = -3.0e38f;
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) {
+                        if (qvalid[q]) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                m[0] = fmaxf(m[0], v[q * 16 + r]);
+                                m[1] = fmaxf(m[1], -v[q * 16 + r]);
+                            }
+                        }
+                    }
+                } else {
+                    m[0] = absmax(v);
+                }
+#pragma unroll
+                for (int j = 0; j < kRed; ++j) {
+                    m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
+                    m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
+                    m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
+                    m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
+                    m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
+                    m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+                }
                 if (!wave_local) {
-                    // row maximum across the row's waves; scratch alternates with the group parity so
+                    // extremes across the row's waves; scratch alternates with the group parity so
                     // that one barrier per group is enough
-                    float* red = red_scratch + decltype(buf_const)::value * 16;
-                    if (lane == 0) lds_store4(red + wave, m);
+                    float* red = red_scratch + decltype(buf_const)::value * 32;
+                    if (lane == 0) {
+#pragma unroll
+                        for (int j = 0; j < kRed; ++j) lds_store4(red + 2 * wave + j, m[j]);
+                    }
                     workgroup_barrier_lds();
                     const int w0 = rr * g.tiles_per_row;
-                    for (int w = 0; w < g.tiles_per_row; ++w) m = fmaxf(m, red[w0 + w]);
-                }
-                row_max = m;
-                const float inv = m > 0.0f ? 7.0f / m : 0.0f;
+                    for (int w = 0; w < g.tiles_per_row; ++w) {
 #pragma unroll
-                for (int q = 0; q < kQ; ++q) {
-                    pk[q][0] = int4_pack8(v + q * 16, inv);
-                    pk[q][1] = int4_pack8(v + q * 16 + 8, inv);
+                        for (int j = 0; j < kRed; ++j) m[j] = fmaxf(m[j], red[2 * (w0 + w) + j]);
+                    }
+                }
+                if constexpr (OUT == OUT_INT4) {
+                    row_max = m[0];
+                    const float inv = m[0] > 0.0f ? 7.0f / m[0] : 0.0f;
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) {
+                        pk[q][0] = int4_pack8(v + q * 16, inv);
+                        pk[q][1] = int4_pack8(v + q * 16 + 8, inv);
+                    }
+                } else if constexpr (OUT == OUT_FP4_TOKEN) {
+                    row_max = m[0];
+                    const float inv = m[0] > 0.0f ? 6.0f / m[0] : 0.0f;
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q) {
+                        pk[q][0] = fp4_pack8(v + q * 16, inv);
+                        pk[q][1] = fp4_pack8(v + q * 16 + 8, inv);
+                    }
+                } else {
+                    row_max = m[0] + m[1];                 // hi - lo
+                    const Int4Asym qa = int4_asym_row(-m[1], m[0]);
+                    row_zero = qa.z;
+                    if (!qa.clamp) {
+                        const uint32_t zn = (uint32_t)qa.z * 0x11111111u;
+#pragma unroll
+                        for (int q = 0; q < kQ; ++q) {
+                            pk[q][0] = int4a_pack8(v + q * 16, qa.inv, zn);
+                            pk[q][1] = int4a_pack8(v + q * 16 + 8, qa.inv, zn);
+                        }
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < kQ; ++q) {
+                            pk[q][0] = int4a_pack8_clamped(v + q * 16, qa.inv, qa.z);
+                            pk[q][1] = int4a_pack8_clamped(v + q * 16 + 8, qa.inv, qa.z);
+                        }
+                    }
                 }
             }
             // Give lane (c,0) the whole of its sub-blocks q = 0, 1 and lane (c,1) the whole of q = 2, 3:
@@ -504,9 +562,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                         for (int q = 0; q < kQ; ++q)
                             if (h == 0 && qvalid[q]) srow[sbq(q)] = (uint8_t)(ebytes >> (8 * q));
                     }
+                } else if constexpr (OUT == OUT_INT4_ASYM) {
+                    if (lane == 0 && tile_base == 0)
+                        static_cast<float2*>(p.scales)[row] =
+                            make_float2((float)((double)row_max * p.inv_15sqrt_b), (float)row_zero);
                 } else {
                     if (lane == 0 && tile_base == 0)
-                        static_cast<float*>(p.scales)[row] = (float)((double)row_max * p.inv_7sqrt_b);
+                        static_cast<float*>(p.scales)[row] =
+                            (float)((double)row_max * (OUT == OUT_INT4 ? p.inv_7sqrt_b : p.inv_6sqrt_b));
                 }
             }
         }
@@ -746,7 +809,7 @@ bool mfma_supports(const ApplyParams& p) {
 // of consecutive rows are contiguous, so only the operand addresses through `perm` know about it.
 // Not for the per-token scale, which needs one maximum per real row.
 static bool folds(const ApplyParams& p, int out_kind) {
-    return out_kind != OUT_INT4 && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 && p.T % (kTile / p.d) == 0;
+    return (out_kind == OUT_MXFP4 || out_kind == OUT_F32) && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 && p.T % (kTile / p.d) == 0;
 }
 
 bool mfma_preferred(const ApplyParams& p, int out_kind) {
@@ -771,6 +834,12 @@ hipError_t launch_mfma(const ApplyParams& p0, int out_kind, hipStream_t stream) 
             return wide ? launch_mfma_nw<OUT_INT4, 8>(p, fold_mask, stream) : launch_mfma_nw<OUT_INT4, 4>(p, fold_mask, stream);
         case OUT_MXFP4:
             return wide ? launch_mfma_nw<OUT_MXFP4, 8>(p, fold_mask, stream) : launch_mfma_nw<OUT_MXFP4, 4>(p, fold_mask, stream);
+        case OUT_INT4_ASYM:
+            return wide ? launch_mfma_nw<OUT_INT4_ASYM, 8>(p, fold_mask, stream)
+                        : launch_mfma_nw<OUT_INT4_ASYM, 4>(p, fold_mask, stream);
+        case OUT_FP4_TOKEN:
+            return wide ? launch_mfma_nw<OUT_FP4_TOKEN, 8>(p, fold_mask, stream)
+                        : launch_mfma_nw<OUT_FP4_TOKEN, 4>(p, fold_mask, stream);
         default:
             return wide ? launch_mfma_nw<OUT_F32, 8>(p, fold_mask, stream) : launch_mfma_nw<OUT_F32, 4>(p, fold_mask, stream);
     }

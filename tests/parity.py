@@ -147,6 +147,96 @@ def check_mxfp4(packed_gpu: np.ndarray, E_gpu: np.ndarray, ref: dict, x_bits: np
             rep.notes.append(f"mxfp4 code row {rows[j]} col {cols[j]}: gpu {g[j]:#x} oracle {o[j]:#x} v {v[j]!r}")
 
 
+def check_int4_asym(packed_gpu: np.ndarray, scales_gpu: np.ndarray, ref: dict, x_bits: np.ndarray,
+                    rep: ParityReport) -> None:
+    """Asymmetric per-token INT4: step within the tolerance of (max - min)/15; the integer zero
+    point exact unless min/s is within tolerance of a tie (then the oracle is re-quantised with
+    the library's zero point, counted as a scale exception); codes as for the symmetric case.
+    The quotient y/s inherits the error of y and of s: tolerance (1 + 2|v|/15) * 1e-5*||x||/s."""
+    l2 = row_l2(x_bits)
+    c_gpu = unpack_nibbles(packed_gpu).astype(np.int16)
+    rep.elements += c_gpu.size
+    s, z = ref["s64"], ref["z"]
+    s_g, z_g = scales_gpu[:, 0].astype(np.float64), scales_gpu[:, 1].astype(np.float64)
+    bad_scale = np.abs(s_g - s) > 2.0 * REL_TOL * l2 / 15.0
+    rep.scale_fail += int(bad_scale.sum())
+    if bad_scale.any():
+        i = int(np.argmax(bad_scale))
+        rep.notes.append(f"int4_asym step row {i}: gpu {s_g[i]!r} oracle {s[i]!r}")
+    safe = np.where(s > 0, s, 1.0)
+    lo_q = ref["y"].min(axis=1) / safe
+    zd = z_g != z
+    if zd.any():
+        tie = np.abs(lo_q - (np.floor(lo_q) + 0.5))
+        near = (np.abs(z_g - z) == 1) & (tie <= (1.0 + 2.0 * np.abs(lo_q) / 15.0) * REL_TOL * l2 / safe) & (s > 0)
+        ok_rows = zd & near
+        rep.scale_exceptions += int(ok_rows.sum())
+        rep.scale_fail += int((zd & ~near).sum())
+        if (zd & ~near).any():
+            i = int(np.argmax(zd & ~near))
+            rep.notes.append(f"int4_asym zero point row {i}: gpu {z_g[i]!r} oracle {z[i]!r} min/s {lo_q[i]!r}")
+        c_orc, _, _ = orc.quant_int4_asym_token(ref["y"], z_given=np.where(ok_rows, z_g, z))
+        z = np.where(ok_rows, z_g, z)
+    else:
+        c_orc = ref["codes"]
+    c_orc = c_orc.astype(np.int16)
+    mis = c_gpu != c_orc
+    if mis.any():
+        rows, cols = np.nonzero(mis)
+        v = ref["y"][rows, cols] / safe[rows]
+        bnd = np.floor(v) + 0.5
+        dist = np.abs(v - bnd)
+        adjacent = np.abs(c_gpu[rows, cols] - c_orc[rows, cols]) == 1
+        sides = np.minimum(c_gpu[rows, cols], c_orc[rows, cols]) + z[rows] == np.floor(v)
+        inA = adjacent & sides & (dist <= REL_TOL)
+        inB = adjacent & sides & (dist <= (1.0 + 2.0 * np.abs(v) / 15.0) * REL_TOL * l2[rows] / safe[rows]) & ~inA
+        fail = ~(inA | inB)
+        rep.code_mismatch_A += int(inA.sum())
+        rep.code_mismatch_B += int(inB.sum())
+        rep.code_mismatch_fail += int(fail.sum())
+        if fail.any():
+            k = int(np.argmax(fail))
+            rep.notes.append(f"int4_asym code row {rows[k]} col {cols[k]}: gpu {c_gpu[rows[k], cols[k]]} "
+                             f"oracle {c_orc[rows[k], cols[k]]} v {v[k]!r} z {z[rows[k]]!r}")
+
+
+def check_fp4_token(packed_gpu: np.ndarray, scales_gpu: np.ndarray, ref: dict, x_bits: np.ndarray,
+                    rep: ParityReport) -> None:
+    """FP4 with one scale per token: scale within tolerance / 6, codes as for MXFP4 with the
+    quotient tolerance (1 + |v|/6) * 1e-5*||x||/s."""
+    l2 = row_l2(x_bits)
+    c_gpu = unpack_nibbles(packed_gpu)
+    rep.neg_zero_seen += int((c_gpu == 8).sum())
+    c_gpu = np.where(c_gpu == 8, 0, c_gpu).astype(np.uint8)
+    c_orc = ref["codes"]
+    rep.elements += c_orc.size
+    s = ref["s64"]
+    bad_scale = np.abs(scales_gpu.astype(np.float64) - s) > REL_TOL * l2 / 6.0
+    rep.scale_fail += int(bad_scale.sum())
+    if bad_scale.any():
+        i = int(np.argmax(bad_scale))
+        rep.notes.append(f"fp4 scale row {i}: gpu {scales_gpu[i]!r} oracle {s[i]!r}")
+    safe = np.where(s > 0, s, 1.0)
+    mis = c_gpu != c_orc
+    if mis.any():
+        rows, cols = np.nonzero(mis)
+        v = np.abs(ref["y"][rows, cols]) / safe[rows]
+        k = np.abs(v[:, None] - E2M1_BOUNDARIES[None, :]).argmin(axis=1)
+        dist = np.abs(v - E2M1_BOUNDARIES[k])
+        g, o = c_gpu[rows, cols].astype(np.int16), c_orc[rows, cols].astype(np.int16)
+        same_sign = ((g & 8) == (o & 8)) | ((g & 7) == 0) | ((o & 7) == 0)
+        adjacent = (np.abs((g & 7) - (o & 7)) == 1) & same_sign & (np.minimum(g & 7, o & 7) == k)
+        inA = adjacent & (dist <= REL_TOL)
+        inB = adjacent & (dist <= (1.0 + v / 6.0) * REL_TOL * l2[rows] / safe[rows]) & ~inA
+        fail = ~(inA | inB)
+        rep.code_mismatch_A += int(inA.sum())
+        rep.code_mismatch_B += int(inB.sum())
+        rep.code_mismatch_fail += int(fail.sum())
+        if fail.any():
+            j = int(np.argmax(fail))
+            rep.notes.append(f"fp4 code row {rows[j]} col {cols[j]}: gpu {g[j]:#x} oracle {o[j]:#x} v {v[j]!r}")
+
+
 def compare_apply(x_bits, perm, b, fmt, packed_gpu, scales_gpu, y_gpu=None, rotate=None) -> ParityReport:
     """Run the oracle on x_bits and compare a GPU result (NumPy arrays) with it."""
     rep = ParityReport()
@@ -155,6 +245,10 @@ def compare_apply(x_bits, perm, b, fmt, packed_gpu, scales_gpu, y_gpu=None, rota
         check_prequant(y_gpu, ref["y"], x_bits, rep)
     if fmt == "int4":
         check_int4(packed_gpu, scales_gpu, ref, x_bits, rep)
-    else:
+    elif fmt == "mxfp4":
         check_mxfp4(packed_gpu, scales_gpu, ref, x_bits, rep)
+    elif fmt == "int4_asym":
+        check_int4_asym(packed_gpu, scales_gpu, ref, x_bits, rep)
+    else:
+        check_fp4_token(packed_gpu, scales_gpu, ref, x_bits, rep)
     return rep

@@ -260,3 +260,59 @@ def test_run_time_schedule_counters_come_back_to_zero():
         elif i % 10 == 9 or i >= 140:
             assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"launch {i} differs"
     torch.cuda.synchronize()
+
+
+# ---- the two per-token formats of Appendix B: asymmetric INT4, FP4 with a real scale -------------
+TOKEN_FORMAT_SHAPES = [
+    # (T, d, b list)
+    (37, 256, [16, 64, 256]),
+    (19, 1024, [32, 1024]),
+    (13, 3072, [16, 1024]),
+    (9, 4096, [128, 4096]),
+    (7, 8192, [32, 2048, 8192]),
+    (5, 14336, [128, 2048]),                 # ragged last tile: absent sub-blocks must not enter min / max
+    (4, 20480, [256, 4096]),
+]
+
+
+@pytest.mark.parametrize("fmt", ["int4_asym", "fp4_token"])
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("T,d,bs", TOKEN_FORMAT_SHAPES)
+def test_token_formats_against_oracle(T, d, bs, algo, fmt):
+    rng = np.random.default_rng(2000 + d)
+    x = rng.standard_t(4, size=(T, d)) * np.exp(rng.uniform(-3, 3, size=(T, 1)))
+    x[: T // 2] += 0.4 * np.exp(rng.uniform(-3, 3, size=(T // 2, 1)))         # off-centre rows
+    x[-1] = np.abs(x[-1]) + 0.5                                                # an all-positive row
+    x = synth.f64_to_bf16_bits(x)
+    perm = rng.permutation(d).astype(np.int32)
+    for b in bs:
+        rotate = orc.fwht_f64 if b > 4096 else None
+        assert_parity(x, None, b, fmt, algo, rotate=rotate, label="token-format/identity")
+        assert_parity(x, perm, b, fmt, algo, rotate=rotate, label="token-format/perm")
+
+
+@pytest.mark.parametrize("fmt", ["int4_asym", "fp4_token"])
+def test_token_formats_structured_rows(fmt):
+    d, b = 1024, 64
+    rows = [np.zeros(d), np.full(d, 0.75), np.full(d, -2.0)]
+    r = np.zeros(d); r[5] = 3.0; rows.append(r)
+    r = np.zeros(d); r[700] = -1.5; rows.append(r)
+    rows.append(np.where(np.arange(d) % 2 == 0, 1.0, -1.0))
+    x = synth.f64_to_bf16_bits(np.array(rows))
+    for algo in ALGOS:
+        codes, scales, y = run_gpu(x, None, b, fmt, algo)
+        rep = parity.compare_apply(x, None, b, fmt, codes, scales, y)
+        assert rep.ok(), (algo, rep.summary(), rep.notes[:5])
+        assert np.all(codes[0] == 0) and np.all(scales[0] == 0)              # all-zero row
+
+
+@pytest.mark.parametrize("fmt,T,d,b,with_perm", [("int4_asym", 4099, 4096, 128, True), ("fp4_token", 4099, 4096, 128, True),
+                                                  ("int4_asym", 1030, 14336, 128, False), ("fp4_token", 2051, 8192, 32, True)])
+def test_token_formats_run_time_schedule(fmt, T, d, b, with_perm):
+    rng = np.random.default_rng(T + d + b + 1)
+    x = synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d)) * np.exp(rng.uniform(-2, 2, size=(T, 1))) + 0.1)
+    perm = rng.permutation(d).astype(np.int32) if with_perm else None
+    codes, scales, _ = run_gpu(x, perm, b, fmt, "mfma", want_y=False)
+    rep = parity.compare_apply(x, perm, b, fmt, codes, scales, None)
+    print("       ", rep.summary(), flush=True)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
