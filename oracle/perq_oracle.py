@@ -42,6 +42,7 @@ __all__ = [
     "bf16_bits_to_f64", "sylvester_hadamard", "permute_channels", "block_hadamard",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
     "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
+    "merge_into_weights", "w4a4_matmul",
     "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
     "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
 ]
@@ -352,6 +353,24 @@ def brute_force_min_max_block_mass(a, b: int) -> float:
 
     rec(list(range(d)), 0.0)
     return best[0]
+
+
+# ----------------------------------------------------------------------------------------
+# consumer of the codes: W4A4 product with P and R~ merged into the weights
+# (Remark "Merging Permutations", Section 4;  R~ R~^T = I, Notation of Section 1)
+# ----------------------------------------------------------------------------------------
+def merge_into_weights(W: np.ndarray, perm, b: int) -> np.ndarray:
+    """W~ = R~^T P^T W for W in R^{d x N} (row i = input channel i), returned transposed as
+    [N, d]: row n is column n of W gathered through perm and block-rotated -- the same P, R~ the
+    activations go through, since (X P R~)(R~^T P^T W) = X W."""
+    return block_hadamard(permute_channels(np.ascontiguousarray(W.T, dtype=np.float64), perm), b)
+
+
+def w4a4_matmul(codes_a: np.ndarray, s_a: np.ndarray, codes_w: np.ndarray, s_w: np.ndarray):
+    """out[t, n] = s_a[t] * s_w[n] * sum_i codes_a[t, i] * codes_w[n, i] for symmetric INT4 codes
+    (Eq. 4 with z = 0 on both operands).  Returns (integer sums int64 [T, N], out float64)."""
+    acc = codes_a.astype(np.int64) @ codes_w.astype(np.int64).T
+    return acc, acc.astype(np.float64) * np.asarray(s_a, np.float64)[:, None] * np.asarray(s_w, np.float64)[None, :]
 
 
 # ----------------------------------------------------------------------------------------

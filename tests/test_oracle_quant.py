@@ -325,3 +325,46 @@ def test_apply_new_formats_shapes():
     assert r["scales"].shape == (4, 2) and r["packed"].shape == (4, 32) and r["codes"].max() <= 15
     r = orc.perq_apply(x, None, 16, "fp4_token")
     assert r["scales"].shape == (4,) and r["packed"].shape == (4, 32)
+
+
+# ---- merged weights and the W4A4 product (Remark "Merging Permutations", Section 4) -----------
+def test_merged_weights_reproduce_the_unrotated_product():
+    rng = _rng(31)
+    d, N, b = 128, 24, 32
+    X = rng.standard_normal((10, d))
+    W = rng.standard_normal((d, N))
+    perm = rng.permutation(d)
+    Y = orc.block_hadamard(orc.permute_channels(X, perm), b)            # X P R~
+    Wt = orc.merge_into_weights(W, perm, b)                             # (R~^T P^T W)^T
+    assert np.allclose(Y @ Wt.T, X @ W, rtol=1e-12, atol=1e-12)
+    # without the permutation on the weight side the product is a different one
+    assert not np.allclose(Y @ orc.merge_into_weights(W, None, b).T, X @ W, atol=1e-3)
+
+
+def test_w4a4_matmul_is_the_product_of_the_dequantised_operands():
+    rng = _rng(32)
+    ca = rng.integers(-7, 8, size=(9, 64)).astype(np.int8)
+    cw = rng.integers(-7, 8, size=(5, 64)).astype(np.int8)
+    sa, sw = rng.uniform(0.01, 2, size=9), rng.uniform(0.01, 2, size=5)
+    acc, out = orc.w4a4_matmul(ca, sa, cw, sw)
+    brute = [[sum(int(ca[t, i]) * int(cw[n, i]) for i in range(64)) for n in range(5)] for t in range(9)]
+    assert acc.tolist() == brute
+    assert np.allclose(out, orc.dequant_int4(ca, sa) @ orc.dequant_int4(cw, sw).T, rtol=1e-13)
+
+
+def test_w4a4_end_to_end_error_is_quantisation_error_only():
+    """Q(X P R~) Q(R~^T P^T W) stays within the product of the two INT4 error bounds of X W."""
+    rng = _rng(33)
+    d, N, b = 256, 16, 64
+    X, W = rng.standard_normal((12, d)), rng.standard_normal((d, N))
+    perm = rng.permutation(d)
+    Y = orc.block_hadamard(orc.permute_channels(X, perm), b)
+    Wt = orc.merge_into_weights(W, perm, b)
+    ca, sa = orc.quant_int4_sym_token(Y)
+    cw, sw = orc.quant_int4_sym_token(Wt)
+    _, out = orc.w4a4_matmul(ca, sa, cw, sw)
+    # |y~ w~ - y w| <= |dy||w| + |y||dw| + |dy||dw| with |dy|_2 <= sqrt(d) s_a / 2 etc.
+    ey, ew = math.sqrt(d) * sa / 2, math.sqrt(d) * sw / 2
+    ny, nw = np.linalg.norm(Y, axis=1), np.linalg.norm(Wt, axis=1)
+    bound = ey[:, None] * nw[None, :] + ny[:, None] * ew[None, :] + ey[:, None] * ew[None, :]
+    assert np.all(np.abs(out - X @ W) <= bound * (1 + 1e-12))
