@@ -113,6 +113,8 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  *   scales   INT4:  device float [T], s_t = ||y_t||_inf / 7 (0 for an all-zero row)
  *            MXFP4: device uint8 [T, d/32], biased exponent E, scale = 2^(E-127),
  *                   E - 127 = floor(log2 ||group||_inf) - 2, clamped to [0,254], 0 for a zero group
+ *            INT4_ASYM_TOKEN: device float [T][2] = (step, zero point); FP4_TOKEN: device float [T]
+ *                   (see perq_fmt_t)
  *   d % 32 == 0 is required for both formats; T == 0 is OK and does nothing.
  *
  * Rounding is to nearest, ties to even; MXFP4 saturates at +-6 and always writes zero as +0.
@@ -135,6 +137,25 @@ perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, int64_t T, 
 perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
                                       const int32_t* perm, int32_t b, perq_algo_t algo,
                                       float* y, void* hip_stream);
+
+/*
+ * Reference consumer of the codes (Remark "Merging Permutations", Section 4): with P and the block
+ * rotation merged into the weights, W~ = R~^T P^T W, the product of the two quantized operands
+ * stands for X W.  Both operands are PERQ_FMT_INT4_SYM_TOKEN outputs of
+ * perq_permute_rotate_quant: the activations [T, d], and the weights as the rows of W^T [N, d] run
+ * through the same perm and b (one step per output channel).
+ *
+ *   out[t, n] = a_scales[t] * w_scales[n] * sum_i a_code[t, i] * w_code[n, i]
+ *
+ *   a_codes  device, uint8 [T, d/2], 16-byte aligned;   a_scales  device, float [T]
+ *   w_codes  device, uint8 [N, d/2], 16-byte aligned;   w_scales  device, float [N]
+ *   out      device, float [T, ldo], ldo >= N
+ * The integer sums are exact; the two multiplications are fp32, left to right.  A plain integer
+ * kernel for checking the layout end to end, not a tuned GEMM.  T == 0 or N == 0 does nothing.
+ */
+perq_status_t perq_w4a4_gemm_ref(const uint8_t* a_codes, const float* a_scales, int64_t T,
+                                 const uint8_t* w_codes, const float* w_scales, int32_t N, int32_t d,
+                                 float* out, int64_t ldo, void* hip_stream);
 
 #ifdef __cplusplus
 }

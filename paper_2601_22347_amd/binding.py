@@ -23,7 +23,7 @@ ALGO = {"auto": PERQ_ALGO_AUTO, "butterfly": PERQ_ALGO_BUTTERFLY, "mfma": PERQ_A
 
 EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colabs_mean",
            "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
-           "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32"]
+           "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref"]
 
 _lib = None
 
@@ -63,6 +63,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
                                                    vp, vp, vp]
     lib.perq_permute_rotate_f32.restype = ctypes.c_int
     lib.perq_permute_rotate_f32.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, vp, vp]
+    lib.perq_w4a4_gemm_ref.argtypes = [vp, vp, i64, vp, vp, i32, i32, vp, i64, vp]
+    lib.perq_w4a4_gemm_ref.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -165,6 +167,21 @@ def perq_permute_rotate_f32(x, perm, b: int, y=None, stream=None, algo: str = "a
                                         _dev_ptr(y), _stream_ptr(stream))
     _check(st, "perq_permute_rotate_f32")
     return y
+
+
+def perq_w4a4_gemm_ref(a_codes, a_scales, w_codes, w_scales, out=None, stream=None):
+    """out[t, n] = a_scales[t] * w_scales[n] * <a_codes[t], w_codes[n]> for symmetric INT4 operands
+    (CUDA uint8 [T, d/2] / [N, d/2], float32 [T] / [N]); returns CUDA float32 [T, N]."""
+    import torch
+    T, N, d = a_codes.shape[0], w_codes.shape[0], a_codes.shape[1] * 2
+    if w_codes.shape[1] * 2 != d or not a_codes.is_contiguous() or not w_codes.is_contiguous():
+        raise ValueError("a_codes [T, d/2] and w_codes [N, d/2] must be contiguous with the same d")
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float32, device=a_codes.device)
+    st = load().perq_w4a4_gemm_ref(_dev_ptr(a_codes), _dev_ptr(a_scales), T, _dev_ptr(w_codes), _dev_ptr(w_scales),
+                                   N, d, _dev_ptr(out), out.stride(0) if T else N, _stream_ptr(stream))
+    _check(st, "perq_w4a4_gemm_ref")
+    return out
 
 
 def bits_to_device(bits: np.ndarray, device="cuda"):

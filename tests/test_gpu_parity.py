@@ -316,3 +316,46 @@ def test_token_formats_run_time_schedule(fmt, T, d, b, with_perm):
     rep = parity.compare_apply(x, perm, b, fmt, codes, scales, None)
     print("       ", rep.summary(), flush=True)
     assert rep.ok(), (rep.summary(), rep.notes[:5])
+
+
+# ---- the codes consumed: W4A4 product with P and the rotation merged into the weights -----------
+@pytest.mark.parametrize("T,N,d,b", [(70, 50, 256, 32), (33, 130, 4096, 128), (5, 3, 1024, 1024)])
+def test_w4a4_gemm_against_oracle_and_unrotated_product(T, N, d, b):
+    torch = _torch()
+    rng = np.random.default_rng(T + N + d)
+    x_bits = synth.f64_to_bf16_bits(rng.standard_t(5, size=(T, d)))
+    wt_bits = synth.f64_to_bf16_bits(rng.standard_normal((N, d)) * 0.05)        # rows of W^T
+    perm = rng.permutation(d).astype(np.int32)
+    perm_t = torch.from_numpy(perm).cuda()
+    xa, wa = binding.bits_to_device(x_bits), binding.bits_to_device(wt_bits)
+    ca, sa = binding.perq_permute_rotate_quant(xa, perm_t, b, "int4")
+    cw, sw = binding.perq_permute_rotate_quant(wa, perm_t, b, "int4")
+    out = binding.perq_w4a4_gemm_ref(ca, sa, cw, sw).cpu().numpy().astype(np.float64)
+    # (1) exactly the oracle's product of the library's own codes and scales
+    def signed(c):
+        n = parity.unpack_nibbles(c.cpu().numpy()).astype(np.int16)
+        return np.where(n >= 8, n - 16, n).astype(np.int8)
+    acc, want = orc.w4a4_matmul(signed(ca), sa.cpu().numpy(), signed(cw), sw.cpu().numpy())
+    assert np.all(np.abs(out - want) <= 4e-7 * np.abs(want) + 1e-30)
+    # (2) it stands for X W: within the two operands' INT4 error bounds of the unrotated product
+    X, Wt = orc.bf16_bits_to_f64(x_bits), orc.bf16_bits_to_f64(wt_bits)
+    s_a, s_w = sa.cpu().numpy().astype(np.float64), sw.cpu().numpy().astype(np.float64)
+    ey, ew = np.sqrt(d) * s_a / 2, np.sqrt(d) * s_w / 2
+    ny, nw = np.linalg.norm(X, axis=1), np.linalg.norm(Wt, axis=1)
+    bound = ey[:, None] * nw[None, :] + ny[:, None] * ew[None, :] + ey[:, None] * ew[None, :]
+    assert np.all(np.abs(out - X @ Wt.T) <= bound * (1 + 1e-4))
+    # (3) and the rotation really cancels: pre-quantization outputs of both sides multiply to X W
+    y = binding.perq_permute_rotate_f32(xa, perm_t, b).cpu().numpy().astype(np.float64)
+    wy = binding.perq_permute_rotate_f32(wa, perm_t, b).cpu().numpy().astype(np.float64)
+    ref = X @ Wt.T
+    assert np.all(np.abs(y @ wy.T - ref) <= 1e-5 * ny[:, None] * nw[None, :] * 2)
+
+
+def test_w4a4_gemm_argument_checks():
+    torch = _torch()
+    a = torch.zeros((4, 16), dtype=torch.uint8, device="cuda")
+    s = torch.ones(4, device="cuda")
+    out = binding.perq_w4a4_gemm_ref(a, s, a[:0], s[:0])
+    assert out.shape == (4, 0)
+    with pytest.raises(ValueError):
+        binding.perq_w4a4_gemm_ref(a, s, torch.zeros((4, 8), dtype=torch.uint8, device="cuda"), s)
