@@ -42,7 +42,7 @@ __all__ = [
     "bf16_bits_to_f64", "sylvester_hadamard", "permute_channels", "block_hadamard",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
     "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
-    "merge_into_weights", "w4a4_matmul",
+    "merge_into_weights", "w4a4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics",
     "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
     "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
 ]
@@ -353,6 +353,51 @@ def brute_force_min_max_block_mass(a, b: int) -> float:
 
     rec(list(range(d)), 0.0)
     return best[0]
+
+
+# ----------------------------------------------------------------------------------------
+# alternative permutations of the ablation (Appendix C, "Permutations") and the quantities of
+# Propositions 1, 2 and Corollary 3.3 per token
+# ----------------------------------------------------------------------------------------
+def colabs_max(X: np.ndarray) -> np.ndarray:
+    """Per-channel l_inf over the calibration tokens: the statistic of "absmax" and ZigZag."""
+    return np.abs(X).max(axis=0)
+
+
+def perm_sorted_desc(stat) -> np.ndarray:
+    """"absmax": coordinates in descending order of the statistic (stable: lower channel first)."""
+    stat = np.asarray(stat, dtype=np.float64)
+    return np.argsort(-stat, kind="stable").astype(np.int32)
+
+
+def perm_zigzag(stat, b: int) -> np.ndarray:
+    """ZigZag.  The paper only names the strategy (coordinates sorted by their l_inf and dealt to
+    the blocks in a zigzag) and cites it; reading: rank r of the stable descending order goes to
+    block r mod n on even rounds floor(r / n) and to block n - 1 - (r mod n) on odd rounds; blocks
+    are concatenated in index order, each in the order its coordinates arrived."""
+    stat = np.asarray(stat, dtype=np.float64)
+    d = stat.size
+    n = d // b
+    order = np.argsort(-stat, kind="stable")
+    blocks = [[] for _ in range(n)]
+    for r, ch in enumerate(order):
+        rnd, pos = divmod(r, n)
+        blocks[pos if rnd % 2 == 0 else n - 1 - pos].append(int(ch))
+    return np.array([i for blk in blocks for i in blk], dtype=np.int32)
+
+
+def block_diagnostics(x_bits: np.ndarray, perm, b: int) -> np.ndarray:
+    """float64 [T, 4] per token: ||X||_inf, ||X||_1, max_j ||(XP)_{j}||_1, ||XP R~||_inf.
+
+    From these: delta = ||X||_1 / (d ||X||_inf) (Proposition 1); the bound of Proposition 2,
+    max_j delta_j sqrt(b) ||X_j||_inf = max_j ||X_j||_1 / sqrt(b) = Z(b; XP) of Corollary 3.3;
+    the suppression ratio ||XP R~||_inf / ||X||_inf."""
+    X = bf16_bits_to_f64(x_bits)
+    Xp = permute_channels(X, perm)
+    T, d = X.shape
+    l1b = np.abs(Xp).reshape(T, d // b, b).sum(axis=2).max(axis=1)
+    y = block_hadamard(Xp, b)
+    return np.stack([np.abs(X).max(axis=1), np.abs(X).sum(axis=1), l1b, np.abs(y).max(axis=1)], axis=1)
 
 
 # ----------------------------------------------------------------------------------------

@@ -96,3 +96,55 @@ def test_greedy_beats_identity_on_outlier_workloads():
         bound_g = np.abs(Xa[:, perm]).reshape(wl.T, -1, b).sum(axis=2).max(axis=1)
         bound_i = np.abs(Xa).reshape(wl.T, -1, b).sum(axis=2).max(axis=1)
         assert bound_g.mean() < bound_i.mean()
+
+
+# ---- alternative permutations (Appendix C) and the per-token quantities of Section 3 ----------
+def test_sorted_and_zigzag_permutations_closed_forms():
+    stat = np.array([5.0, 1.0, 7.0, 3.0, 8.0, 2.0, 6.0, 4.0])
+    assert orc.perm_sorted_desc(stat).tolist() == [4, 2, 6, 0, 7, 3, 5, 1]
+    # n = 4 blocks of 2: ranks 0..3 go to blocks 0..3, ranks 4..7 to blocks 3..0
+    assert orc.perm_zigzag(stat, 2).tolist() == [4, 1, 2, 5, 6, 3, 0, 7]
+    # n = 2 blocks of 4: rounds alternate direction
+    assert orc.perm_zigzag(stat, 4).tolist() == [4, 0, 7, 1, 2, 6, 3, 5]
+    # one block: the sorted order; equal statistics: stable
+    assert orc.perm_zigzag(stat, 8).tolist() == orc.perm_sorted_desc(stat).tolist()
+    assert orc.perm_sorted_desc(np.ones(6)).tolist() == list(range(6))
+    rng = np.random.default_rng(5)
+    for d, b in ((64, 16), (96, 32), (128, 128)):
+        p = orc.perm_zigzag(rng.random(d), b)
+        assert sorted(p.tolist()) == list(range(d))
+    # on a geometric sequence the serpentine beats the sorted order by construction
+    g = 2.0 ** -np.arange(16.0)
+    assert orc.block_masses(g, orc.perm_zigzag(g, 4), 4).max() < orc.block_masses(g, orc.perm_sorted_desc(g), 4).max()
+
+
+def test_block_diagnostics_bounds_and_special_cases():
+    from paper_2601_22347_amd import synth
+    rng = np.random.default_rng(6)
+    T, d = 40, 256
+    x = rng.standard_t(3, size=(T, d))
+    x[:, [3, 4, 5]] *= 40
+    bits = synth.f64_to_bf16_bits(x)
+    X = orc.bf16_bits_to_f64(bits)
+    perm = orc.massdiff_greedy(orc.colabs_mean(X), 32)
+    for pm in (None, perm):
+        for b in (16, 32, 256):
+            if pm is not None and b != 32:
+                continue
+            D = orc.block_diagnostics(bits, pm, b)
+            amax, l1, l1b, ymax = D.T
+            assert np.allclose(amax, np.abs(X).max(axis=1)) and np.allclose(l1, np.abs(X).sum(axis=1))
+            assert np.all(ymax <= l1b / np.sqrt(b) * (1 + 1e-12))               # Proposition 2
+            assert np.all(l1b >= l1 / (d // b) * (1 - 1e-12)) and np.all(l1b <= l1 * (1 + 1e-12))
+            if b == d:
+                assert np.allclose(l1b, l1)                                      # Proposition 1 is the case b = d
+    # Corollary 3.3: Z(b) <= sqrt(k) Z(b') for b = k b'
+    Z = {b: orc.block_diagnostics(bits, None, b)[:, 2] / np.sqrt(b) for b in (16, 32, 64, 256)}
+    for b, bp in ((32, 16), (64, 16), (256, 64), (256, 32)):
+        assert np.all(Z[b] <= np.sqrt(b / bp) * Z[bp] * (1 + 1e-12))
+    # the calibrated permutation lowers the mean bound on data with the calibrated outlier channels
+    assert orc.block_diagnostics(bits, perm, 32)[:, 2].mean() < orc.block_diagnostics(bits, None, 32)[:, 2].mean()
+    # one-hot row: every quantity in closed form
+    r = np.zeros((1, 64)); r[0, 10] = -2.0
+    D = orc.block_diagnostics(synth.f64_to_bf16_bits(r), None, 16)
+    assert np.allclose(D[0], [2.0, 2.0, 2.0, 0.5])
