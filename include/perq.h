@@ -89,6 +89,14 @@ perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int
                                void* hip_stream);
 
 /*
+ * max_k |x[k, i]| per channel, the statistic of the "absmax" and ZigZag permutations compared in
+ * Appendix C ("Permutations").  Arguments, workspace size and errors as perq_colabs_mean; exact.
+ */
+perq_status_t perq_colabs_absmax(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                                 float* out_max, void* workspace, size_t workspace_bytes,
+                                 void* hip_stream);
+
+/*
  * Algorithm 1 (mass diffusion), host side, on the sufficient statistic a = colabs_mean.
  *
  *   colabs_mean  host, float [d], finite and >= 0
@@ -99,6 +107,17 @@ perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int
  * Any b >= 1 dividing d is accepted here (the rotation's b >= 16 limit does not apply).
  */
 perq_status_t perq_massdiff_perm(const float* colabs_mean, int32_t d, int32_t b, int32_t* perm_out);
+
+/*
+ * The other calibrated permutations of Appendix C ("Permutations"), host side, same output
+ * convention as perq_massdiff_perm.  stat: host, float [d], finite and >= 0.
+ *   perq_perm_sorted  "absmax": channels in descending order of stat (ties: lower channel first).
+ *   perq_perm_zigzag  the paper only names the strategy; taken: rank r of that order goes to block
+ *                     r mod n on even rounds floor(r/n) and to block n-1-(r mod n) on odd rounds
+ *                     (n = d/b), each block in arrival order.
+ */
+perq_status_t perq_perm_sorted(const float* stat, int32_t d, int32_t* perm_out);
+perq_status_t perq_perm_zigzag(const float* stat, int32_t d, int32_t b, int32_t* perm_out);
 
 /* OK iff perm (host, int32 [d]) is a bijection on [0, d); INVALID_ARG otherwise. */
 perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
@@ -137,6 +156,16 @@ perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, int64_t T, 
 perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
                                       const int32_t* perm, int32_t b, perq_algo_t algo,
                                       float* y, void* hip_stream);
+
+/*
+ * Per-token quantities of Section 3 for a given permutation and block size (device):
+ *   out[t] = ( ||x_t||_inf,  ||x_t||_1,  max_j ||(x_t P)_{j}||_1,  ||x_t P R~||_inf )     float [T][4]
+ * so that delta = out[1] / (d out[0]) (Proposition 1), the bound of Proposition 2 and Z(b; xP) of
+ * Corollary 3.3 are out[2] / sqrt(b), and the outlier suppression ratio is out[3] / out[0].
+ * Arguments and errors as perq_permute_rotate_f32; out 16-byte aligned.  fp32 sums in a fixed order.
+ */
+perq_status_t perq_block_diagnostics(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                     const int32_t* perm, int32_t b, float* out, void* hip_stream);
 
 /*
  * Reference consumer of the codes (Remark "Merging Permutations", Section 4): with P and the block

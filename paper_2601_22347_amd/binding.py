@@ -23,7 +23,8 @@ ALGO = {"auto": PERQ_ALGO_AUTO, "butterfly": PERQ_ALGO_BUTTERFLY, "mfma": PERQ_A
 
 EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colabs_mean",
            "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
-           "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref"]
+           "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
+           "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics"]
 
 _lib = None
 
@@ -65,6 +66,14 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_permute_rotate_f32.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, vp, vp]
     lib.perq_w4a4_gemm_ref.argtypes = [vp, vp, i64, vp, vp, i32, i32, vp, i64, vp]
     lib.perq_w4a4_gemm_ref.restype = ctypes.c_int
+    lib.perq_colabs_absmax.argtypes = [vp, i64, i32, i64, vp, vp, sz, vp]
+    lib.perq_colabs_absmax.restype = ctypes.c_int
+    lib.perq_perm_sorted.argtypes = [vp, i32, vp]
+    lib.perq_perm_sorted.restype = ctypes.c_int
+    lib.perq_perm_zigzag.argtypes = [vp, i32, i32, vp]
+    lib.perq_perm_zigzag.restype = ctypes.c_int
+    lib.perq_block_diagnostics.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
+    lib.perq_block_diagnostics.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -107,6 +116,22 @@ def perq_massdiff_perm(colabs_mean: np.ndarray, b: int) -> np.ndarray:
     return perm
 
 
+def perq_perm_sorted(stat: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(stat, dtype=np.float32)
+    perm = np.empty(a.shape[0], dtype=np.int32)
+    _check(load().perq_perm_sorted(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], perm.ctypes.data_as(ctypes.c_void_p)),
+           "perq_perm_sorted")
+    return perm
+
+
+def perq_perm_zigzag(stat: np.ndarray, b: int) -> np.ndarray:
+    a = np.ascontiguousarray(stat, dtype=np.float32)
+    perm = np.empty(a.shape[0], dtype=np.int32)
+    _check(load().perq_perm_zigzag(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], int(b),
+                                   perm.ctypes.data_as(ctypes.c_void_p)), "perq_perm_zigzag")
+    return perm
+
+
 def perq_perm_validate(perm: np.ndarray) -> bool:
     p = np.ascontiguousarray(perm, dtype=np.int32)
     return load().perq_perm_validate(p.ctypes.data_as(ctypes.c_void_p), p.shape[0]) == PERQ_OK
@@ -124,6 +149,31 @@ def perq_colabs_mean(x, out=None, stream=None):
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
     st = lib.perq_colabs_mean(_dev_ptr(x), M, d, ldx, _dev_ptr(out), _dev_ptr(ws), nbytes, _stream_ptr(stream))
     _check(st, "perq_colabs_mean")
+    return out
+
+
+def perq_colabs_absmax(x, out=None, stream=None):
+    """x: CUDA bf16 [M, d] -> CUDA float32 [d], max_k |x[k, i]|."""
+    import torch
+    M, d, ldx = _check_x(x)
+    lib = load()
+    if out is None:
+        out = torch.empty(d, dtype=torch.float32, device=x.device)
+    nbytes = lib.perq_colabs_mean_workspace_bytes(M, d)
+    ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
+    st = lib.perq_colabs_absmax(_dev_ptr(x), M, d, ldx, _dev_ptr(out), _dev_ptr(ws), nbytes, _stream_ptr(stream))
+    _check(st, "perq_colabs_absmax")
+    return out
+
+
+def perq_block_diagnostics(x, perm, b: int, out=None, stream=None):
+    """x: CUDA bf16 [T, d] -> CUDA float32 [T, 4] = (|x|_inf, |x|_1, max block l1 of xP, |xP R~|_inf)."""
+    import torch
+    T, d, ldx = _check_x(x)
+    if out is None:
+        out = torch.empty((T, 4), dtype=torch.float32, device=x.device)
+    st = load().perq_block_diagnostics(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), int(b), _dev_ptr(out), _stream_ptr(stream))
+    _check(st, "perq_block_diagnostics")
     return out
 
 

@@ -138,3 +138,16 @@ extern "C" perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t
     p.y = y;
     return perq::dispatch(p, perq::OUT_F32, algo, static_cast<hipStream_t>(hip_stream));
 }
+
+extern "C" perq_status_t perq_block_diagnostics(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
+                                                const int32_t* perm, int32_t b, float* out, void* hip_stream) {
+    perq::ApplyParams p;
+    const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
+    if (st != PERQ_OK || p.T == 0) return st;
+    if (out == nullptr) return PERQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(out) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
+    p.y = out;
+    return perq::launch_butterfly(p, perq::OUT_DIAG, static_cast<hipStream_t>(hip_stream)) == hipSuccess
+               ? PERQ_OK
+               : PERQ_ERR_LAUNCH;
+}

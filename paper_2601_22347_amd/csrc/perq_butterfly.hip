@@ -119,6 +119,23 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
             }
         }
 
+        // ---- diagnostics: statistics of the permuted, not yet rotated values ------------------
+        float dg_amax = 0.0f, dg_l1 = 0.0f, dg_blk = 0.0f;
+        if constexpr (OUT == OUT_DIAG) {
+            float s0 = 0.0f, s1 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { s0 += fabsf(v[i]); s1 += fabsf(v[16 + i]); }
+            if (active) {
+                dg_amax = absmax(v);
+                dg_l1 = s0 + s1;
+                dg_blk = b == 16 ? fmaxf(s0, s1) : dg_l1;     // b >= 64: summed over lanes below
+            }
+            if (b >= 64) {
+                float* sums = reinterpret_cast<float*>(lds + g.red_off) + 64;
+                if (active) sums[r * g.nt + t] = dg_l1;
+            }
+        }
+
         // ---- rotation: unnormalised +-1 butterflies ----------------------------------------
         reg_stages<32>(v, b);                               // distances 1..16 (16 only if b >= 32)
         if (b >= 64) lane_stage<1>(v, sgn[0]);
@@ -164,6 +181,46 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
                     yo[j] = make_float4(v[4 * j] * p.rsqrt_b, v[4 * j + 1] * p.rsqrt_b,
                                         v[4 * j + 2] * p.rsqrt_b, v[4 * j + 3] * p.rsqrt_b);
             }
+        } else if constexpr (OUT == OUT_DIAG) {
+            // per token: ||x||_inf, ||x||_1, largest block l1 of the permuted row, ||y||_inf
+            __syncthreads();                    // the lane sums are in LDS
+            if (b >= 64) {
+                const int lanes = b >> 5;       // lanes per block; the first of each adds them in order
+                const float* sums = reinterpret_cast<const float*>(lds + g.red_off) + 64;
+                dg_blk = 0.0f;
+                if (active && (t & (lanes - 1)) == 0) {
+                    for (int k = 0; k < lanes; ++k) dg_blk += sums[r * g.nt + t + k];
+                }
+            }
+            float m[4] = {dg_amax, dg_l1, dg_blk, active ? absmax(v) * p.rsqrt_b : 0.0f};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // sums and maxima of non-negative numbers; lanes past the row hold zeros
+#define PERQ_DIAG_STEP(M)                                              \
+    if (g.nt > M) { const float o = lane_xor<M>(m[j]); m[j] = j == 1 ? m[j] + o : fmaxf(m[j], o); }
+                PERQ_DIAG_STEP(1) PERQ_DIAG_STEP(2) PERQ_DIAG_STEP(4) PERQ_DIAG_STEP(8) PERQ_DIAG_STEP(16) PERQ_DIAG_STEP(32)
+#undef PERQ_DIAG_STEP
+            }
+            if (g.waves_per_row > 1) {
+                float* red = reinterpret_cast<float*>(lds + g.red_off);
+                const int wave = tid >> 6;
+                if (lane == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) red[4 * wave + j] = m[j];
+                }
+                __syncthreads();
+                const int w0 = (r * g.nt) >> 6;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) m[j] = 0.0f;
+                for (int w = 0; w < g.waves_per_row; ++w) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float o = red[4 * (w0 + w) + j];
+                        m[j] = j == 1 ? m[j] + o : fmaxf(m[j], o);
+                    }
+                }
+            }
+            if (live && t == 0) reinterpret_cast<float4*>(p.y)[row] = make_float4(m[0], m[1], m[2], m[3]);
         } else if constexpr (OUT == OUT_MXFP4) {
             if (p.odd_norm != 1.0f) {
 #pragma unroll
@@ -274,7 +331,8 @@ hipError_t launch_butterfly_out(const ApplyParams& p, hipStream_t stream) {
     const uint32_t stage_bytes = (uint32_t)g.rows * g.row_bytes;
     const uint32_t xchg_bytes = p.b >= 4096 ? (uint32_t)g.rows * (uint32_t)p.d * 4u : 0u;
     g.red_off = stage_bytes > xchg_bytes ? stage_bytes : xchg_bytes;
-    const uint32_t lds_bytes = g.red_off + 64u * sizeof(float);
+    // (+ one float per lane of every row: the lane sums of the diagnostics kernel)
+    const uint32_t lds_bytes = g.red_off + 64u * sizeof(float) + (OUT == OUT_DIAG ? (uint32_t)(g.rows * g.nt) * 4u : 0u);
 
     // register budget follows the workgroup size: 256 threads for rows up to 8192, 512 up to
     // 16384, 1024 beyond
@@ -306,6 +364,7 @@ hipError_t launch_butterfly(const ApplyParams& p, int out_kind, hipStream_t stre
         case OUT_MXFP4: return launch_butterfly_out<OUT_MXFP4>(p, stream);
         case OUT_INT4_ASYM: return launch_butterfly_out<OUT_INT4_ASYM>(p, stream);
         case OUT_FP4_TOKEN: return launch_butterfly_out<OUT_FP4_TOKEN>(p, stream);
+        case OUT_DIAG: return launch_butterfly_out<OUT_DIAG>(p, stream);
         default: return launch_butterfly_out<OUT_F32>(p, stream);
     }
 }

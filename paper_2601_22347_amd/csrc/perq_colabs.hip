@@ -1,4 +1,6 @@
-// a_i = (1/M) sum_k |x[k,i]|  -- the sort key of Algorithm 1 -- as two deterministic passes.
+// a_i = (1/M) sum_k |x[k,i]|  -- the sort key of Algorithm 1 -- as two deterministic passes; the
+// same two passes with max in place of + give max_k |x[k,i]|, the statistic of the "absmax" and
+// ZigZag permutations of the ablation (Appendix C).
 //
 // Pass 1: the M rows are cut into S slices; workgroup (column tile, slice) adds |x| over its
 // rows, each lane owning 8 adjacent columns (one 16-byte bf16 load per row), and writes fp32
@@ -34,6 +36,7 @@ ColabsPlan colabs_plan(int64_t M, int32_t d) {
     return pl;
 }
 
+template <bool MAXSTAT>
 __global__ void __launch_bounds__(kThreads)
 colabs_partial_kernel(const uint16_t* __restrict__ x, int64_t M, int32_t d, int64_t ldx,
                       int rows_per_slice, float* __restrict__ part) {
@@ -49,8 +52,9 @@ colabs_partial_kernel(const uint16_t* __restrict__ x, int64_t M, int32_t d, int6
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            acc[2 * q] += fabsf(bf16lo_to_f32(ww[q]));
-            acc[2 * q + 1] += fabsf(bf16hi_to_f32(ww[q]));
+            const float lo = fabsf(bf16lo_to_f32(ww[q])), hi = fabsf(bf16hi_to_f32(ww[q]));
+            acc[2 * q] = MAXSTAT ? fmaxf(acc[2 * q], lo) : acc[2 * q] + lo;
+            acc[2 * q + 1] = MAXSTAT ? fmaxf(acc[2 * q + 1], hi) : acc[2 * q + 1] + hi;
         }
     }
     float4* out = reinterpret_cast<float4*>(part + (int64_t)blockIdx.y * d + col);
@@ -63,6 +67,7 @@ colabs_partial_kernel(const uint16_t* __restrict__ x, int64_t M, int32_t d, int6
 constexpr int kFinishCols = 32;
 constexpr int kFinishWays = kThreads / kFinishCols;   // 8
 
+template <bool MAXSTAT>
 __global__ void __launch_bounds__(kThreads)
 colabs_finish_kernel(const float* __restrict__ part, int slices, int32_t d, float m_rows,
                      float* __restrict__ out) {
@@ -72,15 +77,18 @@ colabs_finish_kernel(const float* __restrict__ part, int slices, int32_t d, floa
     double s = 0.0;
     if (col < d) {
 #pragma unroll 8
-        for (int k = way; k < slices; k += kFinishWays) s += (double)part[(int64_t)k * d + col];
+        for (int k = way; k < slices; k += kFinishWays) {
+            const double v = (double)part[(int64_t)k * d + col];
+            s = MAXSTAT ? (v > s ? v : s) : s + v;
+        }
     }
     red[way][cl] = s;
     __syncthreads();
     if (way == 0 && col < d) {
         double t = red[0][cl];
 #pragma unroll
-        for (int j = 1; j < kFinishWays; ++j) t += red[j][cl];
-        out[col] = (float)(t / (double)m_rows);
+        for (int j = 1; j < kFinishWays; ++j) t = MAXSTAT ? (red[j][cl] > t ? red[j][cl] : t) : t + red[j][cl];
+        out[col] = MAXSTAT ? (float)t : (float)(t / (double)m_rows);
     }
 }
 
@@ -93,10 +101,12 @@ extern "C" size_t perq_colabs_mean_workspace_bytes(int64_t M, int32_t d) {
     return (size_t)pl.slices * (size_t)d * sizeof(float);
 }
 
-extern "C" perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
-                                          float* out_mean, void* workspace, size_t workspace_bytes,
-                                          void* hip_stream) {
-    if (x_bf16 == nullptr || out_mean == nullptr) return PERQ_ERR_INVALID_ARG;
+namespace perq {
+namespace {
+template <bool MAXSTAT>
+perq_status_t colabs_stat(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx, float* out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    if (x_bf16 == nullptr || out == nullptr) return PERQ_ERR_INVALID_ARG;
     if (M <= 0 || d <= 0 || ldx < d) return PERQ_ERR_INVALID_ARG;
     if (d % 8 != 0 || ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x_bf16) & 15u) != 0)
         return PERQ_ERR_UNSUPPORTED;
@@ -104,15 +114,28 @@ extern "C" perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int
     if (workspace == nullptr || workspace_bytes < need) return PERQ_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return PERQ_ERR_INVALID_ARG;
 
-    const perq::ColabsPlan pl = perq::colabs_plan(M, d);
+    const ColabsPlan pl = colabs_plan(M, d);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     float* part = static_cast<float*>(workspace);
-    hipLaunchKernelGGL(perq::colabs_partial_kernel, dim3(pl.col_tiles, pl.slices), dim3(perq::kThreads),
-                       0, stream, x_bf16, M, d, ldx, pl.rows_per_slice, part);
+    hipLaunchKernelGGL(colabs_partial_kernel<MAXSTAT>, dim3(pl.col_tiles, pl.slices), dim3(kThreads), 0, stream, x_bf16,
+                       M, d, ldx, pl.rows_per_slice, part);
     if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(perq::colabs_finish_kernel, dim3((d + perq::kFinishCols - 1) / perq::kFinishCols),
-                       dim3(perq::kThreads), 0, stream, part, pl.slices, d, (float)M,
-                       out_mean);
+    hipLaunchKernelGGL(colabs_finish_kernel<MAXSTAT>, dim3((d + kFinishCols - 1) / kFinishCols), dim3(kThreads), 0,
+                       stream, part, pl.slices, d, (float)M, out);
     if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
     return PERQ_OK;
+}
+}  // namespace
+}  // namespace perq
+
+extern "C" perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                                          float* out_mean, void* workspace, size_t workspace_bytes,
+                                          void* hip_stream) {
+    return perq::colabs_stat<false>(x_bf16, M, d, ldx, out_mean, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" perq_status_t perq_colabs_absmax(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                                            float* out_max, void* workspace, size_t workspace_bytes,
+                                            void* hip_stream) {
+    return perq::colabs_stat<true>(x_bf16, M, d, ldx, out_max, workspace, workspace_bytes, hip_stream);
 }

@@ -14,7 +14,7 @@
 
 namespace perq {
 
-enum OutKind { OUT_INT4 = 0, OUT_MXFP4 = 1, OUT_F32 = 2, OUT_INT4_ASYM = 3, OUT_FP4_TOKEN = 4 };
+enum OutKind { OUT_INT4 = 0, OUT_MXFP4 = 1, OUT_F32 = 2, OUT_INT4_ASYM = 3, OUT_FP4_TOKEN = 4, OUT_DIAG = 5 };
 
 struct ApplyParams {
     const uint16_t* x;      // bf16 [T, ldx]
@@ -23,7 +23,7 @@ struct ApplyParams {
     const int32_t* perm;    // int32 [d] or nullptr
     uint8_t* codes;         // [T, d/2]
     void* scales;           // float [T], uint8 [T, d/32] or float [T][2] (step, zero point)
-    float* y;               // [T, d] (test entry only)
+    float* y;               // [T, d] (test entry), or [T, 4] (diagnostics)
     int32_t d;
     int32_t b;
     int32_t log2b;

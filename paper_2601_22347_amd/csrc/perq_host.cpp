@@ -54,6 +54,38 @@ extern "C" perq_status_t perq_massdiff_perm(const float* colabs_mean, int32_t d,
     return PERQ_OK;
 }
 
+// The two other calibrated permutations of the ablation (Appendix C, "Permutations").
+static bool stat_ok(const float* stat, int32_t d) {
+    for (int32_t i = 0; i < d; ++i)
+        if (!std::isfinite(stat[i]) || stat[i] < 0.0f) return false;
+    return true;
+}
+
+extern "C" perq_status_t perq_perm_sorted(const float* stat, int32_t d, int32_t* perm_out) {
+    if (stat == nullptr || perm_out == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
+    if (!stat_ok(stat, d)) return PERQ_ERR_INVALID_ARG;
+    std::iota(perm_out, perm_out + d, 0);
+    std::stable_sort(perm_out, perm_out + d, [&](int32_t x, int32_t y) { return stat[x] > stat[y]; });
+    return PERQ_OK;
+}
+
+extern "C" perq_status_t perq_perm_zigzag(const float* stat, int32_t d, int32_t b, int32_t* perm_out) {
+    if (stat == nullptr || perm_out == nullptr) return PERQ_ERR_INVALID_ARG;
+    if (d <= 0 || b <= 0 || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    if (!stat_ok(stat, d)) return PERQ_ERR_INVALID_ARG;
+    const int32_t n = d / b;
+    std::vector<int32_t> order(d);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return stat[x] > stat[y]; });
+    // round k of n ranks fills slot k of every block, left to right on even rounds, right to left on odd
+    for (int32_t r = 0; r < d; ++r) {
+        const int32_t round = r / n, pos = r % n;
+        const int32_t blk = (round & 1) ? n - 1 - pos : pos;
+        perm_out[static_cast<int64_t>(blk) * b + round] = order[r];
+    }
+    return PERQ_OK;
+}
+
 extern "C" perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d) {
     if (perm_host == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
     std::vector<uint8_t> seen(d, 0);

@@ -359,3 +359,59 @@ def test_w4a4_gemm_argument_checks():
     assert out.shape == (4, 0)
     with pytest.raises(ValueError):
         binding.perq_w4a4_gemm_ref(a, s, torch.zeros((4, 8), dtype=torch.uint8, device="cuda"), s)
+
+
+# ---- ablation permutations and the per-token diagnostics (Appendix C; Section 3) ------------------
+def test_colabs_absmax_is_exact():
+    wl = synth.llama1b_down()
+    bits = wl.calib_rows()[:700]
+    got = binding.perq_colabs_absmax(binding.bits_to_device(bits)).cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), orc.colabs_max(orc.bf16_bits_to_f64(bits)))
+
+
+@pytest.mark.parametrize("T,d,bs", [(37, 256, [16, 32, 64, 256]), (9, 4096, [16, 128, 2048, 4096]), (5, 14336, [32, 2048]),
+                                     (3, 8192, [4096, 8192]), (4, 32768, [1024, 32768])])
+def test_block_diagnostics_against_oracle(T, d, bs):
+    rng = np.random.default_rng(3000 + d)
+    x = rng.standard_t(3, size=(T, d))
+    x[:, rng.choice(d, size=max(1, d // 100), replace=False)] *= 50
+    bits = synth.f64_to_bf16_bits(x)
+    xd = binding.bits_to_device(bits)
+    torch = _torch()
+    perm = rng.permutation(d).astype(np.int32)
+    for b in bs:
+        for pm in (None, perm):
+            pt = None if pm is None else torch.from_numpy(pm).cuda()
+            got = binding.perq_block_diagnostics(xd, pt, b).cpu().numpy().astype(np.float64)
+            want = orc.block_diagnostics(bits, pm, b) if b <= 4096 else None
+            if want is None:         # explicit H_b too large: same quantities with the fast transform
+                X = orc.bf16_bits_to_f64(bits); Xp = orc.permute_channels(X, pm)
+                want = np.stack([np.abs(X).max(1), np.abs(X).sum(1), np.abs(Xp).reshape(T, d // b, b).sum(2).max(1),
+                                 np.abs(orc.fwht_f64(Xp, b)).max(1)], axis=1)
+            l2 = np.linalg.norm(orc.bf16_bits_to_f64(bits), axis=1)
+            assert np.array_equal(got[:, 0], want[:, 0])
+            assert np.allclose(got[:, 1], want[:, 1], rtol=2e-6) and np.allclose(got[:, 2], want[:, 2], rtol=2e-6)
+            assert np.all(np.abs(got[:, 3] - want[:, 3]) <= 1e-5 * l2)
+            assert np.all(got[:, 3] <= got[:, 2] / np.sqrt(b) * (1 + 1e-5))        # Proposition 2 on the device numbers
+
+
+def test_calibrated_permutations_ranked_by_the_bound():
+    """MassDiff against identity / absmax / ZigZag on the calibrated synthetic law: the mean
+    Proposition 2 bound over apply tokens, from the device diagnostics."""
+    torch = _torch()
+    wl = synth.llama1b_down()
+    b = 32
+    cal = binding.bits_to_device(wl.calib_rows())
+    a = binding.perq_colabs_mean(cal).cpu().numpy()
+    amx = binding.perq_colabs_absmax(cal).cpu().numpy()
+    x = binding.bits_to_device(wl.apply_rows(0, 512))
+    perms = {"identity": None, "massdiff": binding.perq_massdiff_perm(a, b), "absmax": binding.perq_perm_sorted(amx),
+             "zigzag": binding.perq_perm_zigzag(amx, b)}
+    bound = {}
+    for name, pm in perms.items():
+        pt = None if pm is None else torch.from_numpy(pm).cuda()
+        dg = binding.perq_block_diagnostics(x, pt, b).cpu().numpy()
+        bound[name] = float((dg[:, 2] / np.sqrt(b) / dg[:, 0]).mean())
+    print("mean normalised Prop. 2 bound:", bound, flush=True)
+    assert bound["massdiff"] < bound["identity"] and bound["massdiff"] <= bound["zigzag"] * 1.02
+    assert bound["absmax"] > bound["massdiff"]            # sorting concentrates the heavy channels in one block

@@ -102,3 +102,17 @@ def test_apply_argument_checks_happen_before_any_launch(lib):
     assert lib.perq_colabs_mean(fake, 4, 256, 256, fake, None, 0, None) == INV
     assert lib.perq_colabs_mean_workspace_bytes(4096, 8192) >= 8192 * 4
     assert lib.perq_colabs_mean_workspace_bytes(0, 8192) == 0
+
+
+def test_sorted_and_zigzag_match_oracle():
+    rng = np.random.default_rng(77)
+    for d, b in ((256, 16), (4096, 128), (96, 32), (64, 64)):
+        stat = rng.gamma(0.5, size=d).astype(np.float32)
+        stat[rng.choice(d, size=d // 8, replace=False)] = stat[0]          # ties
+        assert np.array_equal(binding.perq_perm_sorted(stat), orc.perm_sorted_desc(stat))
+        z = binding.perq_perm_zigzag(stat, b)
+        assert np.array_equal(z, orc.perm_zigzag(stat, b)) and binding.perq_perm_validate(z)
+    with pytest.raises(binding.PerqError):
+        binding.perq_perm_zigzag(np.ones(10, np.float32), 4)
+    with pytest.raises(binding.PerqError):
+        binding.perq_perm_sorted(np.array([1.0, np.nan], np.float32))
