@@ -415,3 +415,52 @@ def test_calibrated_permutations_ranked_by_the_bound():
     print("mean normalised Prop. 2 bound:", bound, flush=True)
     assert bound["massdiff"] < bound["identity"] and bound["massdiff"] <= bound["zigzag"] * 1.02
     assert bound["absmax"] > bound["massdiff"]            # sorting concentrates the heavy channels in one block
+
+
+# ---- the ticket counters under concurrency and graph replay ------------------------------------------
+def test_run_time_schedule_on_two_streams_and_in_a_graph():
+    """Launches that overlap on two streams draw from different counter sets, and a captured launch
+    can be replayed: every result equals the eager one."""
+    torch = _torch()
+    rng = np.random.default_rng(123)
+    cases = []
+    for T, d, b, fmt in ((6000, 4096, 128, "int4"), (2100, 8192, 32, "mxfp4")):
+        x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_normal((T, d))))
+        perm = torch.from_numpy(rng.permutation(d).astype(np.int32)).cuda()
+        ref = binding.perq_permute_rotate_quant(x, perm, b, fmt, algo="mfma")
+        cases.append((x, perm, b, fmt, ref))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [[], []]
+    for rep in range(40):
+        for k, st in enumerate(streams):
+            x, perm, b, fmt, ref = cases[k]
+            codes, scales = binding.alloc_outputs(x.shape[0], x.shape[1], fmt, x.device)
+            with torch.cuda.stream(st):
+                binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales, stream=st, algo="mfma")
+            outs[k].append((codes, scales))
+    torch.cuda.synchronize()
+    for k in range(2):
+        ref = cases[k][4]
+        for i, (codes, scales) in enumerate(outs[k]):
+            assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"stream {k} launch {i}"
+    # graph: capture one launch, replay it with eager launches in between
+    x, perm, b, fmt, ref = cases[0]
+    codes, scales = binding.alloc_outputs(x.shape[0], x.shape[1], fmt, x.device)
+    g = torch.cuda.CUDAGraph()
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales, stream=st, algo="mfma")   # warm
+        st.synchronize()
+        with torch.cuda.graph(g, stream=st):
+            binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales,
+                                              stream=torch.cuda.current_stream(), algo="mfma")
+    for rep in range(4):
+        codes.fill_(0xAA); scales.fill_(-1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"replay {rep}"
+        eager = binding.perq_permute_rotate_quant(x, perm, b, fmt, algo="mfma")
+        torch.cuda.synchronize()
+        assert torch.equal(eager[0], ref[0])
