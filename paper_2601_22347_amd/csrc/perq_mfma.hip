@@ -15,13 +15,15 @@
 //                       +-H_32 products of the 2 / 4 sub-blocks of its block (more MFMAs, no VALU)
 //     b = 256, 512    : H_128 as above, then one or two butterfly stages across lanes on c
 //                       (DPP quad_perm)
-//     b = 1024 .. 4096: the roles are turned round.  The data become the A operand, read with
-//                       a stride of 32 elements: A[m][K] = x[32 K + m], and the product with the
-//                       +-1 matrix I (x) H_{b/32} contracts the HIGH index bits K (up to 128 of
-//                       them: 8 K-steps x 4 column tiles, 8 .. 32 MFMAs per tile).  A lane then
-//                       holds, for 4 transformed high indices, 16 contiguous low positions m, and
-//                       the low five bits are finished by four in-register butterfly stages and
-//                       one half-wave swap: 5.5 VALU per element instead of 2 per cross-lane stage.
+//     b = 1024 .. 4096: the roles are turned round.  The data become the A operand: row m of A
+//                       collects position bits 0..3 and bit 11 of the tile, the contraction index
+//                       K position bits 4..10 (A[m][K] = x[(m & 15) + 16 K + 2048 (m >> 4)]), and
+//                       the product with the +-1 matrix I (x) H_{b/16} contracts those seven
+//                       middle bits (16 .. 32 MFMAs per tile).  A lane then holds, for 4
+//                       transformed K, 16 contiguous positions, whose four low bits are finished by
+//                       in-register butterflies (4 VALU per element).  Bit 11 separates the two
+//                       half-waves; it belongs to the block only for b = 4096, which alone pays
+//                       one half-wave swap stage.
 //
 // Data movement.  The raw bf16 rows go global -> LDS with 16-byte direct-to-LDS loads (no
 // registers, no ds_write), streaming policy; they are the only HBM reads.  The B operands are
@@ -70,6 +72,9 @@ __device__ __forceinline__ uint32_t granule_slot(uint32_t g) {
 
 __device__ __forceinline__ uint32_t popc_parity(uint32_t v) { return __builtin_popcount(v) & 1u; }
 
+// high-K mode (b >= 1024): position inside the tile of row m (5 bits), contraction index K (7 bits)
+__device__ __forceinline__ uint32_t hk_pos(uint32_t m, uint32_t K) { return (m & 15u) | (K << 4) | ((m >> 4) << 11); }
+
 // Stores to LDS and workgroup barriers of the main loop, written as instructions.  The compiler
 // makes every LDS store it knows of wait until no direct-to-LDS load is outstanding (it cannot
 // tell that the staging buffers and these small scratch areas are disjoint), and its barrier waits
@@ -84,6 +89,11 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 __device__ __forceinline__ void lds_store16(void* p, uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     const u32x4_t v = {a, b, c, d};
     asm volatile("ds_write_b128 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
+}
+__device__ __forceinline__ void lds_store8(void* p, uint32_t a, uint32_t b) {
+    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+    const u32x2_t v = {a, b};
+    asm volatile("ds_write_b64 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
 }
 __device__ __forceinline__ void lds_store4(void* p, float v) {
     asm volatile("ds_write_b32 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
@@ -176,7 +186,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     bool qvalid[kQ];
     // (filled in after the first loads have been issued, see the end of the kernel)
     // sub-block (32 positions) of the tile that accumulator tile q of this lane ends up holding
-    auto sbq = [&](int q) -> int { return kHighK ? q * 32 + c : c * kQ + q; };
+    auto sbq = [&](int q) -> int { return c * kQ + q; };                            // (low-K modes)
+    // high-K mode: first position of the 16 contiguous outputs in accumulator tile q of this lane
+    auto hk_run = [&](int q) -> int { return 16 * (q * 32 + c) + 2048 * h; };
 
     // -1 / +1 of the cross-lane butterflies on c
     float sgn[5];
@@ -372,10 +384,11 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 for (int r = 0; r < 16; ++r) v[qo * 16 + r] = acc[r];
             }
         } else {
-            // D[m][n] = sum_K X[m][K] * S[K][n], S = I (x) H_{b/32} on the 128 high indices of the
-            // tile.  With K = 32 Kh + Kl and n = 32 nt + j the entry is H_{b/1024}[Kh][nt] (zero off
-            // the block diagonal) times H_32[Kl][j]; the latter is the constant fragment.
-            constexpr int kHi = 1 << (STAGES - 5);            // b / 1024: order of the outer factor
+            // D[m][n] = sum_K X[m][K] * S[K][n], S = I (x) H_{b/16} on the 128 middle indices (H_64 (x)
+            // I_2 ... for b = 1024, H_128 for b >= 2048).  With K = 32 Kh + Kl and n = 32 nt + j the entry
+            // is H_kHi[Kh][nt] (zero off the block diagonal) times H_32[Kl][j]; the latter is the
+            // constant fragment.
+            constexpr int kHi = STAGES == 5 ? 2 : 4;          // order of the outer factor on Kh
 #pragma unroll
             for (int nt = 0; nt < kQ; ++nt) {
                 f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -390,7 +403,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) v[nt * 16 + r] = acc[r];
             }
-            // low five bits: positions m = 16 h + r of every sub-block
+            // position bits 0..3: the 16 contiguous outputs of every accumulator tile
 #pragma unroll
             for (int hh = 1; hh < 16; hh <<= 1) {
 #pragma unroll
@@ -402,19 +415,20 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 }
             }
-            lane_stage<32>(v, 0.0f);
+            if constexpr (STAGES == 7) lane_stage<32>(v, 0.0f);      // position bit 11, b = 4096 only
         }
 
         // ---- butterflies across lanes for b = 256, 512 ------------------------------------------
         if constexpr (STAGES == 3 || STAGES == 4) lane_stage<1>(v, sgn[0]);
         if constexpr (STAGES == 4) lane_stage<2>(v, sgn[1]);
 
-        // ---- epilogue: lane (c,h) holds outputs 16h..16h+15 of sub-blocks 4c..4c+3 -------------
+        // ---- epilogue: lane (c,h) holds outputs 16h..16h+15 of sub-blocks 4c..4c+3 (low-K modes),
+        //      or the 16 outputs from hk_run(q) on of every accumulator tile q (high-K mode) -------
         if constexpr (OUT == OUT_F32) {
 #pragma unroll
             for (int q = 0; q < kQ; ++q) {
                 if (row_live && qvalid[q]) {
-                    float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + tile_base + sbq(q) * 32 + 16 * h);
+                    float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + tile_base + (kHighK ? hk_run(q) : sbq(q) * 32 + 16 * h));
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
                         yo[j] = make_float4(v[q * 16 + 4 * j] * p.rsqrt_b, v[q * 16 + 4 * j + 1] * p.rsqrt_b,
@@ -436,7 +450,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     float m = 0.0f;
 #pragma unroll
                     for (int r = 0; r < 16; ++r) m = fmaxf(m, fabsf(v[q * 16 + r]));
-                    m = fmaxf(m, lane_xor<32>(m));                   // the other half of the 32-group
+                    // the other half of the 32-group: the other half-wave, or the neighbouring lane
+                    m = fmaxf(m, kHighK ? lane_xor<1>(m) : lane_xor<32>(m));
                     const int E = mx_shared_exponent(m, p.half_log2b);
                     const float scale = __uint_as_float((uint32_t)(E + p.half_log2b) << 23);
                     pk[q][0] = mxfp4_pack8(v + q * 16, scale);
@@ -525,26 +540,34 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 }
             }
-            // Give lane (c,0) the whole of its sub-blocks q = 0, 1 and lane (c,1) the whole of q = 2, 3:
-            // the half-wave swap exchanges (q, h=1) of the low lanes' tiles with (q+2, h=0).
-            uint32_t out[2][4];
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    auto s = __builtin_amdgcn_permlane32_swap(pk[q][j], pk[q + 2][j], false, false);
-                    out[q][j] = s[0];
-                    out[q][2 + j] = s[1];
-                }
-            }
             // The wave's 2 KiB of codes take one trip through LDS so that each store instruction
-            // writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of 16-byte
-            // pieces at a 32-byte pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
+            // writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of short pieces
+            // at a pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
             unsigned char* ob = out_stage + (uint32_t)wave * 2048u;
-            {
+            if constexpr (!kHighK) {
+                // Give lane (c,0) the whole of its sub-blocks q = 0, 1 and lane (c,1) the whole of
+                // q = 2, 3: the half-wave swap exchanges (q, h=1) of the low lanes' tiles with (q+2, h=0).
+                uint32_t out[2][4];
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        auto s = __builtin_amdgcn_permlane32_swap(pk[q][j], pk[q + 2][j], false, false);
+                        out[q][j] = s[0];
+                        out[q][2 + j] = s[1];
+                    }
+                }
                 const uint32_t s0 = (uint32_t)sbq(2 * h), s1 = (uint32_t)sbq(2 * h + 1);
                 lds_store16(ob + ((s0 ^ ((s0 >> 3) & 7u)) << 4), out[0][0], out[0][1], out[0][2], out[0][3]);
                 lds_store16(ob + ((s1 ^ ((s1 >> 3) & 7u)) << 4), out[1][0], out[1][1], out[1][2], out[1][3]);
+            } else {
+                // 16 codes = 8 bytes per accumulator tile, at byte hk_run(q) / 2 of the wave's block
+#pragma unroll
+                for (int q = 0; q < kQ; ++q) {
+                    const uint32_t off = (uint32_t)hk_run(q) >> 1;
+                    const uint32_t sl = off >> 4;
+                    lds_store8(ob + (((sl ^ ((sl >> 3) & 7u)) << 4) | (off & 8u)), pk[q][0], pk[q][1]);
+                }
             }
             const uint32_t r0 = (uint32_t)lane, r1 = 64u + (uint32_t)lane;
             uint4 o0, o1;
@@ -560,7 +583,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     } else {
 #pragma unroll
                         for (int q = 0; q < kQ; ++q)
-                            if (h == 0 && qvalid[q]) srow[sbq(q)] = (uint8_t)(ebytes >> (8 * q));
+                            if ((c & 1) == 0 && qvalid[q]) srow[hk_run(q) >> 5] = (uint8_t)(ebytes >> (8 * q));
                     }
                 } else if constexpr (OUT == OUT_INT4_ASYM) {
                     if (lane == 0 && tile_base == 0)
@@ -608,7 +631,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const uint32_t pos = 32u * (16u * f + 8u * h + e) + sigma_i;
+                        const uint32_t pos = hk_pos(sigma_i, 16u * f + 8u * h + e);
                         ch[8 * j + e] = (uint32_t)p.perm[pos & g.fold_mask] + (pos & ~g.fold_mask);
                     }
                 }
@@ -698,18 +721,18 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             }
         }
     } else {
-        // high-K mode: fragment kt, element e of lane (i, h) is position 32 K + sigma(i) of the tile,
-        // K = 16 kt + 8 h + e; all 64 channel numbers are fetched before any is used
+        // high-K mode: fragment kt, element e of lane (i, h) is position hk_pos(sigma(i), K) of the
+        // tile, K = 16 kt + 8 h + e; all 64 channel numbers are fetched before any is used
 #pragma unroll
-        for (int q = 0; q < kQ; ++q) qvalid[q] = sbq(q) * 32 < tile_len;
+        for (int q = 0; q < kQ; ++q) qvalid[q] = hk_run(q) < tile_len;
         uint32_t ch[64];
 #pragma unroll
         for (int f = 0; f < 8; ++f) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t K = 16u * f + 8u * h + e;
-                const uint32_t pos = (uint32_t)tile_base + 32u * K + sigma_i;
-                const bool ok = (int)(32u * K) < tile_len;
+                const uint32_t in_tile = hk_pos(sigma_i, 16u * f + 8u * h + e);
+                const uint32_t pos = (uint32_t)tile_base + in_tile;
+                const bool ok = (int)in_tile < tile_len;
                 if constexpr (PERM) ch[f * 8 + e] = (uint32_t)p.perm[ok ? (pos & g.fold_mask) : 0u] + (pos & ~g.fold_mask);
                 else ch[f * 8 + e] = pos;
             }
@@ -718,7 +741,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         for (int f = 0; f < 8; ++f) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const bool ok = (int)(32u * (16u * f + 8u * h + e)) < tile_len;
+                const bool ok = (int)hk_pos(sigma_i, 16u * f + 8u * h + e) < tile_len;
                 const uint32_t cc = ch[f * 8 + e];
                 src[f * 8 + e] = ok ? (uint32_t)rr * g.row_bytes + ((granule_slot(cc >> 3) << 4) | ((cc & 7u) << 1)) : kZeroSlot;
             }
