@@ -73,6 +73,7 @@ def main() -> int:
     ap.add_argument("--identity", action="store_true", help="run the workload with P = I (no gather)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--no-context", action="store_true", help="skip the single-buffer-set and device-copy figures")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (token rows would be sharded across GPUs "
@@ -171,14 +172,17 @@ def main() -> int:
         a1.record(stream)
         torch.cuda.synchronize()
         return a0.elapsed_time(a1) / n
-    one_set_ms = timed(lambda i: binding.perq_permute_rotate_quant(xs[0], perm_t, b, fmt, codes=outs[0][0], scales=outs[0][1],
-                                                                   stream=stream, algo=args.algo), min(args.steps, 300))
-    cp_src, cp_dst = xs[0].view(torch.uint8).reshape(-1), xs[1].view(torch.uint8).reshape(-1)
-    copy_ms = timed(lambda i: cp_dst.copy_(cp_src), 50)
-    context = {"single_buffer_set_ms": one_set_ms,
-               "single_buffer_set_note": "same call on one input/output set (%.0f MB; cache resident if well under 256 MB)"
-                                         % (per_set / 1e6),
-               "device_copy_GBs": 2 * cp_src.numel() / (copy_ms * 1e-3) / 1e9}
+    context = None
+    if not args.no_context:
+        one_set_ms = timed(lambda i: binding.perq_permute_rotate_quant(xs[0], perm_t, b, fmt, codes=outs[0][0],
+                                                                       scales=outs[0][1], stream=stream, algo=args.algo),
+                           min(args.steps, 300))
+        cp_src, cp_dst = xs[0].view(torch.uint8).reshape(-1), xs[1].view(torch.uint8).reshape(-1)
+        copy_ms = timed(lambda i: cp_dst.copy_(cp_src), 50)
+        context = {"single_buffer_set_ms": one_set_ms,
+                   "single_buffer_set_note": "same call on one input/output set (%.0f MB; cache resident if well under "
+                                             "256 MB)" % (per_set / 1e6),
+                   "device_copy_GBs": 2 * cp_src.numel() / (copy_ms * 1e-3) / 1e9}
 
     # ---- self-check of the timed configuration on sampled rows --------------------------------
     check = None
