@@ -464,3 +464,51 @@ def test_run_time_schedule_on_two_streams_and_in_a_graph():
         eager = binding.perq_permute_rotate_quant(x, perm, b, fmt, algo="mfma")
         torch.cuda.synchronize()
         assert torch.equal(eager[0], ref[0])
+
+
+# ---- edges of the run-time schedule: exactly two units per worker, one more, strided rows, long T ----
+@pytest.mark.parametrize("T", [4095, 4096, 4097, 4160])
+def test_run_time_schedule_threshold_edges(T):
+    """d = 4096 runs 2048 waves: T = 4096 is the first size on the ticket path (no row left to draw),
+    T = 4095 the last on the fixed stride."""
+    rng = np.random.default_rng(T)
+    d, b = 4096, 64
+    x = synth.f64_to_bf16_bits(rng.standard_normal((T, d)) * np.exp(rng.uniform(-1, 1, size=(T, 1))))
+    perm = rng.permutation(d).astype(np.int32)
+    for fmt in ("int4", "mxfp4"):
+        for _ in range(2):                          # twice: the counters must be back at zero
+            codes, scales, _y = run_gpu(x, perm, b, fmt, "mfma", want_y=False)
+            rep = parity.compare_apply(x, perm, b, fmt, codes, scales, None)
+            assert rep.ok(), (T, fmt, rep.summary(), rep.notes[:5])
+
+
+def test_run_time_schedule_with_a_row_stride():
+    rng = np.random.default_rng(5)
+    T, d = 2300, 8192
+    x = synth.f64_to_bf16_bits(rng.standard_normal((T, d)))
+    perm = rng.permutation(d).astype(np.int32)
+    codes, scales, _y = run_gpu(x, perm, 128, "int4", "mfma", want_y=False, ldx=d + 512)
+    rep = parity.compare_apply(x, perm, 128, "int4", codes, scales, None)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
+
+
+def test_long_launch_sampled_rows():
+    """T = 131072 rows of 4096 (the largest launch timed in the design notes): 64 tickets per wave;
+    sampled rows against the oracle, every row's scale against the identity |y|_inf = |scale| * 7 <= |x|_2."""
+    torch = _torch()
+    T, d, b = 131072, 4096, 128
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    x = torch.randn((T, d), generator=g, device="cuda").to(torch.bfloat16)
+    perm = np.random.default_rng(12).permutation(d).astype(np.int32)
+    perm_t = torch.from_numpy(perm).cuda()
+    codes, scales = binding.perq_permute_rotate_quant(x, perm_t, b, "int4", algo="mfma")
+    rows = np.unique(np.concatenate([np.arange(40), T - 1 - np.arange(40), np.random.default_rng(13).choice(T, 120, replace=False)]))
+    rt = torch.from_numpy(rows).cuda()
+    x_bits = x[rt].view(torch.int16).cpu().numpy().view(np.uint16)
+    rep = parity.compare_apply(x_bits, perm, b, "int4", codes[rt].cpu().numpy(), scales[rt].cpu().numpy(), None)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
+    l2 = x.float().norm(dim=1)
+    assert torch.all(scales > 0) and torch.all(scales * 7 <= l2 * (1 + 1e-5))
+    nib = codes.view(torch.uint8)
+    lo, hi = nib & 0xF, nib >> 4
+    assert torch.all(((lo == 7) | (lo == 9) | (hi == 7) | (hi == 9)).any(dim=1))       # every row reaches +-7
