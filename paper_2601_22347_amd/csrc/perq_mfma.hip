@@ -188,7 +188,12 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // sub-block (32 positions) of the tile that accumulator tile q of this lane ends up holding
     auto sbq = [&](int q) -> int { return c * kQ + q; };                            // (low-K modes)
     // high-K mode: first position of the 16 contiguous outputs in accumulator tile q of this lane
-    auto hk_run = [&](int q) -> int { return 16 * (q * 32 + c) + 2048 * h; };
+    // (b = 4096: after the stage on position bit 11 a lane holds both halves of two tiles instead
+    //  of its own half of four; run 2 q' + hb is tile 2 h + q', half hb)
+    auto hk_run = [&](int q) -> int {
+        if constexpr (STAGES == 7) return 16 * ((2 * h + (q >> 1)) * 32 + c) + 2048 * (q & 1);
+        return 16 * (q * 32 + c) + 2048 * h;
+    };
 
     // -1 / +1 of the cross-lane butterflies on c
     float sgn[5];
@@ -415,7 +420,25 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 }
             }
-            if constexpr (STAGES == 7) lane_stage<32>(v, 0.0f);      // position bit 11, b = 4096 only
+            if constexpr (STAGES == 7) {
+                // position bit 11 (b = 4096 only): one half-wave swap hands the low lanes both halves
+                // of tiles 0 and 1 and the high lanes both halves of tiles 2 and 3; sum and
+                // difference stay where they are computed (see hk_run), so nothing is swapped back
+                float w[64];
+#pragma unroll
+                for (int qp = 0; qp < 2; ++qp) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[qp * 16 + r]),
+                                                                   __float_as_uint(v[(qp + 2) * 16 + r]), false, false);
+                        const float lo = __uint_as_float(sw[0]), hi = __uint_as_float(sw[1]);
+                        w[qp * 32 + r] = lo + hi;
+                        w[qp * 32 + 16 + r] = lo - hi;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 64; ++i) v[i] = w[i];
+            }
         }
 
         // ---- butterflies across lanes for b = 256, 512 ------------------------------------------
