@@ -29,7 +29,11 @@ butterfly, the Section 3 worst-case INT-q error bound, the e2m1 grid/tie table b
 force, scale equivariance, closed forms and brute-force optimum for the greedy; for the two
 per-token quantizers of Appendix B (asymmetric INT4, FP4) exact rational arithmetic on small
 rows, the half-step error bound, end codes, and the reduction of FP4 to the MXFP4 routine
-when the row maximum is 6 * 2^k.
+when the row maximum is 6 * 2^k; for the non-power-of-two rotation of Appendix A.1 (base
+matrix by Paley's constructions, a stated reading) orthogonality, the quadratic character by
+Euler's criterion, the Kronecker form against the written-out matrix, and the operation counts
+that the appendix's second table and Table 3's "Full" column print, reproduced by a staged
+evaluation that counts its additions and subtractions.
 """
 from __future__ import annotations
 
@@ -40,6 +44,7 @@ import numpy as np
 
 __all__ = [
     "bf16_bits_to_f64", "sylvester_hadamard", "permute_channels", "block_hadamard",
+    "paley_hadamard", "hadamard_factors", "hadamard_matrix", "nonpo2_rotation_counted",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
     "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
     "merge_into_weights", "w4a4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics",
@@ -91,18 +96,179 @@ def permute_channels(X: np.ndarray, perm) -> np.ndarray:
     return X[:, perm]
 
 
+def _quadratic_character(q: int) -> np.ndarray:
+    """chi(x) for x in Z_q, q an odd prime: 0 at 0, +1 on non-zero squares, -1 otherwise."""
+    if q < 3 or any(q % p == 0 for p in range(2, int(math.isqrt(q)) + 1)):
+        raise ValueError("q must be an odd prime")
+    chi = -np.ones(q, dtype=np.int64)
+    chi[0] = 0
+    for x in range(1, q):
+        chi[(x * x) % q] = 1
+    return chi
+
+
+def paley_hadamard(m: int) -> np.ndarray:
+    """Unnormalised m x m Hadamard matrix (+-1, int64) for the non-power-of-two base, m = 4t.
+
+    Appendix A.1 builds the full rotation from a 4t-dimensional base matrix but does not
+    print one (the Llama3-8B example needs 28, the Qwen3 widths 12 and 76).  The reading
+    taken: Paley's constructions over the prime field Z_q, with the Jacobsthal matrix
+    Q[i][j] = chi(i - j):
+      * type I  when q = m - 1 is a prime with q = 3 (mod 4):  H = I + S,
+                S = [[0, 1^T], [-1, Q]]  (S is skew, S S^T = q I);            m = 12 (q = 11)
+      * type II when q = m/2 - 1 is a prime with q = 1 (mod 4): S = [[0, 1^T], [1, Q]]
+                (symmetric), every 0 of S becomes [[1, -1], [-1, -1]] and every entry
+                e = +-1 becomes e * [[1, 1], [1, -1]];                m = 28 (q = 13), 76 (q = 37)
+    Type I is tried first.  Any Hadamard matrix satisfies what the paper proves about the
+    rotation (Propositions 1 and 2 use only that entries are +-1/sqrt(d) and rows orthogonal).
+    """
+    def is_prime(q):
+        return q >= 2 and all(q % p for p in range(2, int(math.isqrt(q)) + 1))
+
+    if m % 4 != 0 or m < 8:
+        raise ValueError("m must be a multiple of four, at least 8")
+    if is_prime(m - 1) and (m - 1) % 4 == 3:
+        q = m - 1
+        chi = _quadratic_character(q)
+        S = np.zeros((m, m), dtype=np.int64)
+        S[0, 1:] = 1
+        S[1:, 0] = -1
+        for i in range(q):
+            for j in range(q):
+                S[1 + i, 1 + j] = chi[(i - j) % q]
+        return np.eye(m, dtype=np.int64) + S
+    if is_prime(m // 2 - 1) and (m // 2 - 1) % 4 == 1:
+        q = m // 2 - 1
+        chi = _quadratic_character(q)
+        S = np.zeros((q + 1, q + 1), dtype=np.int64)
+        S[0, 1:] = 1
+        S[1:, 0] = 1
+        for i in range(q):
+            for j in range(q):
+                S[1 + i, 1 + j] = chi[(i - j) % q]
+        zero_cell = np.array([[1, -1], [-1, -1]], dtype=np.int64)
+        unit_cell = np.array([[1, 1], [1, -1]], dtype=np.int64)
+        H = np.zeros((m, m), dtype=np.int64)
+        for i in range(q + 1):
+            for j in range(q + 1):
+                H[2 * i:2 * i + 2, 2 * j:2 * j + 2] = zero_cell if S[i, j] == 0 else S[i, j] * unit_cell
+        return H
+    raise ValueError(f"no Paley construction over a prime field for order {m}")
+
+
+def hadamard_factors(b: int):
+    """b -> (k', m): R_b is k' Sylvester doublings of an m x m base (Appendix A.1).
+
+    b = k * t with t the odd part; t = 1 gives the pure Sylvester matrix (returned as
+    (log2 b, 1)); otherwise the base has m = 4t rows and k' = log2(k) - 2.
+    """
+    if b < 1:
+        raise ValueError("b must be positive")
+    t = b
+    while t % 2 == 0:
+        t //= 2
+    k = b // t
+    if t == 1:
+        return int(math.log2(b)), 1
+    if k < 4:
+        raise ValueError("a Hadamard order above 2 is a multiple of four")
+    return int(math.log2(k)) - 2, 4 * t
+
+
+def hadamard_matrix(b: int) -> np.ndarray:
+    """Unnormalised b x b matrix H_{2^k'} (x) H_m written out (int64); for small b."""
+    kp, m = hadamard_factors(b)
+    H = np.array([[1]], dtype=np.int64) if m == 1 else paley_hadamard(m)
+    for _ in range(kp):
+        H = np.block([[H, H], [H, -H]])
+    return H
+
+
 def block_hadamard(X: np.ndarray, b: int) -> np.ndarray:
     """X R~ with R~ = I_n (x) R, R = H_b / sqrt(b); X is [T, d], d = n*b, float64.
 
     Written as the definition: each b-wide block of each row is multiplied by the explicit
     matrix, then scaled by 1/sqrt(b) (the normalisation is applied after the +-1 sums).
+    When b is not a power of two, H_b = H_{2^k'} (x) H_m (Appendix A.1: k' doublings of the
+    4t-dimensional base) and the product is taken one Kronecker factor at a time -- with the
+    block viewed as a [2^k', m] array Z, that is H_{2^k'} Z H_m (the Sylvester factor is
+    symmetric); `hadamard_matrix` writes the same matrix out for the sizes a test can hold.
     """
     T, d = X.shape
     if d % b != 0:
         raise ValueError("b must divide d")
-    H = sylvester_hadamard(b).astype(np.float64)
-    Y = (X.reshape(T * (d // b), b) @ H) / math.sqrt(b)
+    kp, m = hadamard_factors(b)
+    if m == 1:
+        H = sylvester_hadamard(b).astype(np.float64)
+        Y = (X.reshape(T * (d // b), b) @ H) / math.sqrt(b)
+        return Y.reshape(T, d)
+    A = 1 << kp
+    HA = sylvester_hadamard(A).astype(np.float64)
+    Hm = paley_hadamard(m).astype(np.float64)
+    Z = X.reshape(T * (d // b), A, m)
+    Y = np.matmul(HA, np.matmul(Z, Hm)) / math.sqrt(b)
     return Y.reshape(T, d)
+
+
+def nonpo2_rotation_counted(x: np.ndarray, b: int, counter: list, dense_base: bool = False) -> np.ndarray:
+    """One row through the staged non-power-of-two rotation of Appendix A.1, counting add/sub.
+
+    x is one b-dimensional vector (float64), b = 2^k' * 4t.  Steps, in the appendix's order:
+    k' radix-2 butterfly stages over the index that counts the 4t-wide pieces, then one
+    4t-dimensional rotation per piece.  With dense_base the piece is multiplied by the base
+    matrix directly (4t - 1 add/sub per output: the "butterfly + matmul" column of the
+    appendix's second table).  Otherwise every group of four adjacent inputs first yields
+    its sums and differences -- two stages, (a+-b, c+-d) then the eight combinations
+    (a+-b)+-(c+-d), which are all sign patterns of four terms up to a common sign -- and
+    each output then adds or subtracts one of these per group, t terms.  counter[0]
+    accumulates the number of additions and subtractions.  Returns x H_b (unnormalised).
+    """
+    kp, m = hadamard_factors(b)
+    if m == 1:
+        raise ValueError("power-of-two sizes use the plain butterfly")
+    t = m // 4
+    H = paley_hadamard(m)
+    v = np.array(x, dtype=np.float64).reshape(1 << kp, m)
+    h = 1
+    while h < (1 << kp):
+        w = v.reshape((1 << kp) // (2 * h), 2, h, m)
+        v = np.stack([w[:, 0] + w[:, 1], w[:, 0] - w[:, 1]], axis=1).reshape(1 << kp, m)
+        counter[0] += b
+        h *= 2
+    out = np.empty_like(v)
+    for piece in range(1 << kp):
+        z = v[piece]
+        if dense_base:
+            for i in range(m):
+                acc = H[0, i] * z[0]
+                for r in range(1, m):
+                    acc = acc + z[r] if H[r, i] > 0 else acc - z[r]
+                    counter[0] += 1
+                out[piece, i] = acc
+            continue
+        combos = []
+        for g in range(t):
+            a_, b_, c_, d_ = z[4 * g:4 * g + 4]
+            p, q_, r_, s_ = a_ + b_, a_ - b_, c_ + d_, c_ - d_
+            counter[0] += 4
+            # keyed by the signs of (b, c, d) relative to a
+            table = {(1, 1, 1): p + r_, (1, -1, -1): p - r_, (1, 1, -1): p + s_, (1, -1, 1): p - s_,
+                     (-1, 1, 1): q_ + r_, (-1, -1, -1): q_ - r_, (-1, 1, -1): q_ + s_, (-1, -1, 1): q_ - s_}
+            counter[0] += 8
+            combos.append(table)
+        for i in range(m):
+            acc = None
+            for g in range(t):
+                col = H[4 * g:4 * g + 4, i]
+                lead = int(col[0])
+                term = combos[g][(int(col[1]) * lead, int(col[2]) * lead, int(col[3]) * lead)]
+                if acc is None:
+                    acc = term if lead > 0 else -term      # a sign on the first term is not an add/sub
+                else:
+                    acc = acc + term if lead > 0 else acc - term
+                    counter[0] += 1
+            out[piece, i] = acc
+    return out.reshape(b)
 
 
 def fwht_f64(X: np.ndarray, b: int, counter: list | None = None) -> np.ndarray:

@@ -27,7 +27,7 @@ struct ColabsPlan {
 ColabsPlan colabs_plan(int64_t M, int32_t d) {
     ColabsPlan pl;
     pl.col_tiles = (d + kTileCols - 1) / kTileCols;
-    int64_t want = 2048 / pl.col_tiles;          // ~8 workgroups per CU in total
+    int64_t want = 512 / pl.col_tiles;           // ~2 workgroups per CU: longer row loops, small partials
     if (want < 1) want = 1;
     int64_t rps = (M + want - 1) / want;
     if (rps < 8) rps = 8;                        // at least a few rows per lane

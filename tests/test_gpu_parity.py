@@ -204,8 +204,9 @@ def test_colabs_mean(M, d):
     _torch().cuda.synchronize()
     got = got.cpu().numpy()
     want = orc.colabs_mean(orc.bf16_bits_to_f64(bits))
-    # fp32 accumulation: rows-per-slice sequential adds, then <= 2048 partials; all terms >= 0
-    assert np.all(np.abs(got - want) <= 2e-6 * want + 1e-30)
+    # fp32 accumulation of non-negative terms, at most 32 rows per slice at these M, then a
+    # reduction in double: relative error below 33 * 2^-24
+    assert np.all(np.abs(got - want) <= 33 * 2.0**-24 * want + 1e-30)
     again = binding.perq_colabs_mean(binding.bits_to_device(bits)).cpu().numpy()
     assert np.array_equal(got, again)
     # constant-magnitude columns are exact

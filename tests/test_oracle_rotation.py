@@ -164,6 +164,93 @@ def test_table3_addsub_counts():
         assert ctr[0] == count
 
 
+# ---- non-power-of-two rotation (Appendix A.1) -------------------------------------------------
+@pytest.mark.parametrize("m", [12, 28, 76])
+def test_paley_base_is_hadamard(m):
+    H = orc.paley_hadamard(m)
+    assert H.shape == (m, m) and set(np.unique(H).tolist()) == {-1, 1}
+    assert np.array_equal(H @ H.T, m * np.eye(m, dtype=np.int64))
+    assert np.array_equal(H.T @ H, m * np.eye(m, dtype=np.int64))
+    # type II matrices are symmetric; the type I matrix is the identity plus a skew matrix
+    # whose first row is all ones
+    if m == 12:
+        assert np.array_equal(H + H.T, 2 * np.eye(m, dtype=np.int64))
+        assert np.all(H[0] == 1) and np.all(H[1:, 0] == -1)
+    else:
+        assert np.array_equal(H, H.T)
+
+
+def test_paley_residues_by_euler_criterion():
+    # chi(x) = x^((q-1)/2) mod q, computed here with modular powers rather than a table of squares
+    for m, q, two in [(12, 11, False), (28, 13, True), (76, 37, True)]:
+        H = orc.paley_hadamard(m)
+        for i in range(q):
+            for j in range(q):
+                if i == j:
+                    continue
+                chi = 1 if pow((i - j) % q, (q - 1) // 2, q) == 1 else -1
+                got = H[2 * (1 + i), 2 * (1 + j)] if two else H[1 + i, 1 + j]
+                assert got == chi
+
+
+@pytest.mark.parametrize("b", [48, 96, 112, 224, 152])
+def test_kronecker_rotation_equals_explicit_matrix(b):
+    kp, m = orc.hadamard_factors(b)
+    assert (1 << kp) * m == b
+    H = orc.hadamard_matrix(b)
+    assert np.array_equal(H @ H.T, b * np.eye(b, dtype=np.int64))
+    base = orc.paley_hadamard(m)
+    assert np.array_equal(H[:m, :m], base) and np.array_equal(H[m:2 * m, m:2 * m], -base if kp else base)
+    X = _rng(b).standard_t(4, size=(5, 3 * b))
+    want = (X.reshape(15, b) @ H.astype(np.float64) / math.sqrt(b)).reshape(5, 3 * b)
+    got = orc.block_hadamard(X, b)
+    assert np.allclose(got, want, rtol=0, atol=1e-12 * np.abs(X).sum(axis=1).max())
+    # rotation: l2 norm of every block preserved, |y|_inf <= |x|_1 / sqrt(b) (Proposition 1)
+    assert np.allclose((got.reshape(-1, b) ** 2).sum(1), (X.reshape(-1, b) ** 2).sum(1), rtol=1e-12)
+    assert np.all(np.abs(got).reshape(-1, b).max(1) <= np.abs(X).reshape(-1, b).sum(1) / math.sqrt(b) * (1 + 1e-12))
+
+
+def test_nonpo2_one_hot():
+    # c e_i -> c times row i of H_b / sqrt(b): every output of the block has magnitude |c| / sqrt(b)
+    b = 224
+    H = orc.hadamard_matrix(b)
+    for i in (0, 5, 27, 28, 223):
+        x = np.zeros((1, 2 * b)); x[0, b + i] = 3.0
+        y = orc.block_hadamard(x, b)
+        assert np.all(y[0, :b] == 0)
+        assert np.allclose(y[0, b:], 3.0 * H[i] / math.sqrt(b), rtol=0, atol=1e-15)
+        assert np.allclose(np.abs(y[0, b:]), 3.0 / math.sqrt(b), rtol=1e-15)
+
+
+def _printed(count, unit):
+    return f"{count / (1e6 if unit == 'M' else 1e3):.2f}{unit}"
+
+
+def test_appendix_a1_operation_counts():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "table4_nonpo2_counts.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 5
+    for d, pieces, base, matmul, bfly_mm, ours, full in rows:
+        d, pieces, base = int(d), int(pieces), int(base)
+        kp, m = orc.hadamard_factors(d)
+        assert (1 << kp, m) == (pieces, base)
+        x = _rng(d).standard_normal(d)
+        want = orc.block_hadamard(x[None, :], d)[0] * math.sqrt(d)
+        tol = 1e-12 * np.abs(x).sum()
+        ctr = [0]
+        got = orc.nonpo2_rotation_counted(x, d, ctr)
+        assert np.allclose(got, want, rtol=0, atol=tol)
+        assert _printed(ctr[0], "K") == ours
+        assert ctr[0] == d * (kp + m // 4 + 2)
+        if full != "-":
+            assert ctr[0] == int(full)
+        ctr = [0]
+        got = orc.nonpo2_rotation_counted(x, d, ctr, dense_base=True)
+        assert np.allclose(got, want, rtol=0, atol=tol)
+        assert _printed(ctr[0], "K") == bfly_mm
+        assert _printed(d * (d - 1), "M") == matmul      # a dense product: d - 1 add/sub per output
+
+
 def test_bf16_decode():
     bits = np.array([0x3F80, 0xBF80, 0x0000, 0x8000, 0x4049, 0x7F7F, 0x0001], dtype=np.uint16)
     want = [1.0, -1.0, 0.0, -0.0, 3.140625, 3.3895313892515355e38, 2.0 ** -133]
