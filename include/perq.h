@@ -119,6 +119,21 @@ perq_status_t perq_massdiff_perm(const float* colabs_mean, int32_t d, int32_t b,
 perq_status_t perq_perm_sorted(const float* stat, int32_t d, int32_t* perm_out);
 perq_status_t perq_perm_zigzag(const float* stat, int32_t d, int32_t b, int32_t* perm_out);
 
+/*
+ * The 4t-dimensional base matrix of the rotation for a block size that is not a power of two
+ * (Appendix A.1, "An Optimized Non-Power-of-2 Hadamard Rotation"): b = 2^k' * m, m = 4t, t odd, and
+ * R = (H_{2^k'} (x) H_m) / sqrt(b), H_{2^k'} Sylvester's matrix, position a*m + r of a block
+ * belonging to row a of the first factor and row r of the second.  The appendix prints no base
+ * matrix; the library takes Paley's constructions over a prime field, Q[i][j] = chi(i - j):
+ *   m - 1 prime, = 3 mod 4:    H_m = I + [[0, 1^T], [-1, Q]]                          (m = 12)
+ *   else m/2 - 1 prime, = 1 mod 4:  [[0, 1^T], [1, Q]] with 0 -> [[1,-1],[-1,-1]] and
+ *                                   e = +-1 -> e [[1,1],[1,-1]]                       (m = 28, 76)
+ *   out   host, int8 [m][m], entries +-1; a row vector x is rotated as x H_m
+ * INVALID_ARG when neither construction exists for m.  Needed offline to rotate the weights that
+ * meet the activations (W~ = R~^T P^T W).
+ */
+perq_status_t perq_hadamard_base(int32_t m, int8_t* out);
+
 /* OK iff perm (host, int32 [d]) is a bijection on [0, d); INVALID_ARG otherwise. */
 perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
 
@@ -127,7 +142,9 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  *
  *   x_bf16   device, bf16 [T, ldx]; ldx >= d; base 16-byte aligned and ldx % 8 == 0
  *   perm     device, int32 [d], or NULL for P = I
- *   b        power of two, 16 <= b <= d, b divides d
+ *   b        16 <= b <= d, b divides d; a power of two, or 2^k' * 28 (k' >= 0; see
+ *            perq_hadamard_base) for d = 3584, 7168 or 14336 -- other non-powers of two whose base
+ *            matrix the library can build (4t = 12, 76) are UNSUPPORTED so far, the rest INVALID_ARG
  *   codes    device, uint8 [T, d/2]; element 2k in the low nibble of byte k, 2k+1 in the high
  *   scales   INT4:  device float [T], s_t = ||y_t||_inf / 7 (0 for an all-zero row)
  *            MXFP4: device uint8 [T, d/32], biased exponent E, scale = 2^(E-127),

@@ -24,7 +24,8 @@ ALGO = {"auto": PERQ_ALGO_AUTO, "butterfly": PERQ_ALGO_BUTTERFLY, "mfma": PERQ_A
 EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colabs_mean",
            "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
            "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
-           "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics"]
+           "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
+           "perq_hadamard_base"]
 
 _lib = None
 
@@ -72,6 +73,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_perm_sorted.restype = ctypes.c_int
     lib.perq_perm_zigzag.argtypes = [vp, i32, i32, vp]
     lib.perq_perm_zigzag.restype = ctypes.c_int
+    lib.perq_hadamard_base.argtypes = [i32, vp]
+    lib.perq_hadamard_base.restype = ctypes.c_int
     lib.perq_block_diagnostics.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
     lib.perq_block_diagnostics.restype = ctypes.c_int
     _lib = lib
@@ -122,6 +125,13 @@ def perq_perm_sorted(stat: np.ndarray) -> np.ndarray:
     _check(load().perq_perm_sorted(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], perm.ctypes.data_as(ctypes.c_void_p)),
            "perq_perm_sorted")
     return perm
+
+
+def perq_hadamard_base(m: int) -> np.ndarray:
+    """The m x m base matrix (+-1, int8) of the non-power-of-two rotation."""
+    out = np.empty((max(int(m), 1), max(int(m), 1)), dtype=np.int8)
+    _check(load().perq_hadamard_base(int(m), out.ctypes.data_as(ctypes.c_void_p)), "perq_hadamard_base")
+    return out
 
 
 def perq_perm_zigzag(stat: np.ndarray, b: int) -> np.ndarray:

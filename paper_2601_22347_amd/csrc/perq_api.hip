@@ -1,5 +1,6 @@
 // C-ABI entry points of the fused apply path: argument checks, kernel choice, launch.
 #include "perq.h"
+#include "perq_base.h"
 #include "perq_launch.h"
 
 #include <cmath>
@@ -37,7 +38,13 @@ bool is_pow2(int32_t v) { return v > 0 && (v & (v - 1)) == 0; }
 perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, const int32_t* perm,
                           int32_t b, ApplyParams* p) {
     if (T < 0 || d <= 0 || ldx < d) return PERQ_ERR_INVALID_ARG;
-    if (!is_pow2(b) || b < 16 || b > d || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    if (b < 16 || b > d || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    if (!is_pow2(b)) {
+        // b = 2^k' * 4t, t odd: a rotation exists for the library iff it can build the 4t-dim base
+        int32_t t = b;
+        while (t % 2 == 0) t /= 2;
+        if (b / t < 4 || hadamard_base_kind(4 * t) == 0) return PERQ_ERR_INVALID_ARG;
+    }
     if (d % 32 != 0) return PERQ_ERR_INVALID_ARG;
     if (d > PERQ_MAX_D) return PERQ_ERR_UNSUPPORTED;
     p->T = T;
@@ -69,6 +76,10 @@ perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, 
 perq_status_t dispatch(const ApplyParams& p, int out_kind, perq_algo_t algo, hipStream_t stream) {
     if (p.T == 0) return PERQ_OK;
     hipError_t e;
+    if (!is_pow2(p.b)) {
+        if (algo != PERQ_ALGO_AUTO || !npo2_supports(p)) return PERQ_ERR_UNSUPPORTED;
+        return launch_npo2(p, out_kind, stream) == hipSuccess ? PERQ_OK : PERQ_ERR_LAUNCH;
+    }
     switch (algo) {
         case PERQ_ALGO_AUTO:
             // The matrix-core kernel wins wherever its 4096-wide wave tiles are filled (measured:
@@ -146,6 +157,7 @@ extern "C" perq_status_t perq_block_diagnostics(const uint16_t* x_bf16, int64_t 
     if (st != PERQ_OK || p.T == 0) return st;
     if (out == nullptr) return PERQ_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(out) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
+    if (!perq::is_pow2(b)) return PERQ_ERR_UNSUPPORTED;
     p.y = out;
     return perq::launch_butterfly(p, perq::OUT_DIAG, static_cast<hipStream_t>(hip_stream)) == hipSuccess
                ? PERQ_OK

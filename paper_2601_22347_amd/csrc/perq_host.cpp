@@ -1,6 +1,7 @@
-// Host side of the PeRQ library: status strings, Algorithm 1 (mass diffusion) and the
-// permutation validator.  No device code here.
+// Host side of the PeRQ library: status strings, Algorithm 1 (mass diffusion), the permutation
+// validator and the base matrices of the non-power-of-two rotation.  No device code here.
 #include "perq.h"
+#include "perq_base.h"
 
 #include <algorithm>
 #include <cmath>
@@ -94,5 +95,69 @@ extern "C" perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d)
         if (p < 0 || p >= d || seen[p]) return PERQ_ERR_INVALID_ARG;
         seen[p] = 1;
     }
+    return PERQ_OK;
+}
+
+// ---- base matrices of the non-power-of-two rotation (Appendix A.1) -----------------------------
+namespace perq {
+namespace {
+
+bool prime(int32_t q) {
+    if (q < 2) return false;
+    for (int32_t f = 2; (int64_t)f * f <= q; ++f)
+        if (q % f == 0) return false;
+    return true;
+}
+
+// Legendre symbol of v modulo the odd prime q by Euler's criterion: v^((q-1)/2) mod q.
+int legendre(int32_t v, int32_t q) {
+    v %= q;
+    if (v < 0) v += q;
+    if (v == 0) return 0;
+    int64_t acc = 1, base = v;
+    for (int32_t e = (q - 1) / 2; e > 0; e >>= 1) {
+        if (e & 1) acc = acc * base % q;
+        base = base * base % q;
+    }
+    return acc == 1 ? 1 : -1;
+}
+
+}  // namespace
+
+int hadamard_base_kind(int32_t m) {
+    if (m < 8 || m % 4 != 0) return 0;
+    if (prime(m - 1) && (m - 1) % 4 == 3) return 1;
+    if (prime(m / 2 - 1) && (m / 2 - 1) % 4 == 1) return 2;
+    return 0;
+}
+
+int hadamard_base_entry(int32_t m, int kind, int32_t r, int32_t c) {
+    if (kind == 1) {
+        // I + S, S = [[0, 1^T], [-1, Q]], Q[i][j] = chi(i - j) over Z_(m-1)
+        if (r == c) return 1;
+        if (r == 0) return 1;
+        if (c == 0) return -1;
+        return legendre(r - c, m - 1);
+    }
+    // S = [[0, 1^T], [1, Q]] over Z_(m/2-1); a zero of S becomes [[1,-1],[-1,-1]], an entry e
+    // becomes e [[1,1],[1,-1]]
+    const int32_t R = r >> 1, C = c >> 1, q = m / 2 - 1;
+    const int rr = r & 1, cc = c & 1;
+    int e;
+    if (R == C) e = 0;
+    else if (R == 0 || C == 0) e = 1;
+    else e = legendre(R - C, q);
+    if (e == 0) return (rr == 0 && cc == 0) ? 1 : -1;
+    return (rr == 1 && cc == 1) ? -e : e;
+}
+
+}  // namespace perq
+
+extern "C" perq_status_t perq_hadamard_base(int32_t m, int8_t* out) {
+    if (out == nullptr) return PERQ_ERR_INVALID_ARG;
+    const int kind = perq::hadamard_base_kind(m);
+    if (kind == 0) return PERQ_ERR_INVALID_ARG;
+    for (int32_t r = 0; r < m; ++r)
+        for (int32_t c = 0; c < m; ++c) out[(int64_t)r * m + c] = (int8_t)perq::hadamard_base_entry(m, kind, r, c);
     return PERQ_OK;
 }

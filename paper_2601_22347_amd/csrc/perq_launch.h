@@ -20,5 +20,8 @@ bool mfma_supports(const ApplyParams& p);
 // Whether the matrix-core kernel is the faster of the two for this call (measured crossovers).
 bool mfma_preferred(const ApplyParams& p, int out_kind);
 hipError_t launch_mfma(const ApplyParams& p, int out_kind, hipStream_t stream);
+// Block sizes 2^k' * 28 (non-power-of-two rotation).
+bool npo2_supports(const ApplyParams& p);
+hipError_t launch_npo2(const ApplyParams& p, int out_kind, hipStream_t stream);
 
 }  // namespace perq

@@ -513,3 +513,78 @@ def test_long_launch_sampled_rows():
     nib = codes.view(torch.uint8)
     lo, hi = nib & 0xF, nib >> 4
     assert torch.all(((lo == 7) | (lo == 9) | (hi == 7) | (hi == 9)).any(dim=1))       # every row reaches +-7
+
+
+# ---- block sizes 2^k' * 28 (the non-power-of-two rotation of Appendix A.1) ----------------------
+def _heavy_rows(T, d, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_t(3, size=(T, d)).clip(-1e4, 1e4)
+    x[:, rng.choice(d, max(d // 100, 1), replace=False)] *= 50.0
+    return synth.f64_to_bf16_bits(x)
+
+
+@pytest.mark.parametrize("d,bs", [(3584, [28, 112, 896, 3584]), (7168, [56, 1792, 7168]),
+                                  (14336, [28, 224, 3584, 7168, 14336])])
+@pytest.mark.parametrize("with_perm", [False, True])
+def test_nonpo2_rotation_against_oracle(d, bs, with_perm):
+    T = 13 if d == 14336 else 21                       # ragged against 1, 2 and 4 rows per workgroup pass
+    x = _heavy_rows(T, d, 900 + d)
+    perm = np.random.default_rng(d).permutation(d).astype(np.int32) if with_perm else None
+    for b in bs:
+        for fmt in (["int4", "mxfp4"] if b not in (bs[0], bs[-1]) else ["int4", "mxfp4", "int4_asym", "fp4_token"]):
+            assert_parity(x, perm, b, fmt, "auto", label="nonpo2")
+
+
+def test_nonpo2_structured_rows_and_many_rows():
+    d, b = 14336, 14336
+    H28 = binding.perq_hadamard_base(28).astype(np.float64)
+    # one-hot rows: every output has magnitude |c| / sqrt(b); row a*28 + r of H_512 (x) H_28
+    T = 6
+    x = np.zeros((T, d))
+    hot = [0, 27, 28, 5000, 14335, 7168]
+    for t, i in enumerate(hot):
+        x[t, i] = 2.0 ** (t - 2)
+    bits = synth.f64_to_bf16_bits(x)
+    torch = _torch()
+    y = binding.perq_permute_rotate_f32(binding.bits_to_device(bits), None, b).cpu().numpy().astype(np.float64)
+    for t, i in enumerate(hot):
+        a, r = divmod(i, 28)
+        aa = np.arange(512)
+        sylv = 1.0 - 2.0 * (np.array([bin(a & v).count("1") for v in aa]) & 1)
+        want = (sylv[:, None] * H28[r][None, :]).reshape(d) * 2.0 ** (t - 2) / np.sqrt(b)
+        assert np.allclose(y[t], want, rtol=1e-6, atol=0), (t, i)
+    # all-zero rows, a constant row, and more rows than one pass of the grid covers
+    x = np.zeros((3, d)); x[1] = 1.0
+    for fmt in ("int4", "mxfp4", "int4_asym", "fp4_token"):
+        assert_parity(synth.f64_to_bf16_bits(x), None, b, fmt, "auto", label="nonpo2/zero+const")
+    big = _heavy_rows(1100, d, 77)
+    codes, scales = binding.perq_permute_rotate_quant(binding.bits_to_device(big), None, b, "int4")
+    torch.cuda.synchronize()
+    rows = np.r_[0:8, 505:520, 1017:1032, 1092:1100]
+    rep = parity.compare_apply(big[rows], None, b, "int4", codes.cpu().numpy()[rows], scales.cpu().numpy()[rows])
+    print("       ", rep.summary(), flush=True)
+    assert rep.ok(), rep.summary()
+
+
+def test_nonpo2_argument_checks():
+    torch = _torch()
+    x = torch.zeros((4, 14336), dtype=torch.bfloat16, device="cuda")
+    # 14336 = 2^9 * 28 only: a base of 12 or 76 does not divide it, and 7 * 2^k with k < 2 is no Hadamard order
+    with pytest.raises(binding.PerqError) as ei:
+        binding.perq_permute_rotate_quant(x, None, 14, "int4")
+    assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
+    # known base, width the kernel does not cover
+    x12 = torch.zeros((4, 3072), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.PerqError) as ei:
+        binding.perq_permute_rotate_quant(x12, None, 3072, "int4")
+    assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED
+    # order 4 * 9 = 36 = 2 * (17 + 1) exists by the second construction, 4 * 23 = 92 by neither
+    x92 = torch.zeros((4, 92 * 8), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.PerqError) as ei:
+        binding.perq_permute_rotate_quant(x92, None, 92, "int4")
+    assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
+    # the rotation kernels named explicitly do not take these block sizes
+    for algo in ("butterfly", "mfma"):
+        with pytest.raises(binding.PerqError) as ei:
+            binding.perq_permute_rotate_quant(x, None, 14336, "int4", algo=algo)
+        assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED

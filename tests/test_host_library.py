@@ -116,3 +116,17 @@ def test_sorted_and_zigzag_match_oracle():
         binding.perq_perm_zigzag(np.ones(10, np.float32), 4)
     with pytest.raises(binding.PerqError):
         binding.perq_perm_sorted(np.array([1.0, np.nan], np.float32))
+
+
+@pytest.mark.parametrize("m", [12, 20, 28, 36, 44, 76])
+def test_hadamard_base_matches_oracle_construction(m):
+    H = binding.perq_hadamard_base(m).astype(np.int64)
+    assert np.array_equal(H @ H.T, m * np.eye(m, dtype=np.int64))
+    assert np.array_equal(H, orc.paley_hadamard(m))
+
+
+def test_hadamard_base_rejects_orders_without_a_construction():
+    for m in (4, 10, 16, 92, 0, -12):       # 16: 15 is not prime, 7 = 3 mod 4
+        with pytest.raises(binding.PerqError) as ei:
+            binding.perq_hadamard_base(m)
+        assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
