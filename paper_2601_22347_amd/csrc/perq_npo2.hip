@@ -49,7 +49,10 @@ struct Npo2Geom {
 };
 
 // NCH = chunks per row (d = NCH * 3584); rows per iteration = 4 / NCH.
-template <int OUT, bool PERM, int NCH>
+// STG >= 0: the block spans whole chunks (k' = 7 + STG): all seven in-chunk stages and STG stages
+// across chunks, unconditionally.  STG = -1: k' < 7 is read at run time (a stage that may or may
+// not run costs a register copy per element on top of its two operations).
+template <int OUT, bool PERM, int NCH, int STG>
 __global__ void __launch_bounds__(kThreads, 2)
 npo2_kernel(const ApplyParams p, const Npo2Geom g) {
     constexpr int kRows = kChunks / NCH;
@@ -64,7 +67,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
     const int lane = tid & 63, wave = tid >> 6;
     const int c = lane & 31, h = lane >> 5;
     const int d = p.d;
-    const int kp = g.kp;
+    const int kp = STG >= 0 ? 7 + STG : g.kp;
     const int my_row = wave / NCH;          // row of the iteration this wave works on
     const int my_chunk = wave % NCH;        // chunk of that row (phase 1)
     unsigned char* const ex_bytes = reinterpret_cast<unsigned char*>(ex);
@@ -121,25 +124,31 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
 
     const int64_t n_units = (p.T + kRows - 1) / kRows;
     uint4 pre[kPre];
+    // 16-byte piece i of this thread: which row of the unit, where in the row, where in LDS
+    uint32_t g_off[kPre], l_off[kPre];
+    int g_row[kPre];
+#pragma unroll
+    for (int i = 0; i < kPre; ++i) {
+        const int gi = tid + kThreads * i;
+        g_row[i] = gi / kRowGranules;
+        g_off[i] = (uint32_t)g_row[i] * (uint32_t)(p.ldx * 2) + 16u * (uint32_t)(gi % kRowGranules);
+        l_off[i] = (uint32_t)(gi / (kChunkPos * 2 / 16)) * (uint32_t)(kChunkPos * 4) + 16u * (uint32_t)(gi % (kChunkPos * 2 / 16));
+    }
 
     auto issue_loads = [&](int64_t unit) {
+        // rows of the unit that exist (uniform); the unit's first row as a scalar base address
+        const int64_t left = p.T - unit * kRows;
+        const int live = unit < n_units ? (left < kRows ? (int)left : kRows) : 0;
+        const unsigned char* base = reinterpret_cast<const unsigned char*>(p.x) + unit * kRows * p.ldx * 2;
 #pragma unroll
         for (int i = 0; i < kPre; ++i) {
-            const int gi = tid + kThreads * i;
-            const int rr = gi / kRowGranules, gr = gi % kRowGranules;
-            const int64_t row = unit * kRows + rr;
             pre[i] = make_uint4(0, 0, 0, 0);
-            if (unit < n_units && row < p.T)
-                pre[i] = load_stream16(reinterpret_cast<const unsigned char*>(p.x + row * p.ldx) + 16 * gr);
+            if (g_row[i] < live) pre[i] = load_stream16(base + g_off[i]);
         }
     };
     auto stage_rows = [&]() {
 #pragma unroll
-        for (int i = 0; i < kPre; ++i) {
-            const int gi = tid + kThreads * i;
-            const int chunk = gi / (kChunkPos * 2 / 16), gc = gi % (kChunkPos * 2 / 16);
-            *reinterpret_cast<uint4*>(ex_bytes + chunk * (kChunkPos * 4) + 16 * gc) = pre[i];
-        }
+        for (int i = 0; i < kPre; ++i) *reinterpret_cast<uint4*>(ex_bytes + l_off[i]) = pre[i];
     };
 
     int64_t unit = blockIdx.x;
@@ -199,20 +208,32 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
                 }
             }
         };
-        if (kp > 0) pair_stage(1);       // a bit 0
-        if (kp > 1) pair_stage(2);       // a bit 1
-        if (kp > 2) lane_stage<32, 64>(v, 0.0f);   // a bit 2: the two half-waves
-        if (kp > 3) pair_stage(4);       // a bit 3
-        if (kp > 4) pair_stage(8);       // a bit 4
-        if (kp > 5) pair_stage(16);      // a bit 5
-        if (kp > 6) pair_stage(32);      // a bit 6
-
+        if (STG >= 0 || kp > 0) pair_stage(1);       // a bit 0
+        if (STG >= 0 || kp > 1) pair_stage(2);       // a bit 1
+        if (STG >= 0 || kp > 3) pair_stage(4);       // a bit 3
+        if (STG >= 0 || kp > 4) pair_stage(8);       // a bit 4
+        if (STG >= 0 || kp > 5) pair_stage(16);      // a bit 5
+        if (STG >= 0 || kp > 6) pair_stage(32);      // a bit 6
+        // a bit 2 separates the half-waves.  One half-wave swap per register pair (i, i+1) hands
+        // the low lanes both halves of register i and the high lanes both halves of register i+1;
+        // sum and difference stay there.  Afterwards the half-wave tells a bit 0 and the slot in
+        // the pair a bit 2.  Without this stage (k' <= 2) the same swap only re-sorts the values,
+        // so that the addresses below hold either way.
+        const bool stage2 = STG >= 0 || kp > 2;
+#pragma unroll
+        for (int i = 0; i < 64; i += 2) {
+            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[i + 1]), false, false);
+            const float lo = __uint_as_float(sw[0]), hi = __uint_as_float(sw[1]);
+            v[i] = stage2 ? lo + hi : lo;
+            v[i + 1] = stage2 ? lo - hi : hi;
+        }
         if (c < kBase) {
-            float* dst = ex + wave * kChunkPos + (4 * h) * kBase + c;
+            float* dst = ex + wave * kChunkPos + h * kBase + c;
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) dst[(32 * mt + 8 * (j >> 2) + (j & 3)) * kBase] = v[mt * 16 + j];
+                for (int j = 0; j < 16; ++j)
+                    dst[(32 * mt + 8 * (j >> 2) + 4 * (j & 1) + (j & 2)) * kBase] = v[mt * 16 + j];
         }
         __syncthreads();                                   // all chunks of all rows are in LDS
 
@@ -236,7 +257,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
                 }
             }
             if constexpr (NCH >= 2) {
-                if (kp > 7) {
+                if (STG >= 1) {
 #pragma unroll
                     for (int ch = 0; ch < NCH; ch += 2)
 #pragma unroll
@@ -248,7 +269,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
                 }
             }
             if constexpr (NCH >= 4) {
-                if (kp > 8) {
+                if (STG >= 2) {
 #pragma unroll
                     for (int ch = 0; ch < 2; ++ch)
 #pragma unroll
@@ -382,14 +403,34 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
     }
 }
 
+template <int OUT, bool PERM, int NCH>
+hipError_t launch_stg(const ApplyParams& p, const Npo2Geom& g, dim3 grid, hipStream_t stream) {
+    const int stg = g.kp - 7;
+    if (stg < 0) {
+        hipLaunchKernelGGL((npo2_kernel<OUT, PERM, NCH, -1>), grid, dim3(kThreads), 0, stream, p, g);
+    } else if (stg == 0) {
+        hipLaunchKernelGGL((npo2_kernel<OUT, PERM, NCH, 0>), grid, dim3(kThreads), 0, stream, p, g);
+    } else if constexpr (NCH >= 2) {
+        if (stg == 1) {
+            hipLaunchKernelGGL((npo2_kernel<OUT, PERM, NCH, 1>), grid, dim3(kThreads), 0, stream, p, g);
+        } else if constexpr (NCH >= 4) {
+            hipLaunchKernelGGL((npo2_kernel<OUT, PERM, NCH, 2>), grid, dim3(kThreads), 0, stream, p, g);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 template <int OUT, bool PERM>
 hipError_t launch_nch(const ApplyParams& p, const Npo2Geom& g, int nch, dim3 grid, hipStream_t stream) {
     switch (nch) {
-        case 1: hipLaunchKernelGGL((npo2_kernel<OUT, PERM, 1>), grid, dim3(kThreads), 0, stream, p, g); break;
-        case 2: hipLaunchKernelGGL((npo2_kernel<OUT, PERM, 2>), grid, dim3(kThreads), 0, stream, p, g); break;
-        default: hipLaunchKernelGGL((npo2_kernel<OUT, PERM, 4>), grid, dim3(kThreads), 0, stream, p, g); break;
+        case 1: return launch_stg<OUT, PERM, 1>(p, g, grid, stream);
+        case 2: return launch_stg<OUT, PERM, 2>(p, g, grid, stream);
+        default: return launch_stg<OUT, PERM, 4>(p, g, grid, stream);
     }
-    return hipGetLastError();
 }
 
 template <int OUT>
@@ -404,7 +445,8 @@ bool npo2_supports(const ApplyParams& p) {
     if (p.d != kChunkPos && p.d != 2 * kChunkPos && p.d != 4 * kChunkPos) return false;
     if (p.b % kBase != 0) return false;
     const int32_t a = p.b / kBase;
-    return a > 0 && (a & (a - 1)) == 0 && p.d % p.b == 0;
+    // row offsets inside a unit of up to four rows are kept in 32 bits
+    return a > 0 && (a & (a - 1)) == 0 && p.d % p.b == 0 && p.ldx < ((int64_t)1 << 28);
 }
 
 hipError_t launch_npo2(const ApplyParams& p, int out_kind, hipStream_t stream) {
