@@ -47,6 +47,13 @@ __device__ __forceinline__ void store_stream16(void* p, uint4 v) {
     __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
 }
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave, which would expose the latency of loads issued
+// ahead of their use once per barrier.
+__device__ __forceinline__ void workgroup_barrier_lds() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ __forceinline__ float bf16lo_to_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 

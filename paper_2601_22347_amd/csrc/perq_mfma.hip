@@ -113,9 +113,6 @@ __device__ __forceinline__ uint32_t lds_load4(const void* p) {
     asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(lds_addr(p)) : "memory");
     return v;
 }
-__device__ __forceinline__ void workgroup_barrier_lds() {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
 
 // STAGES = number of +-1 butterfly stages after the matrix product: log2(b) - 5, 0 for b <= 32.
 // A template parameter so that the accumulators stay in registers along one straight path.

@@ -4,16 +4,19 @@
 // A block of the (permuted) row is a [2^k'][28] array Z (position a*28 + r); the rotation is
 // H_{2^k'} Z H_28 / sqrt(b).
 //
-//   1. Z H_28 is a dense product on the MFMA unit: v_mfma_f32_32x32x16_bf16 with the data as the
-//      A operand (row m = 32 consecutive a, contraction index k = r, padded from 28 to 32 with
-//      zero rows of B) and the +-1 base matrix as B.  bf16 x (+-1) is exact, sums are fp32.
-//      A lane (c, h) then holds column r' = c of 16 rows a per accumulator tile.
-//   2. The Sylvester factor acts on a.  A wave owns a chunk of 128 consecutive a (four tiles):
-//      a-bits 0,1,3,4 (accumulator index), 5,6 (tile) are in-register butterflies, bit 2 (the
-//      half-wave) one swap stage.  Bits 7 and up join different waves' chunks: every wave leaves
-//      its chunk in LDS as fp32 in position order, and after a barrier each thread collects 16
-//      consecutive positions of every chunk of its row and finishes the remaining one or two
-//      stages in registers.
+//   1. Z H_28 and two bits of a (5 and 6) are one dense product on the MFMA unit
+//      (v_mfma_f32_32x32x16_bf16): the data are the A operand, row m = a & 31, contraction
+//      index k = 32 ((a >> 5) & 3) + r (r padded from 28 to 32 by zero rows of B); accumulator
+//      tile n (n = 0..3: the output's bits 5, 6) takes, k-step by k-step, the base matrix or its
+//      negative as B, according to H_4.  bf16 x (+-1) is exact, sums are fp32.  A lane (c, h) then holds
+//      column r' = c of 16 rows per tile.  The matrix unit is nearly idle in this kernel, the
+//      vector ALU is what limits it: every stage moved into the product is two VALU per element less.
+//   2. The rest of the Sylvester factor: a wave owns a chunk of 128 consecutive a; a-bits
+//      0,1,3,4 (accumulator index) are in-register butterflies, bit 2 (the half-wave) one swap
+//      stage.  Bits 7 and up join different waves' chunks: every wave leaves its chunk in LDS
+//      as fp32 in position order, and after a barrier each thread collects 16 consecutive
+//      positions of every chunk of its row and finishes the remaining one or two stages in
+//      registers.
 //   3. In that layout (16 consecutive outputs per thread and chunk) the row statistics, the
 //      rounding and the nibble packing are those of the other kernels.
 //
@@ -26,6 +29,7 @@
 #include "perq_launch.h"
 
 #include <cmath>
+#include <type_traits>
 
 namespace perq {
 namespace {
@@ -72,26 +76,32 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
     const int my_chunk = wave % NCH;        // chunk of that row (phase 1)
     unsigned char* const ex_bytes = reinterpret_cast<unsigned char*>(ex);
 
-    // ---- B operand: lane (c, h) supplies k = 16 kt + 8 h + e of column c ------------------------
-    bf16x8_t bfrag[2];
+    // ---- B operand: lane (c, h) supplies r = 16 half + 8 h + e of column c; both signs -----------
+    bf16x8_t bpos[2], bneg[2];
+    uint32_t hrow[32];                          // (copied first: uniform values, selected by lane below)
 #pragma unroll
-    for (int kt = 0; kt < 2; ++kt) {
+    for (int k = 0; k < 32; ++k) hrow[k] = g.hrow[k];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
         uint32_t w[4];
 #pragma unroll
         for (int e2 = 0; e2 < 4; ++e2) {
             uint32_t pair = 0;
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                const int k_lo = 16 * kt + 2 * e2 + s;               // h = 0
+                const int k_lo = 16 * half + 2 * e2 + s;             // h = 0
                 const int k_hi = k_lo + 8;                           // h = 1
-                const uint32_t bits = h ? g.hrow[k_hi] : g.hrow[k_lo];
+                const uint32_t bits = h ? hrow[k_hi] : hrow[k_lo];
                 const bool live = (h ? k_hi : k_lo) < kBase && c < kBase;
                 const uint32_t val = live ? (((bits >> c) & 1u) ? 0xBF80u : 0x3F80u) : 0u;
                 pair |= val << (16 * s);
             }
             w[e2] = pair;
         }
-        bfrag[kt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+        bpos[half] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+        // (a zero entry stays +0 or becomes -0: either way it contributes nothing)
+        bneg[half] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0] ^ 0x80008000u, w[1] ^ 0x80008000u,
+                                                              w[2] ^ 0x80008000u, w[3] ^ 0x80008000u));
     }
 
     // ---- gather table (P != I): LDS byte address, relative to the row's first chunk, of the
@@ -99,7 +109,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
     uint32_t tab[PERM ? 32 : 1];
     if constexpr (PERM) {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < 4; ++mt)          // (a >> 5) & 3
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -123,19 +133,31 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
     }
 
     const int64_t n_units = (p.T + kRows - 1) / kRows;
-    uint4 pre[kPre];
-    // 16-byte piece i of this thread: which row of the unit, where in the row, where in LDS
-    uint32_t g_off[kPre], l_off[kPre];
-    int g_row[kPre];
-#pragma unroll
-    for (int i = 0; i < kPre; ++i) {
+    // 16-byte piece i of this thread: which row of the unit, where in the row, where in LDS.
+    // Kept in registers across rows where registers are to spare (P = I), recomputed otherwise.
+    constexpr bool kHoist = !PERM;
+    auto piece_row = [&](int i) { return (tid + kThreads * i) / kRowGranules; };
+    auto piece_goff = [&](int i) {
         const int gi = tid + kThreads * i;
-        g_row[i] = gi / kRowGranules;
-        g_off[i] = (uint32_t)g_row[i] * (uint32_t)(p.ldx * 2) + 16u * (uint32_t)(gi % kRowGranules);
-        l_off[i] = (uint32_t)(gi / (kChunkPos * 2 / 16)) * (uint32_t)(kChunkPos * 4) + 16u * (uint32_t)(gi % (kChunkPos * 2 / 16));
+        return (uint32_t)(gi / kRowGranules) * (uint32_t)(p.ldx * 2) + 16u * (uint32_t)(gi % kRowGranules);
+    };
+    auto piece_loff = [&](int i) {
+        const int gi = tid + kThreads * i;
+        return (uint32_t)(gi / (kChunkPos * 2 / 16)) * (uint32_t)(kChunkPos * 4) + 16u * (uint32_t)(gi % (kChunkPos * 2 / 16));
+    };
+    uint32_t g_off[kHoist ? kPre : 1], l_off[kHoist ? kPre : 1];
+    if constexpr (kHoist) {
+#pragma unroll
+        for (int i = 0; i < kPre; ++i) {
+            g_off[i] = piece_goff(i);
+            l_off[i] = piece_loff(i);
+        }
+    } else {
+        g_off[0] = 0;
+        l_off[0] = 0;
     }
 
-    auto issue_loads = [&](int64_t unit) {
+    auto issue_loads = [&](uint4 (&pre)[kPre], int64_t unit) {
         // rows of the unit that exist (uniform); the unit's first row as a scalar base address
         const int64_t left = p.T - unit * kRows;
         const int live = unit < n_units ? (left < kRows ? (int)left : kRows) : 0;
@@ -143,24 +165,27 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
 #pragma unroll
         for (int i = 0; i < kPre; ++i) {
             pre[i] = make_uint4(0, 0, 0, 0);
-            if (g_row[i] < live) pre[i] = load_stream16(base + g_off[i]);
+            if (piece_row(i) < live) pre[i] = load_stream16(base + (kHoist ? g_off[i] : piece_goff(i)));
         }
     };
-    auto stage_rows = [&]() {
+    auto stage_rows = [&](const uint4 (&pre)[kPre]) {
 #pragma unroll
-        for (int i = 0; i < kPre; ++i) *reinterpret_cast<uint4*>(ex_bytes + l_off[i]) = pre[i];
+        for (int i = 0; i < kPre; ++i)
+            *reinterpret_cast<uint4*>(ex_bytes + (kHoist ? l_off[i] : piece_loff(i))) = pre[i];
     };
 
-    int64_t unit = blockIdx.x;
-    issue_loads(unit);
-    stage_rows();
-    issue_loads(unit + gridDim.x);
+    // Raw rows are requested one unit ahead of their use.  (The barriers below wait for LDS only,
+    // so these loads stay in flight across them; a second unit of prefetch was measured: no gain.)
+    const int64_t stride = gridDim.x;
+    uint4 pre[kPre];
 
-    for (; unit < n_units; unit += gridDim.x) {
-        __syncthreads();                                   // raw rows of this unit are in LDS
+    auto body = [&](int64_t unit) {
+        workgroup_barrier_lds();                                   // raw rows of this unit are in LDS
         // ---- phase 1: base product and the in-wave stages on one chunk -------------------------
         const unsigned char* stage = ex_bytes + wave * (kChunkPos * 4);
         const unsigned char* row_stage = ex_bytes + my_row * NCH * (kChunkPos * 4);
+        // afrag[al][half]: row c of A is a & 31 = c, the k-step covers (a >> 5) & 3 = al, r = 16 half + 8 h + e
+        // (lane pitch 56 bytes: the 32 rows of one read fall into different banks)
         bf16x8_t afrag[4][2];
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
@@ -186,18 +211,39 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
                 afrag[mt][kt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
             }
         }
-        if constexpr (PERM) __syncthreads();               // every wave has its operands: the chunks may be overwritten
 
+        // Accumulator tile nt collects the outputs with (a >> 5) & 3 = nt: the sum over al of
+        // H[al][nt] * (Z_al H_28), H = H_4 when the block spans the whole chunk (k' >= 7),
+        // I_2 (x) H_2 for k' = 6 and I_4 below.
+        f32x16_t acc[4];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[nt] = f32x16_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        // keep: those of a-bits 5, 6 that lie above the block (they must agree between input and output)
+        auto products = [&](auto keep_const) {
+            constexpr int keep = decltype(keep_const)::value;
+#pragma unroll
+            for (int al = 0; al < 4; ++al) {
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    if (((al ^ nt) & keep) == 0) {
+                        const bool minus = (__builtin_popcount(al & nt & ~keep) & 1) != 0;
+#pragma unroll
+                        for (int half = 0; half < 2; ++half)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[al][half], minus ? bneg[half] : bpos[half],
+                                                                              acc[nt], 0, 0, 0);
+                    }
+                }
+            }
+        };
+        if (STG >= 0) products(std::integral_constant<int, 0>{});
+        else if (kp == 6) products(std::integral_constant<int, 2>{});
+        else products(std::integral_constant<int, 3>{});
         float v[64];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mt][0], bfrag[0], acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[mt][1], bfrag[1], acc, 0, 0, 0);
+        for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) v[mt * 16 + j] = acc[j];
-        }
-        // accumulator j of tile mt in lane (c, h): a = 32 mt + 8 (j >> 2) + 4 h + (j & 3)
+            for (int j = 0; j < 16; ++j) v[nt * 16 + j] = acc[nt][j];
+        // accumulator j of tile nt in lane (c, h): a = 32 nt + 8 (j >> 2) + 4 h + (j & 3)
         auto pair_stage = [&](int bit_in_index) {
 #pragma unroll
             for (int i = 0; i < 64; ++i) {
@@ -212,8 +258,6 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
         if (STG >= 0 || kp > 1) pair_stage(2);       // a bit 1
         if (STG >= 0 || kp > 3) pair_stage(4);       // a bit 3
         if (STG >= 0 || kp > 4) pair_stage(8);       // a bit 4
-        if (STG >= 0 || kp > 5) pair_stage(16);      // a bit 5
-        if (STG >= 0 || kp > 6) pair_stage(32);      // a bit 6
         // a bit 2 separates the half-waves.  One half-wave swap per register pair (i, i+1) hands
         // the low lanes both halves of register i and the high lanes both halves of register i+1;
         // sum and difference stay there.  Afterwards the half-wave tells a bit 0 and the slot in
@@ -227,15 +271,16 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
             v[i] = stage2 ? lo + hi : lo;
             v[i + 1] = stage2 ? lo - hi : hi;
         }
+        if constexpr (PERM) workgroup_barrier_lds();   // every wave has gathered its operands: the chunks may be overwritten
         if (c < kBase) {
             float* dst = ex + wave * kChunkPos + h * kBase + c;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
-                    dst[(32 * mt + 8 * (j >> 2) + 4 * (j & 1) + (j & 2)) * kBase] = v[mt * 16 + j];
+                    dst[(32 * nt + 8 * (j >> 2) + 4 * (j & 1) + (j & 2)) * kBase] = v[nt * 16 + j];
         }
-        __syncthreads();                                   // all chunks of all rows are in LDS
+        workgroup_barrier_lds();                                   // all chunks of all rows are in LDS
 
         // ---- phase 2: 16 consecutive positions of every chunk of the row per thread ------------
         const int t_row = tid - my_row * kThreadsPerRow;
@@ -318,9 +363,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
                 for (int j = 0; j < kRed; ++j) red[j][wave] = m[j];
             }
         }
-        __syncthreads();            // statistics visible; nobody reads the fp32 chunks any more
-        stage_rows();               // the next unit's raw rows
-        issue_loads(unit + 2 * (int64_t)gridDim.x);
+        workgroup_barrier_lds();            // statistics visible; nobody reads the fp32 chunks any more
+        stage_rows(pre);            // the next unit's raw rows
+        if constexpr (!PERM) issue_loads(pre, unit + 2 * stride);
         if constexpr (kTokenStat) {
 #pragma unroll
             for (int j = 0; j < kRed; ++j) {
@@ -400,7 +445,15 @@ npo2_kernel(const ApplyParams p, const Npo2Geom g) {
                 static_cast<float2*>(p.scales)[row] =
                     make_float2((float)((double)(m[0] + m[1]) * p.inv_15sqrt_b), (float)qa.z);
         }
-    }
+        // (with a gather table held, the registers are free again only here)
+        if constexpr (PERM) issue_loads(pre, unit + 2 * stride);
+    };
+
+    int64_t unit = blockIdx.x;
+    issue_loads(pre, unit);
+    stage_rows(pre);
+    issue_loads(pre, unit + stride);
+    for (; unit < n_units; unit += stride) body(unit);
 }
 
 template <int OUT, bool PERM, int NCH>
