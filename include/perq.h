@@ -142,9 +142,10 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  *
  *   x_bf16   device, bf16 [T, ldx]; ldx >= d; base 16-byte aligned and ldx % 8 == 0
  *   perm     device, int32 [d], or NULL for P = I
- *   b        16 <= b <= d, b divides d; a power of two, or 2^k' * 28 (k' >= 0; see
- *            perq_hadamard_base) for d = 3584, 7168 or 14336 -- other non-powers of two whose base
- *            matrix the library can build (4t = 12, 76) are UNSUPPORTED so far, the rest INVALID_ARG
+ *   b        16 <= b <= d, b divides d; a power of two, or 2^k' * 4t with 4t = 28 (d = 3584, 7168,
+ *            14336), 4t = 12 (d = 3072, 6144, 12288) or 4t = 76 (d = 2432, 4864, 9728); see
+ *            perq_hadamard_base.  Other widths for these bases, and other bases the library can
+ *            build, are UNSUPPORTED; a b for which it knows no Hadamard matrix is INVALID_ARG
  *   codes    device, uint8 [T, d/2]; element 2k in the low nibble of byte k, 2k+1 in the high
  *   scales   INT4:  device float [T], s_t = ||y_t||_inf / 7 (0 for an all-zero row)
  *            MXFP4: device uint8 [T, d/32], biased exponent E, scale = 2^(E-127),

@@ -20,8 +20,11 @@ bool mfma_supports(const ApplyParams& p);
 // Whether the matrix-core kernel is the faster of the two for this call (measured crossovers).
 bool mfma_preferred(const ApplyParams& p, int out_kind);
 hipError_t launch_mfma(const ApplyParams& p, int out_kind, hipStream_t stream);
-// Block sizes 2^k' * 28 (non-power-of-two rotation).
+// Block sizes 2^k' * 4t, 4t = 12, 28 or 76 (non-power-of-two rotation), one family of kernels per base.
 bool npo2_supports(const ApplyParams& p);
 hipError_t launch_npo2(const ApplyParams& p, int out_kind, hipStream_t stream);
+hipError_t launch_npo2_28(const ApplyParams& p, int out_kind, hipStream_t stream);
+hipError_t launch_npo2_12(const ApplyParams& p, int out_kind, hipStream_t stream);
+hipError_t launch_npo2_76(const ApplyParams& p, int out_kind, hipStream_t stream);
 
 }  // namespace perq

@@ -1,0 +1,590 @@
+// Rotation with a block size that is not a power of two: b = 2^k' * MB, MB = 4t the order of the
+// base matrix (Appendix A.1: 28 for the Llama3-8B width 14336 = 2^9 * 28; 12 and 76 for the Qwen3
+// widths), then the same quantizers as the other kernels.  One translation unit per MB includes
+// this file and instantiates launch_npo2_base<MB>.
+//
+// A block of the (permuted) row is a [2^k'][MB] array Z (position a*MB + r); the rotation is
+// H_{2^k'} Z H_MB / sqrt(b).
+//
+//   1. Z H_MB is a dense product on the MFMA unit (v_mfma_f32_32x32x16_bf16): the data are the A
+//      operand, the +-1 base matrix is B; bf16 x (+-1) is exact, sums are fp32.  The contraction
+//      index also takes those bits of a that cost nothing extra there (see Base<MB>): the matrix
+//      unit is far from busy in this kernel, the vector ALU is what limits it, and every stage
+//      moved into the product is two VALU per element less.  A lane (c, h) then holds one column
+//      of 16 rows per accumulator tile.
+//   2. The rest of the Sylvester factor inside a wave's chunk: the a-bits held in the accumulator
+//      index are in-register butterflies, the bit that separates the half-waves is one swap stage.
+//      Bits above the chunk join different waves' chunks: every wave leaves its chunk in LDS as
+//      fp32 in position order, and after a barrier each thread collects 16 consecutive positions
+//      of every chunk of its row and finishes the remaining one or two stages in registers.
+//   3. In that layout (16 consecutive outputs per thread and chunk) the row statistics, the
+//      rounding and the nibble packing are those of the other kernels.
+//
+// A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1.
+// The raw rows go global -> registers (issued one iteration ahead) -> LDS; each chunk's bf16 data
+// lie at the start of the fp32 area of the same chunk, which only the owning wave reads (P = I)
+// before overwriting it.
+#pragma once
+#include "perq_base.h"
+#include "perq_device.h"
+#include "perq_launch.h"
+
+#include <cmath>
+#include <type_traits>
+
+namespace perq {
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// How one base order maps onto 32x32x16 products.  Rows of A are 32 values of a; a k-step holds 16
+// contraction indices, lane (c, h) supplying 8 h .. 8 h + 7 of them.
+//   kA0  a-values side by side in the 32 output columns (2: column c = 16 (a & 1) + r', and the
+//        two k-steps of a product are a & 1 = 0, 1: bit 0 of a is part of the product)
+//   kKS  k-steps that cover r (kA0 = 1) or a & 1 (kA0 = 2)
+//   kNT  column tiles of 32 that cover r'
+//   kAL  row tiles of one chunk that are contracted against each other (4: two more bits of a in
+//        the product, the k-steps of tile al entering output tile al' with the sign of H_4)
+template <int MB> struct Base;
+template <> struct Base<28> { static constexpr int kA0 = 1, kKS = 2, kNT = 1, kAL = 4; };
+template <> struct Base<12> { static constexpr int kA0 = 2, kKS = 2, kNT = 1, kAL = 4; };
+template <> struct Base<76> { static constexpr int kA0 = 1, kKS = 5, kNT = 3, kAL = 1; };
+
+constexpr int kNpo2Threads = 256;
+constexpr int kNpo2Chunks = 4;                 // chunks per workgroup iteration
+
+template <int MB>
+struct Npo2Geom {
+    uint32_t hrow[16 * (Base<MB>::kA0 == 2 ? 1 : Base<MB>::kKS)][Base<MB>::kNT];   // bit c of word w of row r: entry (r, 32 w + c) is -1
+    int32_t kp;          // k' = log2(b / MB)
+    float norm256;       // fl32(256 / sqrt(b))
+};
+
+// NCH = chunks per row; rows per iteration = 4 / NCH.
+// STG >= 0: the block spans whole chunks: every in-chunk stage and STG stages across chunks,
+// unconditionally.  STG = -1: a smaller block, k' is read at run time (a stage that may or may
+// not run costs a register copy per element on top of its two operations).
+template <int OUT, bool PERM, int MB, int NCH, int STG>
+__global__ void __launch_bounds__(kNpo2Threads, 2)
+npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
+    using B = Base<MB>;
+    constexpr int kA0 = B::kA0, kKS = B::kKS, kNT = B::kNT, kAL = B::kAL;
+    constexpr int kSh = kA0 == 2 ? 1 : 0;                 // a-bit of row bit 0 of a product
+    constexpr int kColMask = 32 / kA0 - 1;                // column -> r' inside a tile
+    constexpr int kTileA = 32 * kA0;                      // a-values per row tile
+    constexpr int kChunkA = kTileA * kAL;                 // a-values per wave chunk: 128, 256, 32
+    constexpr int kChunkBits = (kChunkA == 32 ? 5 : (kChunkA == 128 ? 7 : 8));
+    constexpr int kChunkPos = kChunkA * MB;               // 3584, 3072, 2432
+    constexpr int kGroups = kChunkPos / 16;               // runs of 16 positions per chunk
+    constexpr int kChunkGranules = kChunkPos * 2 / 16;    // 16-byte pieces of raw input per chunk
+    constexpr int kGranules = kNpo2Chunks * kChunkGranules;
+    constexpr int kPre = (kGranules + kNpo2Threads - 1) / kNpo2Threads;
+    constexpr bool kPreExact = kGranules % kNpo2Threads == 0;
+    constexpr int kTiles = kAL * kNT;                     // accumulator tiles per lane
+    constexpr int kVals = 16 * kTiles;
+    constexpr int kRows = kNpo2Chunks / NCH;
+    constexpr int kThreadsPerRow = 64 * NCH;
+    constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
+    constexpr int kRowGranules = NCH * kChunkGranules;
+    static_assert(kGroups % 2 == 0 && kChunkPos % 32 == 0, "a 32-group never straddles two threads' pairs");
+
+    __shared__ __attribute__((aligned(16))) float ex[kNpo2Chunks * kChunkPos];
+    __shared__ float red[2][8];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int c = lane & 31, h = lane >> 5;
+    const int d = p.d;
+    const int kp = STG >= 0 ? kChunkBits + STG : g.kp;
+    const int my_row = wave / NCH;          // row of the iteration this wave works on
+    const int my_chunk = wave % NCH;        // chunk of that row (phase 1)
+    unsigned char* const ex_bytes = reinterpret_cast<unsigned char*>(ex);
+
+    // index r of the base matrix that element e of k-step ks holds in this lane
+    auto r_of = [&](int ks, int e) { return (kA0 == 2 ? 0 : 16 * ks) + 8 * h + e; };
+
+    // ---- B operand: lane (c, h) supplies column c, both signs where tiles are contracted ---------
+    bf16x8_t bpos[kNT][kKS], bneg[kAL > 1 ? kNT : 1][kAL > 1 ? kKS : 1];
+#pragma unroll
+    for (int nt = 0; nt < kNT; ++nt) {
+#pragma unroll
+        for (int ks = 0; ks < kKS; ++ks) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e2 = 0; e2 < 4; ++e2) {
+                uint32_t pair = 0;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    const int e = 2 * e2 + s;
+                    const int r_lo = (kA0 == 2 ? 0 : 16 * ks) + e, r_hi = r_lo + 8;     // h = 0, 1
+                    const uint32_t bits = h ? g.hrow[r_hi][nt] : g.hrow[r_lo][nt];
+                    const int rr = h ? r_hi : r_lo;
+                    const int rc = 32 * nt + (c & kColMask);                             // r'
+                    uint32_t val = (rr < MB && rc < MB) ? (((bits >> (c & kColMask)) & 1u) ? 0xBF80u : 0x3F80u) : 0u;
+                    if constexpr (kA0 == 2) {
+                        // H_2 between the a & 1 of the k-step and the a & 1 of the column; the identity
+                        // when bit 0 of a lies above the block (k' = 0)
+                        const int a_in = ks, a_out = c >> 4;
+                        if (kp > 0) val ^= (a_in & a_out) ? 0x8000u : 0u;
+                        else if (a_in != a_out) val = 0u;
+                        if (val == 0x8000u) val = 0u;
+                    }
+                    pair |= val << (16 * s);
+                }
+                w[e2] = pair;
+            }
+            bpos[nt][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+            if constexpr (kAL > 1)      // (a zero entry stays +0 or becomes -0: either way it contributes nothing)
+                bneg[nt][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0] ^ 0x80008000u, w[1] ^ 0x80008000u,
+                                                                       w[2] ^ 0x80008000u, w[3] ^ 0x80008000u));
+        }
+    }
+
+    // a inside the chunk of row c of tile al, k-step ks
+    auto a_of = [&](int al, int ks) { return kTileA * al + kA0 * c + (kA0 == 2 ? ks : 0); };
+
+    // ---- gather table (P != I): LDS byte address, relative to the row's first chunk, of the
+    //      source channel of every A element of this lane; 16-bit, two per register ---------------
+    constexpr int kTab = kAL * kKS * 4;
+    uint32_t tab[PERM ? kTab : 1];
+    if constexpr (PERM) {
+#pragma unroll
+        for (int al = 0; al < kAL; ++al)
+#pragma unroll
+            for (int ks = 0; ks < kKS; ++ks)
+#pragma unroll
+                for (int e2 = 0; e2 < 4; ++e2) {
+                    uint32_t pair = 0;
+#pragma unroll
+                    for (int s = 0; s < 2; ++s) {
+                        const int r = r_of(ks, 2 * e2 + s);
+                        uint32_t off = 0xFFFFu;
+                        if (r < MB) {
+                            const int pos = my_chunk * kChunkPos + a_of(al, ks) * MB + r;
+                            const int ch = p.perm[pos];
+                            off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 4) + (uint32_t)(ch % kChunkPos) * 2u;
+                        }
+                        pair |= off << (16 * s);
+                    }
+                    tab[(al * kKS + ks) * 4 + e2] = pair;
+                }
+    } else {
+        tab[0] = 0;
+    }
+
+    const int64_t n_units = (p.T + kRows - 1) / kRows;
+    // 16-byte piece i of this thread: which row of the unit, where in the row, where in LDS.
+    // Kept in registers across rows where registers are to spare (P = I), recomputed otherwise.
+    constexpr bool kHoist = !PERM;
+    auto piece_live = [&](int i) { return kPreExact || i + 1 < kPre || tid + kNpo2Threads * i < kGranules; };
+    auto piece_row = [&](int i) { return (tid + kNpo2Threads * i) / kRowGranules; };
+    auto piece_goff = [&](int i) {
+        const int gi = tid + kNpo2Threads * i;
+        return (uint32_t)(gi / kRowGranules) * (uint32_t)(p.ldx * 2) + 16u * (uint32_t)(gi % kRowGranules);
+    };
+    auto piece_loff = [&](int i) {
+        const int gi = tid + kNpo2Threads * i;
+        return (uint32_t)(gi / kChunkGranules) * (uint32_t)(kChunkPos * 4) + 16u * (uint32_t)(gi % kChunkGranules);
+    };
+    uint32_t g_off[kHoist ? kPre : 1], l_off[kHoist ? kPre : 1];
+    if constexpr (kHoist) {
+#pragma unroll
+        for (int i = 0; i < kPre; ++i) {
+            g_off[i] = piece_goff(i);
+            l_off[i] = piece_loff(i);
+        }
+    } else {
+        g_off[0] = 0;
+        l_off[0] = 0;
+    }
+
+    auto issue_loads = [&](uint4 (&pre)[kPre], int64_t unit) {
+        // rows of the unit that exist (uniform); the unit's first row as a scalar base address
+        const int64_t left = p.T - unit * kRows;
+        const int live = unit < n_units ? (left < kRows ? (int)left : kRows) : 0;
+        const unsigned char* base = reinterpret_cast<const unsigned char*>(p.x) + unit * kRows * p.ldx * 2;
+#pragma unroll
+        for (int i = 0; i < kPre; ++i) {
+            pre[i] = make_uint4(0, 0, 0, 0);
+            if (piece_live(i) && piece_row(i) < live) pre[i] = load_stream16(base + (kHoist ? g_off[i] : piece_goff(i)));
+        }
+    };
+    auto stage_rows = [&](const uint4 (&pre)[kPre]) {
+#pragma unroll
+        for (int i = 0; i < kPre; ++i)
+            if (piece_live(i)) *reinterpret_cast<uint4*>(ex_bytes + (kHoist ? l_off[i] : piece_loff(i))) = pre[i];
+    };
+
+    // Raw rows are requested one unit ahead of their use.  (The barriers below wait for LDS only,
+    // so these loads stay in flight across them; a second unit of prefetch was measured: no gain.)
+    const int64_t stride = gridDim.x;
+    uint4 pre[kPre];
+
+    auto body = [&](int64_t unit) {
+        workgroup_barrier_lds();                                   // raw rows of this unit are in LDS
+        // ---- phase 1: base product and the in-wave stages on one chunk -------------------------
+        const unsigned char* stage = ex_bytes + wave * (kChunkPos * 4);
+        const unsigned char* row_stage = ex_bytes + my_row * NCH * (kChunkPos * 4);
+        bf16x8_t afrag[kAL][kKS];
+#pragma unroll
+        for (int al = 0; al < kAL; ++al) {
+#pragma unroll
+            for (int ks = 0; ks < kKS; ++ks) {
+                uint32_t w[4];
+                if constexpr (!PERM) {
+                    // 8 consecutive r of one a: two 8-byte reads (the pitch between lanes is MB * kA0 * 2
+                    // bytes: 56, 48 or 152, so the 32 rows of a read fall into different banks)
+                    const unsigned char* src = stage + (a_of(al, ks) * MB + r_of(ks, 0)) * 2;
+                    const uint2 lo = *reinterpret_cast<const uint2*>(src);
+                    uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
+                    if (r_of(ks, 4) >= MB) hi = make_uint2(0, 0);          // past the end of the base
+                    w[0] = lo.x; w[1] = lo.y; w[2] = hi.x; w[3] = hi.y;
+                } else {
+#pragma unroll
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        const uint32_t pair = tab[(al * kKS + ks) * 4 + e2];
+                        const uint32_t o0 = pair & 0xFFFFu, o1 = pair >> 16;
+                        const uint32_t v0 = o0 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + o0);
+                        const uint32_t v1 = o1 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + o1);
+                        w[e2] = v0 | (v1 << 16);
+                    }
+                }
+                afrag[al][ks] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
+            }
+        }
+
+        // Accumulator tile (al', nt): outputs whose a lies in row tile al', columns 32 nt ..: the sum
+        // over al of H[al][al'] * (Z_al H_MB), H = H_4 when the block spans the whole chunk,
+        // I_2 (x) H_2 when it spans half of it, I_4 below.
+        f32x16_t acc[kTiles];
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t) acc[t] = f32x16_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        // keep: those of the two tile bits that lie above the block (they must agree between input and output)
+        auto products = [&](auto keep_const) {
+            constexpr int keep = decltype(keep_const)::value;
+#pragma unroll
+            for (int al = 0; al < kAL; ++al) {
+#pragma unroll
+                for (int ao = 0; ao < kAL; ++ao) {
+                    if (((al ^ ao) & keep) == 0) {
+                        const bool minus = (__builtin_popcount(al & ao & ~keep) & 1) != 0;
+#pragma unroll
+                        for (int nt = 0; nt < kNT; ++nt)
+#pragma unroll
+                            for (int ks = 0; ks < kKS; ++ks) {
+                                if constexpr (kAL > 1)
+                                    acc[ao * kNT + nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                        afrag[al][ks], minus ? bneg[nt][ks] : bpos[nt][ks], acc[ao * kNT + nt], 0, 0, 0);
+                                else
+                                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[al][ks], bpos[nt][ks], acc[nt], 0, 0, 0);
+                            }
+                    }
+                }
+            }
+        };
+        if (kAL == 1 || STG >= 0) products(std::integral_constant<int, 0>{});
+        else if (kp == kChunkBits - 1) products(std::integral_constant<int, 2>{});
+        else products(std::integral_constant<int, 3>{});
+        float v[kVals];
+#pragma unroll
+        for (int t = 0; t < kTiles; ++t)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) v[t * 16 + j] = acc[t][j];
+        // accumulator j of tile (al', nt) in lane (c, h): row m = 8 (j >> 2) + 4 h + (j & 3) of the
+        // product, a = kTileA al' + kA0 m (+ c >> 4 when kA0 = 2); row bit q is a-bit q + kSh
+        auto pair_stage = [&](int bit_in_index) {
+#pragma unroll
+            for (int i = 0; i < kVals; ++i) {
+                if ((i & bit_in_index) == 0) {
+                    const float s = v[i], t = v[i | bit_in_index];
+                    v[i] = s + t;
+                    v[i | bit_in_index] = s - t;
+                }
+            }
+        };
+        if (STG >= 0 || kp > kSh + 0) pair_stage(1);       // row bit 0
+        if (STG >= 0 || kp > kSh + 1) pair_stage(2);       // row bit 1
+        if (STG >= 0 || kp > kSh + 3) pair_stage(4);       // row bit 3
+        if (STG >= 0 || kp > kSh + 4) pair_stage(8);       // row bit 4
+        // Row bit 2 separates the half-waves.  One half-wave swap per register pair (i, i+1) hands
+        // the low lanes both halves of register i and the high lanes both halves of register i+1;
+        // sum and difference stay there.  Afterwards the half-wave tells row bit 0 and the slot in
+        // the pair row bit 2.  Without this stage the same swap only re-sorts the values, so that
+        // the addresses below hold either way.
+        const bool stage2 = STG >= 0 || kp > kSh + 2;
+#pragma unroll
+        for (int i = 0; i < kVals; i += 2) {
+            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[i + 1]), false, false);
+            const float lo = __uint_as_float(sw[0]), hi = __uint_as_float(sw[1]);
+            v[i] = stage2 ? lo + hi : lo;
+            v[i + 1] = stage2 ? lo - hi : hi;
+        }
+        if constexpr (PERM) workgroup_barrier_lds();   // every wave has gathered its operands: the chunks may be overwritten
+        {
+            const int rl = c & kColMask;                // r' inside a column tile
+            float* dst = ex + wave * kChunkPos + (kA0 * h + (kA0 == 2 ? (c >> 4) : 0)) * MB + rl;
+#pragma unroll
+            for (int ao = 0; ao < kAL; ++ao)
+#pragma unroll
+                for (int nt = 0; nt < kNT; ++nt) {
+                    if (32 * nt + rl < MB) {
+#pragma unroll
+                        for (int j = 0; j < 16; ++j)
+                            dst[(kTileA * ao + kA0 * (8 * (j >> 2) + 4 * (j & 1) + (j & 2))) * MB + 32 * nt] =
+                                v[(ao * kNT + nt) * 16 + j];
+                    }
+                }
+        }
+        workgroup_barrier_lds();                                   // all chunks of all rows are in LDS
+
+        // ---- phase 2: 16 consecutive positions of every chunk of the row per thread ------------
+        const int t_row = tid - my_row * kThreadsPerRow;
+        const int64_t row = unit * kRows + my_row;
+        const bool row_live = row < p.T;
+        float f[kIts][NCH][16];
+#pragma unroll
+        for (int it = 0; it < kIts; ++it) {
+            const int gI = t_row + kThreadsPerRow * it;
+            const bool live = gI < kGroups;
+#pragma unroll
+            for (int ch = 0; ch < NCH; ++ch) {
+                const float4* src = reinterpret_cast<const float4*>(ex + (my_row * NCH + ch) * kChunkPos + 16 * (live ? gI : 0));
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 t4 = src[q];
+                    f[it][ch][4 * q] = t4.x; f[it][ch][4 * q + 1] = t4.y;
+                    f[it][ch][4 * q + 2] = t4.z; f[it][ch][4 * q + 3] = t4.w;
+                }
+            }
+            if constexpr (NCH >= 2) {
+                if (STG >= 1) {
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ch += 2)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const float s = f[it][ch][e], t = f[it][ch + 1][e];
+                            f[it][ch][e] = s + t;
+                            f[it][ch + 1][e] = s - t;
+                        }
+                }
+            }
+            if constexpr (NCH >= 4) {
+                if (STG >= 2) {
+#pragma unroll
+                    for (int ch = 0; ch < 2; ++ch)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            const float s = f[it][ch][e], t = f[it][ch + 2][e];
+                            f[it][ch][e] = s + t;
+                            f[it][ch + 2][e] = s - t;
+                        }
+                }
+            }
+        }
+
+        // ---- row statistics (per-token formats) -------------------------------------------------
+        constexpr bool kTokenStat = OUT == OUT_INT4 || OUT == OUT_INT4_ASYM || OUT == OUT_FP4_TOKEN;
+        constexpr int kRed = OUT == OUT_INT4_ASYM ? 2 : 1;
+        float m[2] = {0.0f, 0.0f};
+        if constexpr (kTokenStat) {
+            if constexpr (OUT == OUT_INT4_ASYM) { m[0] = -3.0e38f; m[1] = -3.0e38f; }
+#pragma unroll
+            for (int it = 0; it < kIts; ++it) {
+                if (t_row + kThreadsPerRow * it < kGroups) {
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) {
+                            if constexpr (OUT == OUT_INT4_ASYM) {
+                                m[0] = fmaxf(m[0], f[it][ch][e]);
+                                m[1] = fmaxf(m[1], -f[it][ch][e]);
+                            } else {
+                                m[0] = fmaxf(m[0], fabsf(f[it][ch][e]));
+                            }
+                        }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kRed; ++j) {
+                m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
+                m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
+                m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
+                m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
+                m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
+                m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+            }
+            if (lane == 0) {
+#pragma unroll
+                for (int j = 0; j < kRed; ++j) red[j][wave] = m[j];
+            }
+        }
+        workgroup_barrier_lds();            // statistics visible; nobody reads the fp32 chunks any more
+        stage_rows(pre);            // the next unit's raw rows
+        if constexpr (!PERM) issue_loads(pre, unit + 2 * stride);
+        if constexpr (kTokenStat) {
+#pragma unroll
+            for (int j = 0; j < kRed; ++j) {
+                float t = red[j][my_row * NCH];
+#pragma unroll
+                for (int w = 1; w < NCH; ++w) t = fmaxf(t, red[j][my_row * NCH + w]);
+                m[j] = t;
+            }
+        }
+
+        // ---- quantize, pack, store ---------------------------------------------------------------
+        float inv = 0.0f;
+        Int4Asym qa = {0.0f, 0, false};
+        if constexpr (OUT == OUT_INT4) inv = m[0] > 0.0f ? 7.0f / m[0] : 0.0f;
+        if constexpr (OUT == OUT_FP4_TOKEN) inv = m[0] > 0.0f ? 6.0f / m[0] : 0.0f;
+        if constexpr (OUT == OUT_INT4_ASYM) qa = int4_asym_row(-m[1], m[0]);
+#pragma unroll
+        for (int it = 0; it < kIts; ++it) {
+            const int gI = t_row + kThreadsPerRow * it;
+            if (gI < kGroups && row_live) {
+#pragma unroll
+                for (int ch = 0; ch < NCH; ++ch) {
+                    const int pos = ch * kChunkPos + 16 * gI;
+                    float* val = f[it][ch];
+                    if constexpr (OUT == OUT_F32) {
+                        float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + pos);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            yo[q] = make_float4(val[4 * q] * p.rsqrt_b, val[4 * q + 1] * p.rsqrt_b,
+                                                val[4 * q + 2] * p.rsqrt_b, val[4 * q + 3] * p.rsqrt_b);
+                    } else {
+                        uint32_t lo, hi;
+                        if constexpr (OUT == OUT_INT4) {
+                            lo = int4_pack8(val, inv);
+                            hi = int4_pack8(val + 8, inv);
+                        } else if constexpr (OUT == OUT_FP4_TOKEN) {
+                            lo = fp4_pack8(val, inv);
+                            hi = fp4_pack8(val + 8, inv);
+                        } else if constexpr (OUT == OUT_INT4_ASYM) {
+                            if (!qa.clamp) {
+                                const uint32_t zn = (uint32_t)qa.z * 0x11111111u;
+                                lo = int4a_pack8(val, qa.inv, zn);
+                                hi = int4a_pack8(val + 8, qa.inv, zn);
+                            } else {
+                                lo = int4a_pack8_clamped(val, qa.inv, qa.z);
+                                hi = int4a_pack8_clamped(val + 8, qa.inv, qa.z);
+                            }
+                        } else {
+                            // MXFP4: values normalised by 256 / sqrt(b), so the exponent field handed to
+                            // the convert is never zero; the other half of the 32-group is the
+                            // neighbouring thread's run
+                            float gm = 0.0f;
+#pragma unroll
+                            for (int e = 0; e < 16; ++e) {
+                                val[e] *= g.norm256;
+                                gm = fmaxf(gm, fabsf(val[e]));
+                            }
+                            gm = fmaxf(gm, lane_xor<1>(gm));
+                            const int E = mx_shared_exponent(gm, 8);
+                            const float scale = __uint_as_float((uint32_t)(E + 8) << 23);
+                            lo = mxfp4_pack8(val, scale);
+                            hi = mxfp4_pack8(val + 8, scale);
+                            if ((gI & 1) == 0)
+                                static_cast<uint8_t*>(p.scales)[row * (int64_t)(d >> 5) + (pos >> 5)] = (uint8_t)E;
+                        }
+                        *reinterpret_cast<uint2*>(p.codes + row * (int64_t)(d >> 1) + (pos >> 1)) = make_uint2(lo, hi);
+                    }
+                }
+            }
+        }
+        if (row_live && t_row == 0) {
+            if constexpr (OUT == OUT_INT4)
+                static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_7sqrt_b);
+            if constexpr (OUT == OUT_FP4_TOKEN)
+                static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_6sqrt_b);
+            if constexpr (OUT == OUT_INT4_ASYM)
+                static_cast<float2*>(p.scales)[row] =
+                    make_float2((float)((double)(m[0] + m[1]) * p.inv_15sqrt_b), (float)qa.z);
+        }
+        // (with a gather table held, the registers are free again only here)
+        if constexpr (PERM) issue_loads(pre, unit + 2 * stride);
+    };
+
+    int64_t unit = blockIdx.x;
+    issue_loads(pre, unit);
+    stage_rows(pre);
+    issue_loads(pre, unit + stride);
+    for (; unit < n_units; unit += stride) body(unit);
+}
+
+template <int MB>
+constexpr int npo2_chunk_pos() { return 32 * Base<MB>::kA0 * Base<MB>::kAL * MB; }
+template <int MB>
+constexpr int npo2_chunk_bits() { return Base<MB>::kAL == 1 ? 5 : (Base<MB>::kA0 == 1 ? 7 : 8); }
+
+template <int OUT, bool PERM, int MB, int NCH>
+hipError_t launch_stg(const ApplyParams& p, const Npo2Geom<MB>& g, dim3 grid, hipStream_t stream) {
+    const int stg = g.kp - npo2_chunk_bits<MB>();
+    const dim3 block(kNpo2Threads);
+    if (stg < 0) {
+        hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, -1>), grid, block, 0, stream, p, g);
+    } else if (stg == 0) {
+        hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 0>), grid, block, 0, stream, p, g);
+    } else if constexpr (NCH >= 2) {
+        if (stg == 1) {
+            hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 1>), grid, block, 0, stream, p, g);
+        } else if constexpr (NCH >= 4) {
+            hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 2>), grid, block, 0, stream, p, g);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+template <int OUT, bool PERM, int MB>
+hipError_t launch_nch(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, dim3 grid, hipStream_t stream) {
+    switch (nch) {
+        case 1: return launch_stg<OUT, PERM, MB, 1>(p, g, grid, stream);
+        case 2: return launch_stg<OUT, PERM, MB, 2>(p, g, grid, stream);
+        default: return launch_stg<OUT, PERM, MB, 4>(p, g, grid, stream);
+    }
+}
+
+template <int OUT, int MB>
+hipError_t launch_perm(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, dim3 grid, hipStream_t stream) {
+    return p.perm != nullptr ? launch_nch<OUT, true, MB>(p, g, nch, grid, stream)
+                             : launch_nch<OUT, false, MB>(p, g, nch, grid, stream);
+}
+
+// The caller has checked npo2_supports(p) and that b / MB is a power of two.
+template <int MB>
+hipError_t launch_npo2_base_impl(const ApplyParams& p, int out_kind, hipStream_t stream) {
+    Npo2Geom<MB> g;
+    constexpr int kRowsPad = sizeof(g.hrow) / sizeof(g.hrow[0]);
+    const int kind = hadamard_base_kind(MB);
+    for (int r = 0; r < kRowsPad; ++r)
+        for (int w = 0; w < Base<MB>::kNT; ++w) {
+            uint32_t bits = 0;
+            if (r < MB)
+                for (int c = 0; c < 32 && 32 * w + c < MB; ++c)
+                    if (hadamard_base_entry(MB, kind, r, 32 * w + c) < 0) bits |= 1u << c;
+            g.hrow[r][w] = bits;
+        }
+    g.kp = 0;
+    while ((MB << g.kp) < p.b) ++g.kp;
+    g.norm256 = (float)(256.0 / std::sqrt((double)p.b));
+    const int nch = p.d / npo2_chunk_pos<MB>();
+    const int64_t rows_per_unit = kNpo2Chunks / nch;
+    const int64_t n_units = (p.T + rows_per_unit - 1) / rows_per_unit;
+    const int64_t max_grid = 2 * (int64_t)launch_info().num_cus;
+    const dim3 grid((unsigned)(n_units < max_grid ? n_units : max_grid));
+    switch (out_kind) {
+        case OUT_INT4: return launch_perm<OUT_INT4, MB>(p, g, nch, grid, stream);
+        case OUT_MXFP4: return launch_perm<OUT_MXFP4, MB>(p, g, nch, grid, stream);
+        case OUT_INT4_ASYM: return launch_perm<OUT_INT4_ASYM, MB>(p, g, nch, grid, stream);
+        case OUT_FP4_TOKEN: return launch_perm<OUT_FP4_TOKEN, MB>(p, g, nch, grid, stream);
+        case OUT_F32: return launch_perm<OUT_F32, MB>(p, g, nch, grid, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+}  // namespace perq

@@ -524,10 +524,16 @@ def _heavy_rows(T, d, seed):
 
 
 @pytest.mark.parametrize("d,bs", [(3584, [28, 112, 896, 3584]), (7168, [56, 1792, 7168]),
-                                  (14336, [28, 224, 3584, 7168, 14336])])
+                                  (14336, [28, 224, 3584, 7168, 14336]),
+                                  # base 12 (chunks of 3072): k' = 1 .. 10
+                                  (3072, [24, 48, 768, 1536, 3072]), (6144, [96, 3072, 6144]),
+                                  (12288, [24, 192, 1536, 3072, 6144, 12288]),
+                                  # base 76 (chunks of 2432): k' = 0 .. 7
+                                  (2432, [76, 152, 608, 1216, 2432]), (4864, [304, 2432, 4864]),
+                                  (9728, [76, 1216, 2432, 4864, 9728])])
 @pytest.mark.parametrize("with_perm", [False, True])
 def test_nonpo2_rotation_against_oracle(d, bs, with_perm):
-    T = 13 if d == 14336 else 21                       # ragged against 1, 2 and 4 rows per workgroup pass
+    T = 13 if d >= 9728 else 21                        # ragged against 1, 2 and 4 rows per workgroup pass
     x = _heavy_rows(T, d, 900 + d)
     perm = np.random.default_rng(d).permutation(d).astype(np.int32) if with_perm else None
     for b in bs:
@@ -573,10 +579,15 @@ def test_nonpo2_argument_checks():
     with pytest.raises(binding.PerqError) as ei:
         binding.perq_permute_rotate_quant(x, None, 14, "int4")
     assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
-    # known base, width the kernel does not cover
-    x12 = torch.zeros((4, 3072), dtype=torch.bfloat16, device="cuda")
+    # known base, width the kernels do not cover (1, 2 or 4 chunks of 3072 for the base of 12)
+    x12 = torch.zeros((4, 1536), dtype=torch.bfloat16, device="cuda")
     with pytest.raises(binding.PerqError) as ei:
-        binding.perq_permute_rotate_quant(x12, None, 3072, "int4")
+        binding.perq_permute_rotate_quant(x12, None, 1536, "int4")
+    assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED
+    # a base the library can build (20 = 19 + 1) but has no kernel for
+    x20 = torch.zeros((4, 20 * 64), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(binding.PerqError) as ei:
+        binding.perq_permute_rotate_quant(x20, None, 20 * 64, "int4")
     assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED
     # order 4 * 9 = 36 = 2 * (17 + 1) exists by the second construction, 4 * 23 = 92 by neither
     x92 = torch.zeros((4, 92 * 8), dtype=torch.bfloat16, device="cuda")
