@@ -32,6 +32,9 @@ WORKLOADS = {
     # full-vector rotation at the Llama3-8B width, 14336 = 2^9 * 28 (Appendix A.1); a permutation
     # does not change the bound of one block that spans the row, so P = I
     "llama8b_d14336_full_int4": ("llama8b_d14336", 14336, "int4", False),
+    # the same at the Qwen3 8B and 4B widths, 12288 = 2^10 * 12 and 9728 = 2^7 * 76
+    "qwen3_d12288_full_int4": ("qwen3_d12288", 12288, "int4", False),
+    "qwen3_d9728_full_int4": ("qwen3_d9728", 9728, "int4", False),
     "llama1b_down_b32_int4_perm": ("llama1b_down", 32, "int4", True),
     "block_vs_full_b32_mxfp4": ("block_vs_full", 32, "mxfp4", False),
     "block_vs_full_b2048_mxfp4": ("block_vs_full", 2048, "mxfp4", False),

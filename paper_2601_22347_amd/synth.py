@@ -148,6 +148,17 @@ def llama8b(d: int) -> Workload:
     raise ValueError("d must be 4096 or 14336")
 
 
+def qwen3(d: int) -> Workload:
+    """T=32768, d in {9728, 12288} (Qwen3 4B / 8B down-projection inputs, widths 2^7*76 and 2^10*12),
+    Student-t(3), 1% channels x50; INT4; for the full-vector rotation of non-power-of-two width."""
+    if d not in (9728, 12288):
+        raise ValueError("d must be 9728 or 12288")
+    ch, fac = _channels(d, d // 100, 154 if d == 9728 else 155, 50.0, 50.0)
+    return Workload(f"qwen3_d{d}", 32768, d, "student_t", nu=3.0, data_seed=150 if d == 9728 else 151,
+                    calib_seed=152 if d == 9728 else 153, calib_tokens=2048, outlier_channels=ch,
+                    outlier_factors=fac, block_sizes=(d,), fmt="int4")
+
+
 def calib_apply() -> Workload:
     """Calibrate on 4096 tokens of d=8192, apply to T=65536; Student-t(3) + 1% channels xU[20,100]."""
     ch, fac = _channels(8192, 82, 142, 20.0, 100.0)
@@ -158,4 +169,4 @@ def calib_apply() -> Workload:
 
 ALL = {"tiny": tiny, "llama1b_down": llama1b_down, "block_vs_full": block_vs_full,
        "llama8b_d4096": lambda: llama8b(4096), "llama8b_d14336": lambda: llama8b(14336),
-       "calib_apply": calib_apply}
+       "calib_apply": calib_apply, "qwen3_d9728": lambda: qwen3(9728), "qwen3_d12288": lambda: qwen3(12288)}
