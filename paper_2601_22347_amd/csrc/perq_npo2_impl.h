@@ -22,8 +22,8 @@
 //
 // A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1.
 // The raw rows go global -> registers (issued one iteration ahead) -> LDS; each chunk's bf16 data
-// lie at the start of the fp32 area of the same chunk, which only the owning wave reads (P = I)
-// before overwriting it.
+// lie at the start of the fp32 area of the same chunk; the owning wave puts them there and, without
+// a gather, is the only one to read them before it overwrites them: two barriers per row.
 #pragma once
 #include "perq_base.h"
 #include "perq_device.h"
@@ -78,15 +78,13 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kChunkPos = kChunkA * MB;               // 3584, 3072, 2432
     constexpr int kGroups = kChunkPos / 16;               // runs of 16 positions per chunk
     constexpr int kChunkGranules = kChunkPos * 2 / 16;    // 16-byte pieces of raw input per chunk
-    constexpr int kGranules = kNpo2Chunks * kChunkGranules;
-    constexpr int kPre = (kGranules + kNpo2Threads - 1) / kNpo2Threads;
-    constexpr bool kPreExact = kGranules % kNpo2Threads == 0;
+    constexpr int kPre = (kChunkGranules + 63) / 64;      // pieces per lane: every wave stages its own chunk
+    constexpr bool kPreExact = kChunkGranules % 64 == 0;
     constexpr int kTiles = kAL * kNT;                     // accumulator tiles per lane
     constexpr int kVals = 16 * kTiles;
     constexpr int kRows = kNpo2Chunks / NCH;
     constexpr int kThreadsPerRow = 64 * NCH;
     constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
-    constexpr int kRowGranules = NCH * kChunkGranules;
     static_assert(kGroups % 2 == 0 && kChunkPos % 32 == 0, "a 32-group never straddles two threads' pairs");
 
     __shared__ __attribute__((aligned(16))) float ex[kNpo2Chunks * kChunkPos];
@@ -174,46 +172,26 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     }
 
     const int64_t n_units = (p.T + kRows - 1) / kRows;
-    // 16-byte piece i of this thread: which row of the unit, where in the row, where in LDS.
-    // Kept in registers across rows where registers are to spare (P = I), recomputed otherwise.
-    constexpr bool kHoist = !PERM;
-    auto piece_live = [&](int i) { return kPreExact || i + 1 < kPre || tid + kNpo2Threads * i < kGranules; };
-    auto piece_row = [&](int i) { return (tid + kNpo2Threads * i) / kRowGranules; };
-    auto piece_goff = [&](int i) {
-        const int gi = tid + kNpo2Threads * i;
-        return (uint32_t)(gi / kRowGranules) * (uint32_t)(p.ldx * 2) + 16u * (uint32_t)(gi % kRowGranules);
-    };
-    auto piece_loff = [&](int i) {
-        const int gi = tid + kNpo2Threads * i;
-        return (uint32_t)(gi / kChunkGranules) * (uint32_t)(kChunkPos * 4) + 16u * (uint32_t)(gi % kChunkGranules);
-    };
-    uint32_t g_off[kHoist ? kPre : 1], l_off[kHoist ? kPre : 1];
-    if constexpr (kHoist) {
-#pragma unroll
-        for (int i = 0; i < kPre; ++i) {
-            g_off[i] = piece_goff(i);
-            l_off[i] = piece_loff(i);
-        }
-    } else {
-        g_off[0] = 0;
-        l_off[0] = 0;
-    }
+    // Every wave loads and stages the raw data of its own chunk (16-byte piece lane + 64 i of the
+    // chunk's 2 * kChunkPos bytes), so without a gather nobody else's data are needed in phase 1.
+    auto piece_live = [&](int i) { return kPreExact || i + 1 < kPre || lane + 64 * i < kChunkGranules; };
+    const uint32_t g_base = (uint32_t)my_row * (uint32_t)(p.ldx * 2) + (uint32_t)my_chunk * (uint32_t)(kChunkPos * 2) + 16u * (uint32_t)lane;
+    unsigned char* const l_base = ex_bytes + wave * (kChunkPos * 4) + 16 * lane;
 
     auto issue_loads = [&](uint4 (&pre)[kPre], int64_t unit) {
-        // rows of the unit that exist (uniform); the unit's first row as a scalar base address
-        const int64_t left = p.T - unit * kRows;
-        const int live = unit < n_units ? (left < kRows ? (int)left : kRows) : 0;
-        const unsigned char* base = reinterpret_cast<const unsigned char*>(p.x) + unit * kRows * p.ldx * 2;
+        // the unit's first row as a scalar base address; rows past the end are read as zeros
+        const bool live = unit < n_units && unit * kRows + my_row < p.T;
+        const unsigned char* base = reinterpret_cast<const unsigned char*>(p.x) + unit * kRows * p.ldx * 2 + g_base;
 #pragma unroll
         for (int i = 0; i < kPre; ++i) {
             pre[i] = make_uint4(0, 0, 0, 0);
-            if (piece_live(i) && piece_row(i) < live) pre[i] = load_stream16(base + (kHoist ? g_off[i] : piece_goff(i)));
+            if (live && piece_live(i)) pre[i] = load_stream16(base + 1024 * i);
         }
     };
     auto stage_rows = [&](const uint4 (&pre)[kPre]) {
 #pragma unroll
         for (int i = 0; i < kPre; ++i)
-            if (piece_live(i)) *reinterpret_cast<uint4*>(ex_bytes + (kHoist ? l_off[i] : piece_loff(i))) = pre[i];
+            if (piece_live(i)) *reinterpret_cast<uint4*>(l_base + 1024 * i) = pre[i];
     };
 
     // Raw rows are requested one unit ahead of their use.  (The barriers below wait for LDS only,
@@ -222,7 +200,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     uint4 pre[kPre];
 
     auto body = [&](int64_t unit) {
-        workgroup_barrier_lds();                                   // raw rows of this unit are in LDS
+        if constexpr (PERM) workgroup_barrier_lds();               // the gather reads other waves' chunks too
         // ---- phase 1: base product and the in-wave stages on one chunk -------------------------
         const unsigned char* stage = ex_bytes + wave * (kChunkPos * 4);
         const unsigned char* row_stage = ex_bytes + my_row * NCH * (kChunkPos * 4);
