@@ -18,8 +18,10 @@ CASES = [
     ("llama1b_down", (16, 32, 64, 128), 2048),
     ("block_vs_full", (32, 2048), 640),
     ("llama8b_d4096", (128, 4096), 192),
-    ("llama8b_d14336", (128, 2048), 96),
+    ("llama8b_d14336", (128, 2048, 14336), 96),       # 14336 = 2^9 * 28: the full-vector rotation
     ("calib_apply", (16, 32), 256),
+    ("qwen3_d12288", (12288, 3072), 96),              # 2^10 * 12
+    ("qwen3_d9728", (9728,), 96),                     # 2^7 * 76
 ]
 
 
