@@ -220,8 +220,20 @@ def main() -> int:
         for s in range(0, n2, 2048):
             orc.perq_apply(x_bits[s:min(n2, s + 2048)], perm_np, b, fmt)
         cpu_s = time.perf_counter() - c0
+        pow2 = b & (b - 1) == 0
+        how = "explicit H_b product" if pow2 else "explicit product, one Kronecker factor of H_b at a time"
         cpu = {"value": n2 / cpu_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-               "sample": f"first {n2} tokens of the workload, fp64 NumPy, explicit H_b product, {cpu_s:.1f} s"}
+               "sample": f"first {n2} tokens of the workload, fp64 NumPy, {how}, {cpu_s:.1f} s"}
+        if pow2 and b >= 2048:
+            # the oracle's second evaluation (fp64 radix-2 butterflies) on the same rows, for scale:
+            # the explicit product costs O(d b) per token, this one O(d log b)
+            n3 = min(n2, 4096)
+            c0 = time.perf_counter()
+            for s in range(0, n3, 2048):
+                orc.perq_apply(x_bits[s:min(n3, s + 2048)], perm_np, b, fmt, rotate=orc.fwht_f64)
+            f_s = time.perf_counter() - c0
+            cpu["butterfly_variant"] = {"value": n3 / f_s, "unit": "tokens/s",
+                                        "sample": f"first {n3} tokens, fp64 radix-2 butterflies, {f_s:.1f} s"}
 
     line = {
         "metric": "fused permute+block-Hadamard+quant tokens/s",
