@@ -599,3 +599,25 @@ def test_nonpo2_argument_checks():
         with pytest.raises(binding.PerqError) as ei:
             binding.perq_permute_rotate_quant(x, None, 14336, "int4", algo=algo)
         assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED
+
+
+def test_nonpo2_row_stride_single_row_empty_and_repeat():
+    torch = _torch()
+    for d, b in [(14336, 14336), (6144, 1536), (9728, 9728)]:
+        x = _heavy_rows(9, d, 31 + d)
+        # rows at a pitch larger than d (a view into a wider buffer)
+        assert_parity(x, None, b, "int4", "auto", ldx=d + 64, label="nonpo2/stride")
+        perm = np.random.default_rng(5).permutation(d).astype(np.int32)
+        assert_parity(x, perm, b, "mxfp4", "auto", ldx=d + 8, label="nonpo2/stride+perm")
+        # one row (three of a pass's four chunk slots stay empty when a row has one or two chunks)
+        assert_parity(x[:1], None, b, "int4_asym", "auto", label="nonpo2/one row")
+        # no rows: nothing is read or written
+        xe = torch.empty((0, d), dtype=torch.bfloat16, device="cuda")
+        codes, scales = binding.perq_permute_rotate_quant(xe, None, b, "int4")
+        assert codes.shape[0] == 0 and scales.shape[0] == 0
+        # the same call twice gives the same bytes
+        xd = binding.bits_to_device(x)
+        c1, s1 = binding.perq_permute_rotate_quant(xd, None, b, "fp4_token")
+        c2, s2 = binding.perq_permute_rotate_quant(xd, None, b, "fp4_token")
+        torch.cuda.synchronize()
+        assert torch.equal(c1, c2) and torch.equal(s1, s2)
