@@ -621,3 +621,41 @@ def test_nonpo2_row_stride_single_row_empty_and_repeat():
         c2, s2 = binding.perq_permute_rotate_quant(xd, None, b, "fp4_token")
         torch.cuda.synchronize()
         assert torch.equal(c1, c2) and torch.equal(s1, s2)
+
+
+# ---- a seeded sweep over shapes, block sizes, formats, permutations and row pitches ---------------
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    widths = [64, 256, 320, 512, 1536, 2048, 2432, 3072, 3584, 4096, 4864, 5120, 6144, 7168, 8192, 9728, 12288,
+              14336, 16384]
+    cases = []
+    while len(cases) < n:
+        d = int(rng.choice(widths))
+        # block sizes the library takes for this width: powers of two, and 2^k' * {12, 28, 76} on the
+        # widths of the three bases
+        bs = [b for b in (16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384) if b <= d and d % b == 0]
+        for base, chunk in ((28, 3584), (12, 3072), (76, 2432)):
+            if d in (chunk, 2 * chunk, 4 * chunk):
+                bs += [base << k for k in range(12) if (base << k) >= 16 and (base << k) <= d and d % (base << k) == 0]
+        if d % 32 != 0 or not bs:
+            continue
+        b = int(rng.choice(bs))
+        T = int(rng.integers(1, 48))
+        fmt = str(rng.choice(["int4", "mxfp4", "int4_asym", "fp4_token"]))
+        with_perm = bool(rng.integers(0, 2))
+        pad = int(rng.choice([0, 0, 8, 64, 1000]))
+        cases.append((T, d, b, fmt, with_perm, pad, int(rng.integers(1 << 30))))
+    return cases
+
+
+@pytest.mark.parametrize("T,d,b,fmt,with_perm,pad,seed", _random_cases(72, 20260122))
+def test_seeded_sweep(T, d, b, fmt, with_perm, pad, seed):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_t(3, size=(T, d)).clip(-1e4, 1e4) * np.exp(rng.uniform(-4, 4, size=(T, 1)))
+    x[:, rng.choice(d, size=max(1, d // 64), replace=False)] *= 40.0
+    if T > 2:
+        x[1] = 0.0                                   # an all-zero row
+    bits = synth.f64_to_bf16_bits(x)
+    perm = rng.permutation(d).astype(np.int32) if with_perm else None
+    rotate = orc.fwht_f64 if (b > 4096 and b & (b - 1) == 0) else None
+    assert_parity(bits, perm, b, fmt, "auto", rotate=rotate, ldx=(d + pad) if pad else None, label="sweep")
