@@ -26,5 +26,8 @@ hipError_t launch_npo2(const ApplyParams& p, int out_kind, hipStream_t stream);
 hipError_t launch_npo2_28(const ApplyParams& p, int out_kind, hipStream_t stream);
 hipError_t launch_npo2_12(const ApplyParams& p, int out_kind, hipStream_t stream);
 hipError_t launch_npo2_76(const ApplyParams& p, int out_kind, hipStream_t stream);
+// The same chunked kernel with H_32 as base: power-of-two b > 4096 on d = 8192, 16384.
+bool chunked_pow2_supports(const ApplyParams& p);
+hipError_t launch_npo2_32(const ApplyParams& p, int out_kind, hipStream_t stream);
 
 }  // namespace perq

@@ -50,6 +50,9 @@ template <int MB> struct Base;
 template <> struct Base<28> { static constexpr int kA0 = 1, kKS = 2, kNT = 1, kAL = 4; };
 template <> struct Base<12> { static constexpr int kA0 = 2, kKS = 2, kNT = 1, kAL = 4; };
 template <> struct Base<76> { static constexpr int kA0 = 1, kKS = 5, kNT = 3, kAL = 1; };
+// Sylvester's H_32 as the base: power-of-two blocks above what the 4096-wide tiles of the other
+// matrix-core kernel hold (b = 8192, 16384 on d = 8192, 16384) take the same path.
+template <> struct Base<32> { static constexpr int kA0 = 1, kKS = 2, kNT = 1, kAL = 4; };
 
 constexpr int kNpo2Threads = 256;
 constexpr int kNpo2Chunks = 4;                 // chunks per workgroup iteration
@@ -86,6 +89,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kThreadsPerRow = 64 * NCH;
     constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
     static_assert(kGroups % 2 == 0 && kChunkPos % 32 == 0, "a 32-group never straddles two threads' pairs");
+    // MB = 32: a row of the A operand is 64 bytes, so rows four apart would share their banks.  The
+    // 16-byte piece q of row a is kept at piece q ^ ((a >> 2) & 3) of the row instead (raw data only).
+    constexpr bool kSwz = MB == 32;
 
     __shared__ __attribute__((aligned(16))) float ex[kNpo2Chunks * kChunkPos];
     __shared__ float red[2][8];
@@ -161,7 +167,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                         if (r < MB) {
                             const int pos = my_chunk * kChunkPos + a_of(al, ks) * MB + r;
                             const int ch = p.perm[pos];
-                            off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 4) + (uint32_t)(ch % kChunkPos) * 2u;
+                            const uint32_t cl = (uint32_t)(ch % kChunkPos);
+                            off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 4) +
+                                  (kSwz ? ((cl >> 5) * 4u + (((cl >> 3) & 3u) ^ ((cl >> 7) & 3u))) * 16u + (cl & 7u) * 2u : cl * 2u);
                         }
                         pair |= off << (16 * s);
                     }
@@ -176,7 +184,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     // chunk's 2 * kChunkPos bytes), so without a gather nobody else's data are needed in phase 1.
     auto piece_live = [&](int i) { return kPreExact || i + 1 < kPre || lane + 64 * i < kChunkGranules; };
     const uint32_t g_base = (uint32_t)my_row * (uint32_t)(p.ldx * 2) + (uint32_t)my_chunk * (uint32_t)(kChunkPos * 2) + 16u * (uint32_t)lane;
-    unsigned char* const l_base = ex_bytes + wave * (kChunkPos * 4) + 16 * lane;
+    // (swizzled: piece lane + 64 i belongs to row (lane >> 2) + 16 i, whose bits 2, 3 are those of lane >> 4)
+    unsigned char* const l_base = ex_bytes + wave * (kChunkPos * 4) +
+                                  16 * (kSwz ? ((lane & ~3) | ((lane & 3) ^ ((lane >> 4) & 3))) : lane);
 
     auto issue_loads = [&](uint4 (&pre)[kPre], int64_t unit) {
         // the unit's first row as a scalar base address; rows past the end are read as zeros
@@ -213,7 +223,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                 if constexpr (!PERM) {
                     // 8 consecutive r of one a: two 8-byte reads (the pitch between lanes is MB * kA0 * 2
                     // bytes: 56, 48 or 152, so the 32 rows of a read fall into different banks)
-                    const unsigned char* src = stage + (a_of(al, ks) * MB + r_of(ks, 0)) * 2;
+                    const unsigned char* src =
+                        kSwz ? stage + a_of(al, ks) * 64 + (((2 * ks + h) ^ ((c >> 2) & 3)) * 16)
+                             : stage + (a_of(al, ks) * MB + r_of(ks, 0)) * 2;
                     const uint2 lo = *reinterpret_cast<const uint2*>(src);
                     uint2 hi = *reinterpret_cast<const uint2*>(src + 8);
                     if (r_of(ks, 4) >= MB) hi = make_uint2(0, 0);          // past the end of the base
@@ -495,6 +507,13 @@ constexpr int npo2_chunk_pos() { return 32 * Base<MB>::kA0 * Base<MB>::kAL * MB;
 template <int MB>
 constexpr int npo2_chunk_bits() { return Base<MB>::kAL == 1 ? 5 : (Base<MB>::kA0 == 1 ? 7 : 8); }
 
+// Entry (r, c) of the base: Sylvester's matrix for 32, Paley's constructions otherwise.
+template <int MB>
+int base_entry(int kind, int r, int c) {
+    if constexpr (MB == 32) return (__builtin_popcount((unsigned)(r & c)) & 1) ? -1 : 1;
+    else return hadamard_base_entry(MB, kind, r, c);
+}
+
 template <int OUT, bool PERM, int MB, int NCH>
 hipError_t launch_stg(const ApplyParams& p, const Npo2Geom<MB>& g, dim3 grid, hipStream_t stream) {
     const int stg = g.kp - npo2_chunk_bits<MB>();
@@ -537,13 +556,13 @@ template <int MB>
 hipError_t launch_npo2_base_impl(const ApplyParams& p, int out_kind, hipStream_t stream) {
     Npo2Geom<MB> g;
     constexpr int kRowsPad = sizeof(g.hrow) / sizeof(g.hrow[0]);
-    const int kind = hadamard_base_kind(MB);
+    const int kind = MB == 32 ? 0 : hadamard_base_kind(MB);
     for (int r = 0; r < kRowsPad; ++r)
         for (int w = 0; w < Base<MB>::kNT; ++w) {
             uint32_t bits = 0;
             if (r < MB)
                 for (int c = 0; c < 32 && 32 * w + c < MB; ++c)
-                    if (hadamard_base_entry(MB, kind, r, 32 * w + c) < 0) bits |= 1u << c;
+                    if (base_entry<MB>(kind, r, 32 * w + c) < 0) bits |= 1u << c;
             g.hrow[r][w] = bits;
         }
     g.kp = 0;
