@@ -29,6 +29,9 @@ WORKLOADS = {
     "llama8b_d4096_b4096_int4_perm": ("llama8b_d4096", 4096, "int4", True),
     "llama8b_d14336_b128_int4_perm": ("llama8b_d14336", 128, "int4", True),
     "llama8b_d14336_b2048_int4_perm": ("llama8b_d14336", 2048, "int4", True),
+    # full-vector rotation at the Llama3 1B/3B width (Table 3, first row), on the d = 8192 workloads
+    "calib_apply_full_mxfp4": ("calib_apply", 8192, "mxfp4", False),
+    "llama1b_down_full_int4": ("llama1b_down", 8192, "int4", False),
     # full-vector rotation at the Llama3-8B width, 14336 = 2^9 * 28 (Appendix A.1); a permutation
     # does not change the bound of one block that spans the row, so P = I
     "llama8b_d14336_full_int4": ("llama8b_d14336", 14336, "int4", False),
