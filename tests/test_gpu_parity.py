@@ -320,7 +320,10 @@ def test_token_formats_run_time_schedule(fmt, T, d, b, with_perm):
 
 
 # ---- the codes consumed: W4A4 product with P and the rotation merged into the weights -----------
-@pytest.mark.parametrize("T,N,d,b", [(70, 50, 256, 32), (33, 130, 4096, 128), (5, 3, 1024, 1024)])
+@pytest.mark.parametrize("T,N,d,b", [(70, 50, 256, 32), (33, 130, 4096, 128), (5, 3, 1024, 1024),
+                                     # rotations that are not symmetric matrices (base 12) or not powers of two
+                                     (20, 24, 3072, 3072), (9, 17, 3584, 896), (6, 5, 2432, 2432),
+                                     (7, 9, 8192, 8192)])
 def test_w4a4_gemm_against_oracle_and_unrotated_product(T, N, d, b):
     torch = _torch()
     rng = np.random.default_rng(T + N + d)
