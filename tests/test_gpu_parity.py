@@ -662,3 +662,29 @@ def test_seeded_sweep(T, d, b, fmt, with_perm, pad, seed):
     perm = rng.permutation(d).astype(np.int32) if with_perm else None
     rotate = orc.fwht_f64 if (b > 4096 and b & (b - 1) == 0) else None
     assert_parity(bits, perm, b, fmt, "auto", rotate=rotate, ldx=(d + pad) if pad else None, label="sweep")
+
+
+@pytest.mark.parametrize("d,b,fmt,with_perm", [(3584, 3584, "int4", False), (7168, 1792, "mxfp4", True),
+                                               (3072, 3072, "int4_asym", True), (6144, 6144, "fp4_token", False),
+                                               (2432, 2432, "mxfp4", False), (4864, 4864, "int4", True),
+                                               (8192, 8192, "int4", True), (16384, 16384, "mxfp4", False)])
+def test_chunked_kernels_more_rows_than_one_pass_of_the_grid(d, b, fmt, with_perm):
+    """Every workgroup comes round several times (4, 2 or 1 rows per pass); sampled rows against the oracle."""
+    torch = _torch()
+    chunk = next(c for c in (3584, 3072, 2432, 4096) if d % c == 0)      # positions per wave chunk
+    rows_per_pass = 4 // (d // chunk)                                    # a workgroup takes 4 chunks per pass
+    T = int(512 * rows_per_pass * 2.5) + 3
+    print(f"[many] d={d} b={b} fmt={fmt} T={T}", flush=True)
+    x = _heavy_rows(T, d, 4000 + d)
+    perm = np.random.default_rng(d + 1).permutation(d).astype(np.int32) if with_perm else None
+    perm_t = None if perm is None else torch.from_numpy(perm).cuda()
+    codes, scales = binding.perq_permute_rotate_quant(binding.bits_to_device(x), perm_t, b, fmt)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    rows = np.unique(np.r_[0:6, T - 6:T, rng.choice(T, size=40, replace=False),
+                           512 * rows_per_pass - 2:512 * rows_per_pass + 3])
+    rotate = orc.fwht_f64 if (b > 4096 and b & (b - 1) == 0) else None
+    rep = parity.compare_apply(x[rows], perm, b, fmt, codes.cpu().numpy()[rows], scales.cpu().numpy()[rows],
+                               rotate=rotate)
+    print("       ", rep.summary(), flush=True)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
