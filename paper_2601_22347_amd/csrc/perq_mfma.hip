@@ -672,9 +672,11 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         }
     }
 
+    // Operand addresses through `perm`, general case with two staging buffers: see below.
+    constexpr bool kLdsTable = PERM && !SHARED && kDouble;
     if (tid < 4) {
         *reinterpret_cast<uint32_t*>(lds + kZeroSlot + 4 * tid) = 0u;
-        if constexpr (kDouble) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
+        if constexpr (kDouble && !kLdsTable) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
     }
     __syncthreads();
     auto first_loads = [&]() {
@@ -682,7 +684,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         if (drawing) draw();
         if constexpr (kDouble) n_behind = u_nxt < n_units ? issue_loads(u_nxt, kBufStride) : 0;
     };
-    if constexpr (!SHARED) first_loads();
+    if constexpr (!SHARED && !kLdsTable) first_loads();
 
     // Shared case: collect the eight fragments of addresses the four waves have left in LDS.
     if constexpr (SHARED) {
@@ -709,6 +711,71 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // (absent sub-blocks re-read position 0 and are redirected to the zero slot).
     if constexpr (shared_src) {
         // done above
+    } else if constexpr (kLdsTable) {
+        // The first unit is requested, then the wave reads its tile of `perm` in order (sixteen
+        // 16-byte loads per lane, 1 KiB per instruction: read lane by lane along the operand
+        // layout the same entries cost eight times as many cache-line requests, which made the
+        // prologue the longest part of a short launch), turns every entry into the 16-bit LDS
+        // offset of its channel inside a row, and keeps the 4096 offsets in its own quarter of
+        // the second staging buffer, still unused.  Every lane then picks its 64 offsets from
+        // there.  Only after that is the second unit requested into that buffer.
+        if (u_cur < n_units) issue_loads(u_cur, 0u);
+        unsigned char* tab = lds + kBufStride + (uint32_t)wave * 8192u;
+        {
+            int4 pe[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t t = ((uint32_t)j * 64u + (uint32_t)lane) * 4u;      // entry inside the tile
+                const uint32_t pos = (uint32_t)tile_base + t;
+                pe[j] = (int)t < tile_len ? *reinterpret_cast<const int4*>(p.perm + (pos & g.fold_mask)) : make_int4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t t = ((uint32_t)j * 64u + (uint32_t)lane) * 4u;
+                const uint32_t fb = ((uint32_t)tile_base + t) & ~g.fold_mask;       // first channel of the real row
+                const uint32_t ch[4] = {fb + pe[j].x, fb + pe[j].y, fb + pe[j].z, fb + pe[j].w};
+                uint32_t o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = (granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1);
+                *reinterpret_cast<uint2*>(tab + 2u * t) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+            }
+        }
+        const uint32_t base = (uint32_t)rr * g.row_bytes;
+        if constexpr (!kHighK) {
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) qvalid[q] = (c * kQ + q) * 32 < tile_len;
+#pragma unroll
+            for (int f = 0; f < kQ * 2; ++f) {
+                const uint32_t in_tile = ((uint32_t)c * kQ + (f >> 1)) * 32u + 16u * (f & 1) + 8u * h;
+                const uint4 t4 = *reinterpret_cast<const uint4*>(tab + 2u * in_tile);
+                const uint32_t w[4] = {t4.x, t4.y, t4.z, t4.w};
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    src[f * 8 + e] = qvalid[f >> 1] ? base + (w[e >> 1] & 0xFFFFu) : kZeroSlot;
+                    src[f * 8 + e + 1] = qvalid[f >> 1] ? base + (w[e >> 1] >> 16) : kZeroSlot;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) qvalid[q] = hk_run(q) < tile_len;
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t in_tile = hk_pos(sigma_i, 16u * f + 8u * h + e);
+                    const bool ok = (int)in_tile < tile_len;
+                    const uint32_t off = *reinterpret_cast<const uint16_t*>(tab + 2u * (ok ? in_tile : 0u));
+                    src[f * 8 + e] = ok ? base + off : kZeroSlot;
+                }
+            }
+        }
+        // The zero slot of the second buffer lies in the last wave's table.  That wave clears it once
+        // it has read its offsets and before the barrier: a clear issued after the barrier could land
+        // behind another wave's row data on a launch whose code is still cold.
+        if (wave == NWAVES - 1 && lane < 4) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * lane) = 0u;
+        __syncthreads();      // every wave has its offsets: the tables' place may be written
+        if (drawing) draw();
+        n_behind = u_nxt < n_units ? issue_loads(u_nxt, kBufStride) : 0;
     } else if constexpr (!kHighK) {
         int4 pe[kQ * 2][2];
 #pragma unroll
