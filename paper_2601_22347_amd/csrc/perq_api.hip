@@ -4,7 +4,9 @@
 #include "perq_launch.h"
 
 #include <cmath>
+#include <map>
 #include <mutex>
+#include <tuple>
 
 namespace perq {
 
@@ -28,6 +30,36 @@ const LaunchInfo& launch_info() {
         known[dev] = true;
     }
     return info[dev];
+}
+
+hipError_t resident_blocks(const void* kern, int threads, uint32_t lds_bytes, int* per_cu) {
+    static std::map<std::tuple<const void*, int, int, uint32_t>, int> known;
+    static std::mutex mu;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    const auto key = std::make_tuple(kern, dev, threads, lds_bytes);
+    std::lock_guard<std::mutex> lock(mu);
+    const auto it = known.find(key);
+    if (it != known.end()) {
+        *per_cu = it->second;
+        return hipSuccess;
+    }
+    // the limit is only ever raised: an earlier, larger configuration of the same kernel stays valid
+    static std::map<std::pair<const void*, int>, uint32_t> limit;
+    hipError_t e = hipSuccess;
+    uint32_t& lim = limit[std::make_pair(kern, dev)];
+    if (lds_bytes > lim) {
+        e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        lim = lds_bytes;
+    }
+    int n = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, threads, lds_bytes);
+    if (e != hipSuccess) return e;
+    if (n < 1) n = 1;
+    known[key] = n;
+    *per_cu = n;
+    return hipSuccess;
 }
 
 namespace {

@@ -339,16 +339,10 @@ hipError_t launch_butterfly_out(const ApplyParams& p, hipStream_t stream) {
     auto kern = threads <= 256   ? (p.perm ? butterfly_kernel<OUT, true, 256> : butterfly_kernel<OUT, false, 256>)
                 : threads <= 512 ? (p.perm ? butterfly_kernel<OUT, true, 512> : butterfly_kernel<OUT, false, 512>)
                                  : (p.perm ? butterfly_kernel<OUT, true, 1024> : butterfly_kernel<OUT, false, 1024>);
-    if (lds_bytes > 64u * 1024u) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-    }
     // Persistent grid: as many workgroups as the device keeps resident, each walking the rows.
     int per_cu = 0;
-    hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, threads, lds_bytes);
+    const hipError_t oe = resident_blocks(reinterpret_cast<const void*>(kern), threads, lds_bytes, &per_cu);
     if (oe != hipSuccess) return oe;
-    if (per_cu < 1) per_cu = 1;
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
     int64_t grid = (int64_t)launch_info().num_cus * per_cu;
     if (grid > ngroups) grid = ngroups;

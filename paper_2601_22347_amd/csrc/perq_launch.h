@@ -14,6 +14,11 @@ struct LaunchInfo {
 // Properties of the current device (queried once per process and device).
 const LaunchInfo& launch_info();
 
+// Number of workgroups of `kern` (threads per workgroup, dynamic LDS bytes) that one CU keeps
+// resident; on first use per device also raises the kernel's dynamic-LDS limit to lds_bytes.
+// Asked of the runtime once per kernel, device and configuration, then remembered.
+hipError_t resident_blocks(const void* kern, int threads, uint32_t lds_bytes, int* per_cu);
+
 // Kernel families behind perq_permute_rotate_quant / perq_permute_rotate_f32.
 hipError_t launch_butterfly(const ApplyParams& p, int out_kind, hipStream_t stream);
 bool mfma_supports(const ApplyParams& p);

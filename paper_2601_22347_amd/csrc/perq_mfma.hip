@@ -869,13 +869,9 @@ hipError_t launch_mfma_st(const ApplyParams& p, uint32_t fold_mask, hipStream_t 
         if (p.perm && p.d == kTile) kern = mfma_kernel<OUT, true, NWAVES, STAGES, true>;
     }
     // (static and dynamic LDS together pass 64 KiB)
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds_bytes);
-    if (e != hipSuccess) return e;
     int per_cu = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, NWAVES * 64, lds_bytes);
+    hipError_t e = resident_blocks(reinterpret_cast<const void*>(kern), NWAVES * 64, lds_bytes, &per_cu);
     if (e != hipSuccess) return e;
-    if (per_cu < 1) per_cu = 1;
     int64_t grid = (int64_t)launch_info().num_cus * per_cu;
     if (grid > ngroups) grid = ngroups;
     // Units are dealt at run time when every worker (a wave on rows of its own, else a workgroup)
