@@ -15,9 +15,9 @@
 //   2. The rest of the Sylvester factor inside a wave's chunk: the a-bits held in the accumulator
 //      index are in-register butterflies, the bit that separates the half-waves is one swap stage.
 //      Bits above the chunk join different waves' chunks: every wave leaves its chunk in LDS as
-//      fp32 in position order, and after a barrier each thread collects 16 consecutive positions
+//      fp32 in position order, and after a barrier each thread collects 8 consecutive positions
 //      of every chunk of its row and finishes the remaining one or two stages in registers.
-//   3. In that layout (16 consecutive outputs per thread and chunk) the row statistics, the
+//   3. In that layout (8 consecutive outputs per thread and chunk) the row statistics, the
 //      rounding and the nibble packing are those of the other kernels.
 //
 // A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1.
@@ -79,7 +79,8 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kChunkA = kTileA * kAL;                 // a-values per wave chunk: 128, 256, 32
     constexpr int kChunkBits = (kChunkA == 32 ? 5 : (kChunkA == 128 ? 7 : 8));
     constexpr int kChunkPos = kChunkA * MB;               // 3584, 3072, 2432
-    constexpr int kGroups = kChunkPos / 16;               // runs of 16 positions per chunk
+    constexpr int kRun = 8;                               // consecutive positions per thread and chunk in phase 2
+    constexpr int kGroups = kChunkPos / kRun;             // runs per chunk
     constexpr int kChunkGranules = kChunkPos * 2 / 16;    // 16-byte pieces of raw input per chunk
     constexpr int kPre = (kChunkGranules + 63) / 64;      // pieces per lane: every wave stages its own chunk
     constexpr bool kPreExact = kChunkGranules % 64 == 0;
@@ -88,7 +89,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kRows = kNpo2Chunks / NCH;
     constexpr int kThreadsPerRow = 64 * NCH;
     constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
-    static_assert(kGroups % 2 == 0 && kChunkPos % 32 == 0, "a 32-group never straddles two threads' pairs");
+    // (a run of 8 is one dword of codes; with 16 the last pass would leave 12 .. 40 % of the lanes of
+    //  every wave idle, with 8 whole waves skip it instead)
+    static_assert(kGroups % 4 == 0 && kChunkPos % 32 == 0, "a 32-group is four neighbouring threads' runs");
     // MB = 32: a row of the A operand is 64 bytes, so rows four apart would share their banks.  The
     // 16-byte piece q of row a is kept at piece q ^ ((a >> 2) & 3) of the row instead (raw data only).
     constexpr bool kSwz = MB == 32;
@@ -332,16 +335,16 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         const int t_row = tid - my_row * kThreadsPerRow;
         const int64_t row = unit * kRows + my_row;
         const bool row_live = row < p.T;
-        float f[kIts][NCH][16];
+        float f[kIts][NCH][kRun];
 #pragma unroll
         for (int it = 0; it < kIts; ++it) {
             const int gI = t_row + kThreadsPerRow * it;
             const bool live = gI < kGroups;
 #pragma unroll
             for (int ch = 0; ch < NCH; ++ch) {
-                const float4* src = reinterpret_cast<const float4*>(ex + (my_row * NCH + ch) * kChunkPos + 16 * (live ? gI : 0));
+                const float4* src = reinterpret_cast<const float4*>(ex + (my_row * NCH + ch) * kChunkPos + kRun * (live ? gI : 0));
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < kRun / 4; ++q) {
                     const float4 t4 = src[q];
                     f[it][ch][4 * q] = t4.x; f[it][ch][4 * q + 1] = t4.y;
                     f[it][ch][4 * q + 2] = t4.z; f[it][ch][4 * q + 3] = t4.w;
@@ -352,7 +355,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
 #pragma unroll
                     for (int ch = 0; ch < NCH; ch += 2)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
+                        for (int e = 0; e < kRun; ++e) {
                             const float s = f[it][ch][e], t = f[it][ch + 1][e];
                             f[it][ch][e] = s + t;
                             f[it][ch + 1][e] = s - t;
@@ -364,7 +367,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
 #pragma unroll
                     for (int ch = 0; ch < 2; ++ch)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
+                        for (int e = 0; e < kRun; ++e) {
                             const float s = f[it][ch][e], t = f[it][ch + 2][e];
                             f[it][ch][e] = s + t;
                             f[it][ch + 2][e] = s - t;
@@ -385,7 +388,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) {
+                        for (int e = 0; e < kRun; ++e) {
                             if constexpr (OUT == OUT_INT4_ASYM) {
                                 m[0] = fmaxf(m[0], f[it][ch][e]);
                                 m[1] = fmaxf(m[1], -f[it][ch][e]);
@@ -434,50 +437,42 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
             if (gI < kGroups && row_live) {
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
-                    const int pos = ch * kChunkPos + 16 * gI;
+                    const int pos = ch * kChunkPos + kRun * gI;
                     float* val = f[it][ch];
                     if constexpr (OUT == OUT_F32) {
                         float4* yo = reinterpret_cast<float4*>(p.y + row * (int64_t)d + pos);
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                        for (int q = 0; q < kRun / 4; ++q)
                             yo[q] = make_float4(val[4 * q] * p.rsqrt_b, val[4 * q + 1] * p.rsqrt_b,
                                                 val[4 * q + 2] * p.rsqrt_b, val[4 * q + 3] * p.rsqrt_b);
                     } else {
-                        uint32_t lo, hi;
+                        uint32_t w;
                         if constexpr (OUT == OUT_INT4) {
-                            lo = int4_pack8(val, inv);
-                            hi = int4_pack8(val + 8, inv);
+                            w = int4_pack8(val, inv);
                         } else if constexpr (OUT == OUT_FP4_TOKEN) {
-                            lo = fp4_pack8(val, inv);
-                            hi = fp4_pack8(val + 8, inv);
+                            w = fp4_pack8(val, inv);
                         } else if constexpr (OUT == OUT_INT4_ASYM) {
-                            if (!qa.clamp) {
-                                const uint32_t zn = (uint32_t)qa.z * 0x11111111u;
-                                lo = int4a_pack8(val, qa.inv, zn);
-                                hi = int4a_pack8(val + 8, qa.inv, zn);
-                            } else {
-                                lo = int4a_pack8_clamped(val, qa.inv, qa.z);
-                                hi = int4a_pack8_clamped(val + 8, qa.inv, qa.z);
-                            }
+                            if (!qa.clamp) w = int4a_pack8(val, qa.inv, (uint32_t)qa.z * 0x11111111u);
+                            else w = int4a_pack8_clamped(val, qa.inv, qa.z);
                         } else {
                             // MXFP4: values normalised by 256 / sqrt(b), so the exponent field handed to
-                            // the convert is never zero; the other half of the 32-group is the
-                            // neighbouring thread's run
+                            // the convert is never zero; the rest of the 32-group are the runs of the
+                            // three neighbouring threads
                             float gm = 0.0f;
 #pragma unroll
-                            for (int e = 0; e < 16; ++e) {
+                            for (int e = 0; e < kRun; ++e) {
                                 val[e] *= g.norm256;
                                 gm = fmaxf(gm, fabsf(val[e]));
                             }
                             gm = fmaxf(gm, lane_xor<1>(gm));
+                            gm = fmaxf(gm, lane_xor<2>(gm));
                             const int E = mx_shared_exponent(gm, 8);
                             const float scale = __uint_as_float((uint32_t)(E + 8) << 23);
-                            lo = mxfp4_pack8(val, scale);
-                            hi = mxfp4_pack8(val + 8, scale);
-                            if ((gI & 1) == 0)
+                            w = mxfp4_pack8(val, scale);
+                            if ((gI & 3) == 0)
                                 static_cast<uint8_t*>(p.scales)[row * (int64_t)(d >> 5) + (pos >> 5)] = (uint8_t)E;
                         }
-                        *reinterpret_cast<uint2*>(p.codes + row * (int64_t)(d >> 1) + (pos >> 1)) = make_uint2(lo, hi);
+                        *reinterpret_cast<uint32_t*>(p.codes + row * (int64_t)(d >> 1) + (pos >> 1)) = w;
                     }
                 }
             }
