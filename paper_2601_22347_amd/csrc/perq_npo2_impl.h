@@ -15,9 +15,9 @@
 //   2. The rest of the Sylvester factor inside a wave's chunk: the a-bits held in the accumulator
 //      index are in-register butterflies, the bit that separates the half-waves is one swap stage.
 //      Bits above the chunk join different waves' chunks: every wave leaves its chunk in LDS as
-//      fp32 in position order, and after a barrier each thread collects 8 consecutive positions
-//      of every chunk of its row and finishes the remaining one or two stages in registers.
-//   3. In that layout (8 consecutive outputs per thread and chunk) the row statistics, the
+//      fp32 in position order, and after a barrier each thread collects 8 (or 16) consecutive
+//      positions of every chunk of its row and finishes the remaining one or two stages in registers.
+//   3. In that layout (8 or 16 consecutive outputs per thread and chunk) the row statistics, the
 //      rounding and the nibble packing are those of the other kernels.
 //
 // A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1.
@@ -79,7 +79,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kChunkA = kTileA * kAL;                 // a-values per wave chunk: 128, 256, 32
     constexpr int kChunkBits = (kChunkA == 32 ? 5 : (kChunkA == 128 ? 7 : 8));
     constexpr int kChunkPos = kChunkA * MB;               // 3584, 3072, 2432
-    constexpr int kRun = 8;                               // consecutive positions per thread and chunk in phase 2
+    // consecutive positions per thread and chunk in phase 2 (16 was measured too: no faster where
+    // it fills every lane, and slower with a gather table in registers)
+    constexpr int kRun = 8;
     constexpr int kGroups = kChunkPos / kRun;             // runs per chunk
     constexpr int kChunkGranules = kChunkPos * 2 / 16;    // 16-byte pieces of raw input per chunk
     constexpr int kPre = (kChunkGranules + 63) / 64;      // pieces per lane: every wave stages its own chunk
@@ -89,9 +91,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kRows = kNpo2Chunks / NCH;
     constexpr int kThreadsPerRow = 64 * NCH;
     constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
-    // (a run of 8 is one dword of codes; with 16 the last pass would leave 12 .. 40 % of the lanes of
-    //  every wave idle, with 8 whole waves skip it instead)
-    static_assert(kGroups % 4 == 0 && kChunkPos % 32 == 0, "a 32-group is four neighbouring threads' runs");
+    // (a run of 8 is one dword of codes; where runs of 16 would leave 12 .. 40 % of the lanes of every
+    //  wave idle in the last pass, whole waves skip it with runs of 8 instead)
+    static_assert(kGroups % (32 / kRun) == 0 && kChunkPos % 32 == 0, "a 32-group is two or four neighbouring threads' runs");
     // MB = 32: a row of the A operand is 64 bytes, so rows four apart would share their banks.  The
     // 16-byte piece q of row a is kept at piece q ^ ((a >> 2) & 3) of the row instead (raw data only).
     constexpr bool kSwz = MB == 32;
@@ -446,18 +448,11 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                             yo[q] = make_float4(val[4 * q] * p.rsqrt_b, val[4 * q + 1] * p.rsqrt_b,
                                                 val[4 * q + 2] * p.rsqrt_b, val[4 * q + 3] * p.rsqrt_b);
                     } else {
-                        uint32_t w;
-                        if constexpr (OUT == OUT_INT4) {
-                            w = int4_pack8(val, inv);
-                        } else if constexpr (OUT == OUT_FP4_TOKEN) {
-                            w = fp4_pack8(val, inv);
-                        } else if constexpr (OUT == OUT_INT4_ASYM) {
-                            if (!qa.clamp) w = int4a_pack8(val, qa.inv, (uint32_t)qa.z * 0x11111111u);
-                            else w = int4a_pack8_clamped(val, qa.inv, qa.z);
-                        } else {
-                            // MXFP4: values normalised by 256 / sqrt(b), so the exponent field handed to
-                            // the convert is never zero; the rest of the 32-group are the runs of the
-                            // three neighbouring threads
+                        uint32_t w[kRun / 8];
+                        if constexpr (OUT == OUT_MXFP4) {
+                            // values normalised by 256 / sqrt(b), so the exponent field handed to the
+                            // convert is never zero; the rest of the 32-group are the runs of the
+                            // neighbouring threads
                             float gm = 0.0f;
 #pragma unroll
                             for (int e = 0; e < kRun; ++e) {
@@ -465,14 +460,29 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                                 gm = fmaxf(gm, fabsf(val[e]));
                             }
                             gm = fmaxf(gm, lane_xor<1>(gm));
-                            gm = fmaxf(gm, lane_xor<2>(gm));
+                            if constexpr (kRun == 8) gm = fmaxf(gm, lane_xor<2>(gm));
                             const int E = mx_shared_exponent(gm, 8);
                             const float scale = __uint_as_float((uint32_t)(E + 8) << 23);
-                            w = mxfp4_pack8(val, scale);
-                            if ((gI & 3) == 0)
+#pragma unroll
+                            for (int k = 0; k < kRun / 8; ++k) w[k] = mxfp4_pack8(val + 8 * k, scale);
+                            if ((gI & (32 / kRun - 1)) == 0)
                                 static_cast<uint8_t*>(p.scales)[row * (int64_t)(d >> 5) + (pos >> 5)] = (uint8_t)E;
+                        } else {
+#pragma unroll
+                            for (int k = 0; k < kRun / 8; ++k) {
+                                if constexpr (OUT == OUT_INT4) {
+                                    w[k] = int4_pack8(val + 8 * k, inv);
+                                } else if constexpr (OUT == OUT_FP4_TOKEN) {
+                                    w[k] = fp4_pack8(val + 8 * k, inv);
+                                } else {
+                                    if (!qa.clamp) w[k] = int4a_pack8(val + 8 * k, qa.inv, (uint32_t)qa.z * 0x11111111u);
+                                    else w[k] = int4a_pack8_clamped(val + 8 * k, qa.inv, qa.z);
+                                }
+                            }
                         }
-                        *reinterpret_cast<uint32_t*>(p.codes + row * (int64_t)(d >> 1) + (pos >> 1)) = w;
+                        uint8_t* dst = p.codes + row * (int64_t)(d >> 1) + (pos >> 1);
+                        if constexpr (kRun == 16) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+                        else *reinterpret_cast<uint32_t*>(dst) = w[0];
                     }
                 }
             }
