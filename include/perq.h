@@ -143,7 +143,7 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  *   x_bf16   device, bf16 [T, ldx]; ldx >= d; base 16-byte aligned and ldx % 8 == 0
  *   perm     device, int32 [d], or NULL for P = I
  *   b        16 <= b <= d, b divides d; a power of two, or 2^k' * 4t with 4t = 28 (d = 3584, 7168,
- *            14336), 4t = 12 (d = 3072, 6144, 12288) or 4t = 76 (d = 2432, 4864, 9728); see
+ *            14336, 28672), 4t = 12 (d = 3072, 6144, 12288) or 4t = 76 (d = 2432, 4864, 9728); see
  *            perq_hadamard_base.  Other widths for these bases, and other bases the library can
  *            build, are UNSUPPORTED; a b for which it knows no Hadamard matrix is INVALID_ARG
  *   codes    device, uint8 [T, d/2]; element 2k in the low nibble of byte k, 2k+1 in the high

@@ -115,8 +115,8 @@ perq_status_t dispatch(const ApplyParams& p, int out_kind, perq_algo_t algo, hip
     switch (algo) {
         case PERQ_ALGO_AUTO:
             // The matrix-core kernel wins wherever its 4096-wide wave tiles are filled (measured:
-            // rocprofv3 summaries under profiles/); b = 8192, 16384 on rows of 8192 or 16384 go to the
-            // chunked matrix-core kernel; other narrow rows, odd widths and b > 4096 take the butterflies.
+            // rocprofv3 summaries under profiles/); b > 4096 on rows of 8192, 16384 or 32768 goes to the
+            // chunked matrix-core kernel; other narrow rows and odd widths take the butterflies.
             if (chunked_pow2_supports(p)) e = launch_npo2_32(p, out_kind, stream);
             else e = mfma_preferred(p, out_kind) ? launch_mfma(p, out_kind, stream) : launch_butterfly(p, out_kind, stream);
             break;

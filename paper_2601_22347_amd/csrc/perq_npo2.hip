@@ -27,7 +27,9 @@ bool npo2_supports(const ApplyParams& p) {
         case 76: chunk_pos = npo2_chunk_pos<76>(); break;
         default: return false;
     }
-    if (p.d != chunk_pos && p.d != 2 * chunk_pos && p.d != 4 * chunk_pos) return false;
+    if (p.d != chunk_pos && p.d != 2 * chunk_pos && p.d != 4 * chunk_pos &&
+        !(base_order(p.b) == 28 && p.d == 8 * chunk_pos))
+        return false;
     // row offsets inside a unit of up to four rows are kept in 32 bits
     return p.d % p.b == 0 && p.ldx < ((int64_t)1 << 28);
 }

@@ -20,7 +20,8 @@
 //   3. In that layout (8 or 16 consecutive outputs per thread and chunk) the row statistics, the
 //      rounding and the nibble packing are those of the other kernels.
 //
-// A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1.
+// A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1;
+// rows of 8 chunks (d = 28672 and 32768 for the bases 28 and 32) take workgroups of eight waves.
 // The raw rows go global -> registers (issued one iteration ahead) -> LDS; each chunk's bf16 data
 // lie at the start of the fp32 area of the same chunk; the owning wave puts them there and, without
 // a gather, is the only one to read them before it overwrites them: two barriers per row.
@@ -54,8 +55,8 @@ template <> struct Base<76> { static constexpr int kA0 = 1, kKS = 5, kNT = 3, kA
 // matrix-core kernel hold (b = 8192, 16384 on d = 8192, 16384) take the same path.
 template <> struct Base<32> { static constexpr int kA0 = 1, kKS = 2, kNT = 1, kAL = 4; };
 
-constexpr int kNpo2Threads = 256;
-constexpr int kNpo2Chunks = 4;                 // chunks per workgroup iteration
+// Waves per workgroup = chunks per workgroup iteration: four, or eight for rows of eight chunks.
+constexpr int npo2_waves(int nch) { return nch == 8 ? 8 : 4; }
 
 template <int MB>
 struct Npo2Geom {
@@ -69,7 +70,7 @@ struct Npo2Geom {
 // unconditionally.  STG = -1: a smaller block, k' is read at run time (a stage that may or may
 // not run costs a register copy per element on top of its two operations).
 template <int OUT, bool PERM, int MB, int NCH, int STG>
-__global__ void __launch_bounds__(kNpo2Threads, 2)
+__global__ void __launch_bounds__(64 * npo2_waves(NCH), NCH == 8 ? 1 : 2)
 npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     using B = Base<MB>;
     constexpr int kA0 = B::kA0, kKS = B::kKS, kNT = B::kNT, kAL = B::kAL;
@@ -88,6 +89,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr bool kPreExact = kChunkGranules % 64 == 0;
     constexpr int kTiles = kAL * kNT;                     // accumulator tiles per lane
     constexpr int kVals = 16 * kTiles;
+    constexpr int kNpo2Chunks = npo2_waves(NCH);
     constexpr int kRows = kNpo2Chunks / NCH;
     constexpr int kThreadsPerRow = 64 * NCH;
     constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
@@ -154,7 +156,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     auto a_of = [&](int al, int ks) { return kTileA * al + kA0 * c + (kA0 == 2 ? ks : 0); };
 
     // ---- gather table (P != I): LDS byte address, relative to the row's first chunk, of the
-    //      source channel of every A element of this lane; 16-bit, two per register ---------------
+    //      source channel of every A element of this lane; 16-bit (halved), two per register ------
     constexpr int kTab = kAL * kKS * 4;
     uint32_t tab[PERM ? kTab : 1];
     if constexpr (PERM) {
@@ -173,8 +175,9 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                             const int pos = my_chunk * kChunkPos + a_of(al, ks) * MB + r;
                             const int ch = p.perm[pos];
                             const uint32_t cl = (uint32_t)(ch % kChunkPos);
-                            off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 4) +
-                                  (kSwz ? ((cl >> 5) * 4u + (((cl >> 3) & 3u) ^ ((cl >> 7) & 3u))) * 16u + (cl & 7u) * 2u : cl * 2u);
+                            // (in units of two bytes: eight chunks of fp32 pass 64 KiB)
+                            off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 2) +
+                                  (kSwz ? ((cl >> 5) * 4u + (((cl >> 3) & 3u) ^ ((cl >> 7) & 3u))) * 8u + (cl & 7u) : cl);
                         }
                         pair |= off << (16 * s);
                     }
@@ -240,8 +243,8 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                     for (int e2 = 0; e2 < 4; ++e2) {
                         const uint32_t pair = tab[(al * kKS + ks) * 4 + e2];
                         const uint32_t o0 = pair & 0xFFFFu, o1 = pair >> 16;
-                        const uint32_t v0 = o0 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + o0);
-                        const uint32_t v1 = o1 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + o1);
+                        const uint32_t v0 = o0 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + 2u * o0);
+                        const uint32_t v1 = o1 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + 2u * o1);
                         w[e2] = v0 | (v1 << 16);
                     }
                 }
@@ -352,28 +355,21 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                     f[it][ch][4 * q + 2] = t4.z; f[it][ch][4 * q + 3] = t4.w;
                 }
             }
-            if constexpr (NCH >= 2) {
-                if (STG >= 1) {
+            // stages across chunks: bit s of the chunk index, s < STG
 #pragma unroll
-                    for (int ch = 0; ch < NCH; ch += 2)
+            for (int sb = 0; sb < 3; ++sb) {
+                if (sb < STG && (2 << sb) <= NCH) {
 #pragma unroll
-                        for (int e = 0; e < kRun; ++e) {
-                            const float s = f[it][ch][e], t = f[it][ch + 1][e];
-                            f[it][ch][e] = s + t;
-                            f[it][ch + 1][e] = s - t;
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        if ((ch & (1 << sb)) == 0) {
+#pragma unroll
+                            for (int e = 0; e < kRun; ++e) {
+                                const float s = f[it][ch][e], t = f[it][ch | (1 << sb)][e];
+                                f[it][ch][e] = s + t;
+                                f[it][ch | (1 << sb)][e] = s - t;
+                            }
                         }
-                }
-            }
-            if constexpr (NCH >= 4) {
-                if (STG >= 2) {
-#pragma unroll
-                    for (int ch = 0; ch < 2; ++ch)
-#pragma unroll
-                        for (int e = 0; e < kRun; ++e) {
-                            const float s = f[it][ch][e], t = f[it][ch + 2][e];
-                            f[it][ch][e] = s + t;
-                            f[it][ch + 2][e] = s - t;
-                        }
+                    }
                 }
             }
         }
@@ -522,31 +518,37 @@ int base_entry(int kind, int r, int c) {
 template <int OUT, bool PERM, int MB, int NCH>
 hipError_t launch_stg(const ApplyParams& p, const Npo2Geom<MB>& g, dim3 grid, hipStream_t stream) {
     const int stg = g.kp - npo2_chunk_bits<MB>();
-    const dim3 block(kNpo2Threads);
+    const dim3 block(64 * npo2_waves(NCH));
     if (stg < 0) {
         hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, -1>), grid, block, 0, stream, p, g);
     } else if (stg == 0) {
         hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 0>), grid, block, 0, stream, p, g);
-    } else if constexpr (NCH >= 2) {
-        if (stg == 1) {
-            hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 1>), grid, block, 0, stream, p, g);
-        } else if constexpr (NCH >= 4) {
-            hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 2>), grid, block, 0, stream, p, g);
-        } else {
-            return hipErrorInvalidValue;
-        }
+    } else if (stg == 1 && NCH >= 2) {
+        if constexpr (NCH >= 2) hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 1>), grid, block, 0, stream, p, g);
+    } else if (stg == 2 && NCH >= 4) {
+        if constexpr (NCH >= 4) hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 2>), grid, block, 0, stream, p, g);
+    } else if (stg == 3 && NCH >= 8) {
+        if constexpr (NCH >= 8) hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 3>), grid, block, 0, stream, p, g);
     } else {
         return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
 
+// Rows of eight chunks (d = 28672, 32768) exist for the bases 28 and 32 only.
+template <int MB>
+constexpr bool npo2_has_eight() { return MB == 28 || MB == 32; }
+
 template <int OUT, bool PERM, int MB>
 hipError_t launch_nch(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, dim3 grid, hipStream_t stream) {
     switch (nch) {
         case 1: return launch_stg<OUT, PERM, MB, 1>(p, g, grid, stream);
         case 2: return launch_stg<OUT, PERM, MB, 2>(p, g, grid, stream);
-        default: return launch_stg<OUT, PERM, MB, 4>(p, g, grid, stream);
+        case 4: return launch_stg<OUT, PERM, MB, 4>(p, g, grid, stream);
+        case 8:
+            if constexpr (npo2_has_eight<MB>()) return launch_stg<OUT, PERM, MB, 8>(p, g, grid, stream);
+            return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;
     }
 }
 
@@ -574,9 +576,9 @@ hipError_t launch_npo2_base_impl(const ApplyParams& p, int out_kind, hipStream_t
     while ((MB << g.kp) < p.b) ++g.kp;
     g.norm256 = (float)(256.0 / std::sqrt((double)p.b));
     const int nch = p.d / npo2_chunk_pos<MB>();
-    const int64_t rows_per_unit = kNpo2Chunks / nch;
+    const int64_t rows_per_unit = npo2_waves(nch) / nch;
     const int64_t n_units = (p.T + rows_per_unit - 1) / rows_per_unit;
-    const int64_t max_grid = 2 * (int64_t)launch_info().num_cus;
+    const int64_t max_grid = (nch == 8 ? 1 : 2) * (int64_t)launch_info().num_cus;
     const dim3 grid((unsigned)(n_units < max_grid ? n_units : max_grid));
     switch (out_kind) {
         case OUT_INT4: return launch_perm<OUT_INT4, MB>(p, g, nch, grid, stream);

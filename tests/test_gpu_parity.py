@@ -533,15 +533,19 @@ def _heavy_rows(T, d, seed):
                                   (12288, [24, 192, 1536, 3072, 6144, 12288]),
                                   # base 76 (chunks of 2432): k' = 0 .. 7
                                   (2432, [76, 152, 608, 1216, 2432]), (4864, [304, 2432, 4864]),
-                                  (9728, [76, 1216, 2432, 4864, 9728])])
+                                  (9728, [76, 1216, 2432, 4864, 9728]),
+                                  # rows of eight chunks: workgroups of eight waves (base 28; the powers of
+                                  # two above 4096 take the same kernel with H_32 as base)
+                                  (28672, [28, 3584, 7168, 14336, 28672]), (32768, [8192, 16384, 32768])])
 @pytest.mark.parametrize("with_perm", [False, True])
 def test_nonpo2_rotation_against_oracle(d, bs, with_perm):
-    T = 13 if d >= 9728 else 21                        # ragged against 1, 2 and 4 rows per workgroup pass
+    T = (5 if d >= 28672 else 13) if d >= 9728 else 21      # ragged against 1, 2 and 4 rows per workgroup pass
     x = _heavy_rows(T, d, 900 + d)
     perm = np.random.default_rng(d).permutation(d).astype(np.int32) if with_perm else None
     for b in bs:
+        rotate = orc.fwht_f64 if (b > 4096 and b & (b - 1) == 0) else None
         for fmt in (["int4", "mxfp4"] if b not in (bs[0], bs[-1]) else ["int4", "mxfp4", "int4_asym", "fp4_token"]):
-            assert_parity(x, perm, b, fmt, "auto", label="nonpo2")
+            assert_parity(x, perm, b, fmt, "auto", rotate=rotate, label="nonpo2")
 
 
 def test_nonpo2_structured_rows_and_many_rows():
@@ -630,20 +634,20 @@ def test_nonpo2_row_stride_single_row_empty_and_repeat():
 def _random_cases(n, seed):
     rng = np.random.default_rng(seed)
     widths = [64, 256, 320, 512, 1536, 2048, 2432, 3072, 3584, 4096, 4864, 5120, 6144, 7168, 8192, 9728, 12288,
-              14336, 16384]
+              14336, 16384, 28672, 32768]
     cases = []
     while len(cases) < n:
         d = int(rng.choice(widths))
         # block sizes the library takes for this width: powers of two, and 2^k' * {12, 28, 76} on the
         # widths of the three bases
-        bs = [b for b in (16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384) if b <= d and d % b == 0]
+        bs = [b for b in (16, 32, 64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768) if b <= d and d % b == 0]
         for base, chunk in ((28, 3584), (12, 3072), (76, 2432)):
-            if d in (chunk, 2 * chunk, 4 * chunk):
+            if d in (chunk, 2 * chunk, 4 * chunk) or (base == 28 and d == 8 * chunk):
                 bs += [base << k for k in range(12) if (base << k) >= 16 and (base << k) <= d and d % (base << k) == 0]
         if d % 32 != 0 or not bs:
             continue
         b = int(rng.choice(bs))
-        T = int(rng.integers(1, 48))
+        T = int(rng.integers(1, 48 if d < 20000 else 12))
         fmt = str(rng.choice(["int4", "mxfp4", "int4_asym", "fp4_token"]))
         with_perm = bool(rng.integers(0, 2))
         pad = int(rng.choice([0, 0, 8, 64, 1000]))
@@ -667,12 +671,13 @@ def test_seeded_sweep(T, d, b, fmt, with_perm, pad, seed):
 @pytest.mark.parametrize("d,b,fmt,with_perm", [(3584, 3584, "int4", False), (7168, 1792, "mxfp4", True),
                                                (3072, 3072, "int4_asym", True), (6144, 6144, "fp4_token", False),
                                                (2432, 2432, "mxfp4", False), (4864, 4864, "int4", True),
-                                               (8192, 8192, "int4", True), (16384, 16384, "mxfp4", False)])
+                                               (8192, 8192, "int4", True), (16384, 16384, "mxfp4", False),
+                                               (28672, 28672, "int4", False), (32768, 16384, "mxfp4", True)])
 def test_chunked_kernels_more_rows_than_one_pass_of_the_grid(d, b, fmt, with_perm):
     """Every workgroup comes round several times (4, 2 or 1 rows per pass); sampled rows against the oracle."""
     torch = _torch()
     chunk = next(c for c in (3584, 3072, 2432, 4096) if d % c == 0)      # positions per wave chunk
-    rows_per_pass = 4 // (d // chunk)                                    # a workgroup takes 4 chunks per pass
+    rows_per_pass = max(1, 4 // (d // chunk))                            # a workgroup takes 4 (or 8) chunks per pass
     T = int(512 * rows_per_pass * 2.5) + 3
     print(f"[many] d={d} b={b} fmt={fmt} T={T}", flush=True)
     x = _heavy_rows(T, d, 4000 + d)
