@@ -712,34 +712,42 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     if constexpr (shared_src) {
         // done above
     } else if constexpr (kLdsTable) {
-        // The first unit is requested, then the wave reads its tile of `perm` in order (sixteen
-        // 16-byte loads per lane, 1 KiB per instruction: read lane by lane along the operand
-        // layout the same entries cost eight times as many cache-line requests, which made the
-        // prologue the longest part of a short launch), turns every entry into the 16-bit LDS
-        // offset of its channel inside a row, and keeps the 4096 offsets in its own quarter of
-        // the second staging buffer, still unused.  Every lane then picks its 64 offsets from
+        // The first unit is requested, then the tile of `perm` is read in order (16-byte loads,
+        // 1 KiB per instruction: read lane by lane along the operand layout the same entries cost
+        // eight times as many cache-line requests), every entry is turned into the 16-bit LDS
+        // offset of its channel inside a row, and the 4096 offsets of a tile are kept in a quarter
+        // of the second staging buffer, still unused.  Every lane then picks its 64 offsets from
         // there.  Only after that is the second unit requested into that buffer.
         if (u_cur < n_units) issue_loads(u_cur, 0u);
-        unsigned char* tab = lds + kBufStride + (uint32_t)wave * 8192u;
+        // Waves on the same tile (the rows of a row group; all four on rows of their own) share one
+        // table and read a part of the tile's entries each.
+        const uint32_t tile_id = (uint32_t)wave % (uint32_t)g.tiles_per_row;
+        const uint32_t share = (uint32_t)NWAVES / (uint32_t)g.tiles_per_row;      // 1, 2 or 4 waves per table
+        unsigned char* tab = lds + kBufStride + tile_id * 8192u;
         {
             int4 pe[16];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const uint32_t t = ((uint32_t)j * 64u + (uint32_t)lane) * 4u;      // entry inside the tile
-                const uint32_t pos = (uint32_t)tile_base + t;
-                pe[j] = (int)t < tile_len ? *reinterpret_cast<const int4*>(p.perm + (pos & g.fold_mask)) : make_int4(0, 0, 0, 0);
+            for (int jj = 0; jj < 16; ++jj) {
+                if ((uint32_t)jj * share < 16u) {
+                    const uint32_t t = (((uint32_t)jj * share + (uint32_t)rr) * 64u + (uint32_t)lane) * 4u;   // entry inside the tile
+                    const uint32_t pos = (uint32_t)tile_base + t;
+                    pe[jj] = (int)t < tile_len ? *reinterpret_cast<const int4*>(p.perm + (pos & g.fold_mask)) : make_int4(0, 0, 0, 0);
+                }
             }
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const uint32_t t = ((uint32_t)j * 64u + (uint32_t)lane) * 4u;
-                const uint32_t fb = ((uint32_t)tile_base + t) & ~g.fold_mask;       // first channel of the real row
-                const uint32_t ch[4] = {fb + pe[j].x, fb + pe[j].y, fb + pe[j].z, fb + pe[j].w};
-                uint32_t o[4];
+            for (int jj = 0; jj < 16; ++jj) {
+                if ((uint32_t)jj * share < 16u) {
+                    const uint32_t t = (((uint32_t)jj * share + (uint32_t)rr) * 64u + (uint32_t)lane) * 4u;
+                    const uint32_t fb = ((uint32_t)tile_base + t) & ~g.fold_mask;       // first channel of the real row
+                    const uint32_t ch[4] = {fb + pe[jj].x, fb + pe[jj].y, fb + pe[jj].z, fb + pe[jj].w};
+                    uint32_t o[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1);
-                *reinterpret_cast<uint2*>(tab + 2u * t) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+                    for (int e = 0; e < 4; ++e) o[e] = (granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1);
+                    *reinterpret_cast<uint2*>(tab + 2u * t) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
+                }
             }
         }
+        __syncthreads();      // the tables are complete
         const uint32_t base = (uint32_t)rr * g.row_bytes;
         if constexpr (!kHighK) {
 #pragma unroll
@@ -769,9 +777,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 }
             }
         }
-        // The zero slot of the second buffer lies in the last wave's table.  That wave clears it once
-        // it has read its offsets and before the barrier: a clear issued after the barrier could land
-        // behind another wave's row data on a launch whose code is still cold.
+        // The zero slot of the second buffer lies in the fourth table.  The last wave, the only reader
+        // of that table, clears the slot once it has its offsets and before the barrier: a clear issued
+        // after the barrier could land behind another wave's row data on a launch whose code is still cold.
         if (wave == NWAVES - 1 && lane < 4) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * lane) = 0u;
         __syncthreads();      // every wave has its offsets: the tables' place may be written
         if (drawing) draw();
