@@ -169,16 +169,16 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                     uint32_t pair = 0;
 #pragma unroll
                     for (int s = 0; s < 2; ++s) {
+                        // (an index past the end of the base meets a zero row of B: it is pointed at the
+                        //  a-value's first element, finite like all input, so that every read below is
+                        //  unconditional)
                         const int r = r_of(ks, 2 * e2 + s);
-                        uint32_t off = 0xFFFFu;
-                        if (r < MB) {
-                            const int pos = my_chunk * kChunkPos + a_of(al, ks) * MB + r;
-                            const int ch = p.perm[pos];
-                            const uint32_t cl = (uint32_t)(ch % kChunkPos);
-                            // (in units of two bytes: eight chunks of fp32 pass 64 KiB)
-                            off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 2) +
-                                  (kSwz ? ((cl >> 5) * 4u + (((cl >> 3) & 3u) ^ ((cl >> 7) & 3u))) * 8u + (cl & 7u) : cl);
-                        }
+                        const int pos = my_chunk * kChunkPos + a_of(al, ks) * MB + (r < MB ? r : 0);
+                        const int ch = p.perm[pos];
+                        const uint32_t cl = (uint32_t)(ch % kChunkPos);
+                        // (in units of two bytes: eight chunks of fp32 pass 64 KiB)
+                        const uint32_t off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 2) +
+                                             (kSwz ? ((cl >> 5) * 4u + (((cl >> 3) & 3u) ^ ((cl >> 7) & 3u))) * 8u + (cl & 7u) : cl);
                         pair |= off << (16 * s);
                     }
                     tab[(al * kKS + ks) * 4 + e2] = pair;
@@ -243,8 +243,8 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                     for (int e2 = 0; e2 < 4; ++e2) {
                         const uint32_t pair = tab[(al * kKS + ks) * 4 + e2];
                         const uint32_t o0 = pair & 0xFFFFu, o1 = pair >> 16;
-                        const uint32_t v0 = o0 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + 2u * o0);
-                        const uint32_t v1 = o1 == 0xFFFFu ? 0u : *reinterpret_cast<const uint16_t*>(row_stage + 2u * o1);
+                        const uint32_t v0 = *reinterpret_cast<const uint16_t*>(row_stage + 2u * o0);
+                        const uint32_t v1 = *reinterpret_cast<const uint16_t*>(row_stage + 2u * o1);
                         w[e2] = v0 | (v1 << 16);
                     }
                 }
