@@ -59,13 +59,16 @@ typedef enum {
     PERQ_FMT_FP4_TOKEN = 3
 } perq_fmt_t;
 
-/* Which rotation kernel runs.  AUTO picks the fastest one that covers the shape; the explicit
- * values exist so that the kernels can be compared with each other and each checked alone. */
+/* Which rotation kernel runs.  AUTO picks the fastest one that covers the shape (block sizes that
+ * are not powers of two, and powers of two above 4096 on rows of 8192, 16384 or 32768, have a
+ * matrix-core kernel of their own that only AUTO selects); the explicit values exist so that the
+ * two general kernels can be compared with each other and each checked alone. */
 typedef enum {
     PERQ_ALGO_AUTO = 0,
-    PERQ_ALGO_BUTTERFLY = 1,  /* register / cross-lane / LDS radix-2 butterflies; every shape */
-    PERQ_ALGO_MFMA = 2        /* X * H on the matrix cores for the low index bits; UNSUPPORTED
-                                 for shapes it does not cover */
+    PERQ_ALGO_BUTTERFLY = 1,  /* register / cross-lane / LDS radix-2 butterflies; every shape with a
+                                 power-of-two b */
+    PERQ_ALGO_MFMA = 2        /* X * H on the matrix cores for the low index bits (b <= 4096, d a
+                                 multiple of 512); UNSUPPORTED for shapes it does not cover */
 } perq_algo_t;
 
 /* Largest row width the kernels accept (elements). */
