@@ -132,7 +132,7 @@ perq_status_t perq_perm_zigzag(const float* stat, int32_t d, int32_t b, int32_t*
  *   else m/2 - 1 prime, = 1 mod 4:  [[0, 1^T], [1, Q]] with 0 -> [[1,-1],[-1,-1]] and
  *                                   e = +-1 -> e [[1,1],[1,-1]]                       (m = 28, 76)
  *   out   host, int8 [m][m], entries +-1; a row vector x is rotated as x H_m
- * INVALID_ARG when neither construction exists for m.  Needed offline to rotate the weights that
+ * INVALID_ARG when m is not 4t with t odd and above 1, or neither construction exists for it.  Needed offline to rotate the weights that
  * meet the activations (W~ = R~^T P^T W).
  */
 perq_status_t perq_hadamard_base(int32_t m, int8_t* out);

@@ -125,7 +125,7 @@ int legendre(int32_t v, int32_t q) {
 }  // namespace
 
 int hadamard_base_kind(int32_t m) {
-    if (m < 8 || m % 4 != 0) return 0;
+    if (m < 12 || m % 8 != 4) return 0;      // m = 4t with t odd and above 1 (a power of two has Sylvester's matrix)
     if (prime(m - 1) && (m - 1) % 4 == 3) return 1;
     if (prime(m / 2 - 1) && (m / 2 - 1) % 4 == 1) return 2;
     return 0;

@@ -126,7 +126,7 @@ def test_hadamard_base_matches_oracle_construction(m):
 
 
 def test_hadamard_base_rejects_orders_without_a_construction():
-    for m in (4, 10, 16, 92, 0, -12):       # 16: 15 is not prime, 7 = 3 mod 4
+    for m in (4, 10, 16, 24, 32, 92, 0, -12):   # 24 = 2 * 12 and 32 are not 4t with t odd; 92: 91 = 7 * 13, 45 = 9 * 5
         with pytest.raises(binding.PerqError) as ei:
             binding.perq_hadamard_base(m)
         assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
