@@ -550,7 +550,7 @@ def test_nonpo2_rotation_against_oracle(d, bs, with_perm):
 
 def test_nonpo2_structured_rows_and_many_rows():
     d, b = 14336, 14336
-    H28 = binding.perq_hadamard_base(28).astype(np.float64)
+    H28 = orc.paley_hadamard(28).astype(np.float64)
     # one-hot rows: every output has magnitude |c| / sqrt(b); row a*28 + r of H_512 (x) H_28
     T = 6
     x = np.zeros((T, d))
