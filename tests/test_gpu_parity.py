@@ -335,12 +335,16 @@ def test_w4a4_gemm_against_oracle_and_unrotated_product(T, N, d, b):
     ca, sa = binding.perq_permute_rotate_quant(xa, perm_t, b, "int4")
     cw, sw = binding.perq_permute_rotate_quant(wa, perm_t, b, "int4")
     out = binding.perq_w4a4_gemm_ref(ca, sa, cw, sw).cpu().numpy().astype(np.float64)
-    # (1) exactly the oracle's product of the library's own codes and scales
-    def signed(c):
-        n = parity.unpack_nibbles(c.cpu().numpy()).astype(np.int16)
-        return np.where(n >= 8, n - 16, n).astype(np.int8)
-    acc, want = orc.w4a4_matmul(signed(ca), sa.cpu().numpy(), signed(cw), sw.cpu().numpy())
-    assert np.all(np.abs(out - want) <= 4e-7 * np.abs(want) + 1e-30)
+    # (1) the integer product itself, on operands that the oracle quantized: its codes and scales go
+    # to the device, the library's product of them must equal the oracle's (exact sums, two fp32
+    # multiplications)
+    rot = orc.fwht_f64 if (b > 4096 and b & (b - 1) == 0) else orc.block_hadamard
+    ra, rw = orc.perq_apply(x_bits, perm, b, "int4", rotate=rot), orc.perq_apply(wt_bits, perm, b, "int4", rotate=rot)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    got = binding.perq_w4a4_gemm_ref(dev(ra["packed"]), dev(ra["scales"]), dev(rw["packed"]), dev(rw["scales"]))
+    acc, want = orc.w4a4_matmul(ra["codes"], ra["scales"], rw["codes"], rw["scales"])
+    got = got.cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - want) <= 4e-7 * np.abs(want) + 1e-30)
     # (2) it stands for X W: within the two operands' INT4 error bounds of the unrotated product
     X, Wt = orc.bf16_bits_to_f64(x_bits), orc.bf16_bits_to_f64(wt_bits)
     s_a, s_w = sa.cpu().numpy().astype(np.float64), sw.cpu().numpy().astype(np.float64)
