@@ -193,22 +193,22 @@ def main() -> int:
                                              "256 MB)" % (per_set / 1e6),
                    "device_copy_GBs": 2 * cp_src.numel() / (copy_ms * 1e-3) / 1e9}
 
-    # ---- self-check of the timed configuration on sampled rows --------------------------------
-    check = None
-    if not args.no_check:
-        import parity
-        rng = np.random.default_rng(0)
-        rows = np.unique(np.concatenate([np.arange(32), T - 1 - np.arange(32),
-                                         rng.choice(T, size=64, replace=False), wl.massive_rows[:8]]))
-        codes = outs[(args.steps - 1) % nsets][0][torch.from_numpy(rows).to(dev)].cpu().numpy()
-        sc = outs[(args.steps - 1) % nsets][1][torch.from_numpy(rows).to(dev)].cpu().numpy()
-        rep = parity.compare_apply(x_bits[rows], perm_np, b, fmt, codes, sc)
-        check = dict(rep.summary(), rows=int(rows.size), ok=rep.ok())
-
-    # ---- the oracle on the host cores, bounded sample --------------------------------------------
+    # ---- the oracle on the host cores, bounded sample (the only part of this file that runs it):
+    #      timed as the CPU baseline, and the timed launch configuration is compared with it on
+    #      sampled rows ---------------------------------------------------------------------------
     cpu = None
+    check = None
     if not args.no_cpu_baseline:
         from oracle import perq_oracle as orc
+        if not args.no_check:
+            import parity
+            rng = np.random.default_rng(0)
+            rows = np.unique(np.concatenate([np.arange(32), T - 1 - np.arange(32),
+                                             rng.choice(T, size=64, replace=False), wl.massive_rows[:8]]))
+            codes = outs[(args.steps - 1) % nsets][0][torch.from_numpy(rows).to(dev)].cpu().numpy()
+            sc = outs[(args.steps - 1) % nsets][1][torch.from_numpy(rows).to(dev)].cpu().numpy()
+            rep = parity.compare_apply(x_bits[rows], perm_np, b, fmt, codes, sc)
+            check = dict(rep.summary(), rows=int(rows.size), ok=rep.ok())
         try:
             from threadpoolctl import threadpool_info
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
