@@ -118,9 +118,13 @@ perq_status_t perq_massdiff_perm(const float* colabs_mean, int32_t d, int32_t b,
  *   perq_perm_zigzag  the paper only names the strategy; taken: rank r of that order goes to block
  *                     r mod n on even rounds floor(r/n) and to block n-1-(r mod n) on odd rounds
  *                     (n = d/b), each block in arrival order.
+ *   perq_perm_random  the ablation's random permutation, reproducible: Fisher-Yates from the top down
+ *                     (i = d-1 .. 1, swap positions i and floor(u (i+1) / 2^64)), u the successive
+ *                     outputs of SplitMix64 (Steele, Lea, Flood 2014) started at `seed`.  No stat.
  */
 perq_status_t perq_perm_sorted(const float* stat, int32_t d, int32_t* perm_out);
 perq_status_t perq_perm_zigzag(const float* stat, int32_t d, int32_t b, int32_t* perm_out);
+perq_status_t perq_perm_random(int32_t d, uint64_t seed, int32_t* perm_out);
 
 /*
  * The 4t-dimensional base matrix of the rotation for a block size that is not a power of two

@@ -47,7 +47,7 @@ __all__ = [
     "paley_hadamard", "hadamard_factors", "hadamard_matrix", "nonpo2_rotation_counted",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
     "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
-    "merge_into_weights", "w4a4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics",
+    "merge_into_weights", "w4a4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics", "splitmix64", "perm_random",
     "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
     "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
 ]
@@ -550,6 +550,29 @@ def perm_zigzag(stat, b: int) -> np.ndarray:
         rnd, pos = divmod(r, n)
         blocks[pos if rnd % 2 == 0 else n - 1 - pos].append(int(ch))
     return np.array([i for blk in blocks for i in blk], dtype=np.int32)
+
+
+def splitmix64(seed: int, k: int) -> int:
+    """k-th output (k = 0, 1, ...) of the SplitMix64 generator started at `seed` (Steele, Lea and
+    Flood, "Fast splittable pseudorandom number generators", 2014): the state advances by the
+    golden-ratio constant, the output is the state through two xor-shift-multiply rounds."""
+    mask = (1 << 64) - 1
+    z = (seed + (k + 1) * 0x9E3779B97F4A7C15) & mask
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+    return z ^ (z >> 31)
+
+
+def perm_random(d: int, seed: int) -> np.ndarray:
+    """The ablation's random permutation, made reproducible.  The paper draws it with an unnamed
+    generator; reading: a Fisher-Yates shuffle of the identity from the top down, i = d-1 .. 1,
+    swapping position i with position floor(u * (i + 1) / 2^64), u the (d-1-i)-th SplitMix64 output
+    for the seed.  Every channel is equally likely at every position up to 2^-64 * d."""
+    perm = np.arange(d, dtype=np.int64)
+    for i in range(d - 1, 0, -1):
+        j = (splitmix64(seed, d - 1 - i) * (i + 1)) >> 64
+        perm[i], perm[j] = perm[j], perm[i]
+    return perm.astype(np.int32)
 
 
 def block_diagnostics(x_bits: np.ndarray, perm, b: int) -> np.ndarray:

@@ -25,7 +25,7 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
            "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
-           "perq_hadamard_base"]
+           "perq_hadamard_base", "perq_perm_random"]
 
 _lib = None
 
@@ -75,6 +75,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_perm_zigzag.restype = ctypes.c_int
     lib.perq_hadamard_base.argtypes = [i32, vp]
     lib.perq_hadamard_base.restype = ctypes.c_int
+    lib.perq_perm_random.argtypes = [i32, ctypes.c_uint64, vp]
+    lib.perq_perm_random.restype = ctypes.c_int
     lib.perq_block_diagnostics.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
     lib.perq_block_diagnostics.restype = ctypes.c_int
     _lib = lib
@@ -125,6 +127,14 @@ def perq_perm_sorted(stat: np.ndarray) -> np.ndarray:
     _check(load().perq_perm_sorted(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], perm.ctypes.data_as(ctypes.c_void_p)),
            "perq_perm_sorted")
     return perm
+
+
+def perq_perm_random(d: int, seed: int) -> np.ndarray:
+    """Reproducible random permutation of d channels (host)."""
+    perm = np.empty(max(int(d), 1), dtype=np.int32)
+    _check(load().perq_perm_random(int(d), int(seed) & ((1 << 64) - 1), perm.ctypes.data_as(ctypes.c_void_p)),
+           "perq_perm_random")
+    return perm[:max(int(d), 0)]
 
 
 def perq_hadamard_base(m: int) -> np.ndarray:

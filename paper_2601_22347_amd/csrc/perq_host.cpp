@@ -87,6 +87,23 @@ extern "C" perq_status_t perq_perm_zigzag(const float* stat, int32_t d, int32_t 
     return PERQ_OK;
 }
 
+extern "C" perq_status_t perq_perm_random(int32_t d, uint64_t seed, int32_t* perm_out) {
+    if (perm_out == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < d; ++i) perm_out[i] = i;
+    uint64_t state = seed;
+    for (int32_t i = d - 1; i > 0; --i) {
+        // SplitMix64: next state, then two xor-shift-multiply rounds
+        state += 0x9E3779B97F4A7C15ull;
+        uint64_t z = state;
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        z ^= z >> 31;
+        const uint64_t j = (uint64_t)(((unsigned __int128)z * (uint64_t)(i + 1)) >> 64);
+        std::swap(perm_out[i], perm_out[j]);
+    }
+    return PERQ_OK;
+}
+
 extern "C" perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d) {
     if (perm_host == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
     std::vector<uint8_t> seen(d, 0);

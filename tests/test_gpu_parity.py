@@ -404,7 +404,7 @@ def test_block_diagnostics_against_oracle(T, d, bs):
 
 
 def test_calibrated_permutations_ranked_by_the_bound():
-    """MassDiff against identity / absmax / ZigZag on the calibrated synthetic law: the mean
+    """MassDiff against identity / random / absmax / ZigZag on the calibrated synthetic law: the mean
     Proposition 2 bound over apply tokens, from the device diagnostics."""
     torch = _torch()
     wl = synth.llama1b_down()
@@ -414,7 +414,7 @@ def test_calibrated_permutations_ranked_by_the_bound():
     amx = binding.perq_colabs_absmax(cal).cpu().numpy()
     x = binding.bits_to_device(wl.apply_rows(0, 512))
     perms = {"identity": None, "massdiff": binding.perq_massdiff_perm(a, b), "absmax": binding.perq_perm_sorted(amx),
-             "zigzag": binding.perq_perm_zigzag(amx, b)}
+             "zigzag": binding.perq_perm_zigzag(amx, b), "random": binding.perq_perm_random(wl.d, 2026)}
     bound = {}
     for name, pm in perms.items():
         pt = None if pm is None else torch.from_numpy(pm).cuda()
@@ -423,6 +423,7 @@ def test_calibrated_permutations_ranked_by_the_bound():
     print("mean normalised Prop. 2 bound:", bound, flush=True)
     assert bound["massdiff"] < bound["identity"] and bound["massdiff"] <= bound["zigzag"] * 1.02
     assert bound["absmax"] > bound["massdiff"]            # sorting concentrates the heavy channels in one block
+    assert bound["random"] >= bound["massdiff"]           # a shuffle spreads them by chance only
 
 
 # ---- the ticket counters under concurrency and graph replay ------------------------------------------

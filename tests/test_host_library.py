@@ -130,3 +130,13 @@ def test_hadamard_base_rejects_orders_without_a_construction():
         with pytest.raises(binding.PerqError) as ei:
             binding.perq_hadamard_base(m)
         assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
+
+
+def test_random_permutation_matches_oracle_generator():
+    for d, seed in [(1, 0), (2, 7), (33, 1), (4096, 123456789), (14336, 2 ** 63 + 5)]:
+        got = binding.perq_perm_random(d, seed)
+        assert np.array_equal(got, orc.perm_random(d, seed))
+        assert binding.perq_perm_validate(got)
+    with pytest.raises(binding.PerqError) as ei:
+        binding.perq_perm_random(0, 1)
+    assert ei.value.status == binding.PERQ_ERR_INVALID_ARG

@@ -148,3 +148,28 @@ def test_block_diagnostics_bounds_and_special_cases():
     r = np.zeros((1, 64)); r[0, 10] = -2.0
     D = orc.block_diagnostics(synth.f64_to_bf16_bits(r), None, 16)
     assert np.allclose(D[0], [2.0, 2.0, 2.0, 0.5])
+
+
+# ---- reproducible random permutation (the ablation's "Random" row) ---------------------------------
+def test_splitmix64_reference_outputs():
+    # first outputs of the published reference implementation for seed 0
+    assert [orc.splitmix64(0, k) for k in range(3)] == [0xE220A8397B1DCDAF, 0x6E789E6AA1B965F4, 0x06C45D188009454F]
+
+
+def test_random_permutation_is_a_uniform_looking_bijection():
+    for d, seed in [(1, 5), (2, 0), (17, 1), (256, 2), (4096, 3)]:
+        p = orc.perm_random(d, seed)
+        assert p.dtype == np.int32 and np.array_equal(np.sort(p), np.arange(d))
+        assert np.array_equal(p, orc.perm_random(d, seed))
+    # d = 2: position 1 is swapped with floor(u * 2 / 2^64), i.e. kept iff the top bit of u is set
+    for seed in range(20):
+        kept = orc.splitmix64(seed, 0) >> 63
+        assert list(orc.perm_random(2, seed)) == ([0, 1] if kept else [1, 0])
+    # over many seeds every channel lands on every position about equally often (d = 8: 64 cells,
+    # 4000 shuffles, expected 500 each; chi-square with 49 degrees of freedom stays far below 120)
+    counts = np.zeros((8, 8))
+    for seed in range(4000):
+        p = orc.perm_random(8, seed)
+        counts[np.arange(8), p] += 1
+    chi2 = ((counts - 500.0) ** 2 / 500.0).sum()
+    assert chi2 < 120.0, chi2
