@@ -1,7 +1,8 @@
 // Rotation with a block size that is not a power of two: b = 2^k' * MB, MB = 4t the order of the
 // base matrix (Appendix A.1: 28 for the Llama3-8B width 14336 = 2^9 * 28; 12 and 76 for the Qwen3
-// widths), then the same quantizers as the other kernels.  One translation unit per MB includes
-// this file and instantiates launch_npo2_base<MB>.
+// widths), then the same quantizers as the other kernels.  With Sylvester's H_32 in the place of the
+// base the same kernel takes power-of-two blocks above 4096.  One translation unit per MB includes
+// this file and instantiates launch_npo2_base_impl<MB>.
 //
 // A block of the (permuted) row is a [2^k'][MB] array Z (position a*MB + r); the rotation is
 // H_{2^k'} Z H_MB / sqrt(b).
@@ -15,10 +16,10 @@
 //   2. The rest of the Sylvester factor inside a wave's chunk: the a-bits held in the accumulator
 //      index are in-register butterflies, the bit that separates the half-waves is one swap stage.
 //      Bits above the chunk join different waves' chunks: every wave leaves its chunk in LDS as
-//      fp32 in position order, and after a barrier each thread collects 8 (or 16) consecutive
-//      positions of every chunk of its row and finishes the remaining one or two stages in registers.
-//   3. In that layout (8 or 16 consecutive outputs per thread and chunk) the row statistics, the
-//      rounding and the nibble packing are those of the other kernels.
+//      fp32 in position order, and after a barrier each thread collects 8 consecutive positions
+//      of every chunk of its row and finishes the remaining one to three stages in registers.
+//   3. In that layout (8 consecutive outputs per thread and chunk: one dword of codes) the row
+//      statistics, the rounding and the nibble packing are those of the other kernels.
 //
 // A workgroup of four waves handles 4 chunks per iteration: one row of 4 chunks, two of 2, four of 1;
 // rows of 8 chunks (d = 28672 and 32768 for the bases 28 and 32) take workgroups of eight waves.
@@ -52,7 +53,7 @@ template <> struct Base<28> { static constexpr int kA0 = 1, kKS = 2, kNT = 1, kA
 template <> struct Base<12> { static constexpr int kA0 = 2, kKS = 2, kNT = 1, kAL = 4; };
 template <> struct Base<76> { static constexpr int kA0 = 1, kKS = 5, kNT = 3, kAL = 1; };
 // Sylvester's H_32 as the base: power-of-two blocks above what the 4096-wide tiles of the other
-// matrix-core kernel hold (b = 8192, 16384 on d = 8192, 16384) take the same path.
+// matrix-core kernel hold (b = 8192 .. 32768 on d = 8192, 16384, 32768) take the same path.
 template <> struct Base<32> { static constexpr int kA0 = 1, kKS = 2, kNT = 1, kAL = 4; };
 
 // Waves per workgroup = chunks per workgroup iteration: four, or eight for rows of eight chunks.
@@ -65,7 +66,7 @@ struct Npo2Geom {
     float norm256;       // fl32(256 / sqrt(b))
 };
 
-// NCH = chunks per row; rows per iteration = 4 / NCH.
+// NCH = chunks per row (1, 2, 4, 8); rows per iteration = waves / NCH.
 // STG >= 0: the block spans whole chunks: every in-chunk stage and STG stages across chunks,
 // unconditionally.  STG = -1: a smaller block, k' is read at run time (a stage that may or may
 // not run costs a register copy per element on top of its two operations).
@@ -79,7 +80,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kTileA = 32 * kA0;                      // a-values per row tile
     constexpr int kChunkA = kTileA * kAL;                 // a-values per wave chunk: 128, 256, 32
     constexpr int kChunkBits = (kChunkA == 32 ? 5 : (kChunkA == 128 ? 7 : 8));
-    constexpr int kChunkPos = kChunkA * MB;               // 3584, 3072, 2432
+    constexpr int kChunkPos = kChunkA * MB;               // 3584, 3072, 2432; 4096 for H_32
     // consecutive positions per thread and chunk in phase 2 (16 was measured too: no faster where
     // it fills every lane, and slower with a gather table in registers)
     constexpr int kRun = 8;
