@@ -562,17 +562,22 @@ hipError_t launch_perm(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, dim
 // The caller has checked npo2_supports(p) and that b / MB is a power of two.
 template <int MB>
 hipError_t launch_npo2_base_impl(const ApplyParams& p, int out_kind, hipStream_t stream) {
-    Npo2Geom<MB> g;
-    constexpr int kRowsPad = sizeof(g.hrow) / sizeof(g.hrow[0]);
-    const int kind = MB == 32 ? 0 : hadamard_base_kind(MB);
-    for (int r = 0; r < kRowsPad; ++r)
-        for (int w = 0; w < Base<MB>::kNT; ++w) {
-            uint32_t bits = 0;
-            if (r < MB)
-                for (int c = 0; c < 32 && 32 * w + c < MB; ++c)
-                    if (base_entry<MB>(kind, r, 32 * w + c) < 0) bits |= 1u << c;
-            g.hrow[r][w] = bits;
-        }
+    // the sign bits of the base matrix are worked out once per process
+    static const Npo2Geom<MB> base_bits = [] {
+        Npo2Geom<MB> t{};
+        constexpr int kRowsPad = sizeof(t.hrow) / sizeof(t.hrow[0]);
+        const int kind = MB == 32 ? 0 : hadamard_base_kind(MB);
+        for (int r = 0; r < kRowsPad; ++r)
+            for (int w = 0; w < Base<MB>::kNT; ++w) {
+                uint32_t bits = 0;
+                if (r < MB)
+                    for (int c = 0; c < 32 && 32 * w + c < MB; ++c)
+                        if (base_entry<MB>(kind, r, 32 * w + c) < 0) bits |= 1u << c;
+                t.hrow[r][w] = bits;
+            }
+        return t;
+    }();
+    Npo2Geom<MB> g = base_bits;
     g.kp = 0;
     while ((MB << g.kp) < p.b) ++g.kp;
     g.norm256 = (float)(256.0 / std::sqrt((double)p.b));
