@@ -211,6 +211,24 @@ perq_status_t perq_w4a4_gemm_ref(const uint8_t* a_codes, const float* a_scales, 
                                  const uint8_t* w_codes, const float* w_scales, int32_t N, int32_t d,
                                  float* out, int64_t ldo, void* hip_stream);
 
+/*
+ * The same for PERQ_FMT_MXFP4 operands (Appendix B, Eq. 5): both are outputs of
+ * perq_permute_rotate_quant, e2m1 codes with one e8m0 byte per 32.
+ *
+ *   out[t, n] = sum over 32-groups g of 2^(Ea[t,g] - 127) 2^(Ew[n,g] - 127) sum_{i in g} a[t,i] w[n,i]
+ *
+ *   a_codes  device, uint8 [T, d/2], 16-byte aligned;   a_scales  device, uint8 [T, d/32]
+ *   w_codes  device, uint8 [N, d/2], 16-byte aligned;   w_scales  device, uint8 [N, d/32]
+ *   out      device, float [T, ldo], ldo >= N
+ * Runs on gfx950's scaled matrix instruction (v_mfma_scale_f32_32x32x64_f8f6f4, fp4 x fp4), which
+ * takes a 32-group of packed codes and its scale byte exactly as the fused path writes them: the
+ * products are exact, the sums are fp32 in the unit's own order.  A checker of the layout, not a
+ * tuned GEMM.  d % 32 == 0; T == 0 or N == 0 does nothing.
+ */
+perq_status_t perq_w4a4_mxfp4_gemm_ref(const uint8_t* a_codes, const uint8_t* a_scales, int64_t T,
+                                       const uint8_t* w_codes, const uint8_t* w_scales, int32_t N, int32_t d,
+                                       float* out, int64_t ldo, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

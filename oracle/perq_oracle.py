@@ -47,7 +47,7 @@ __all__ = [
     "paley_hadamard", "hadamard_factors", "hadamard_matrix", "nonpo2_rotation_counted",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
     "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
-    "merge_into_weights", "w4a4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics", "splitmix64", "perm_random",
+    "merge_into_weights", "w4a4_matmul", "w4a4_mxfp4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics", "splitmix64", "perm_random",
     "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
     "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
 ]
@@ -605,6 +605,13 @@ def w4a4_matmul(codes_a: np.ndarray, s_a: np.ndarray, codes_w: np.ndarray, s_w: 
     (Eq. 4 with z = 0 on both operands).  Returns (integer sums int64 [T, N], out float64)."""
     acc = codes_a.astype(np.int64) @ codes_w.astype(np.int64).T
     return acc, acc.astype(np.float64) * np.asarray(s_a, np.float64)[:, None] * np.asarray(s_w, np.float64)[None, :]
+
+
+def w4a4_mxfp4_matmul(codes_a: np.ndarray, E_a: np.ndarray, codes_w: np.ndarray, E_w: np.ndarray) -> np.ndarray:
+    """out[t, n] = sum_i a[t, i] w[n, i] with both operands decoded from MXFP4 (Eq. 5: e2m1 element
+    times 2^(E - 127) of its 32-group); float64 [T, N].  Every product and every partial sum of a
+    realistic size is exact in float64, so this is the value itself."""
+    return dequant_mxfp4(codes_a, E_a) @ dequant_mxfp4(codes_w, E_w).T
 
 
 # ----------------------------------------------------------------------------------------

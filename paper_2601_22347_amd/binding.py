@@ -25,7 +25,7 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
            "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
-           "perq_hadamard_base", "perq_perm_random"]
+           "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref"]
 
 _lib = None
 
@@ -67,6 +67,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_permute_rotate_f32.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, vp, vp]
     lib.perq_w4a4_gemm_ref.argtypes = [vp, vp, i64, vp, vp, i32, i32, vp, i64, vp]
     lib.perq_w4a4_gemm_ref.restype = ctypes.c_int
+    lib.perq_w4a4_mxfp4_gemm_ref.argtypes = [vp, vp, i64, vp, vp, i32, i32, vp, i64, vp]
+    lib.perq_w4a4_mxfp4_gemm_ref.restype = ctypes.c_int
     lib.perq_colabs_absmax.argtypes = [vp, i64, i32, i64, vp, vp, sz, vp]
     lib.perq_colabs_absmax.restype = ctypes.c_int
     lib.perq_perm_sorted.argtypes = [vp, i32, vp]
@@ -251,6 +253,24 @@ def perq_w4a4_gemm_ref(a_codes, a_scales, w_codes, w_scales, out=None, stream=No
     st = load().perq_w4a4_gemm_ref(_dev_ptr(a_codes), _dev_ptr(a_scales), T, _dev_ptr(w_codes), _dev_ptr(w_scales),
                                    N, d, _dev_ptr(out), out.stride(0) if T else N, _stream_ptr(stream))
     _check(st, "perq_w4a4_gemm_ref")
+    return out
+
+
+def perq_w4a4_mxfp4_gemm_ref(a_codes, a_scales, w_codes, w_scales, out=None, stream=None):
+    """The same product for MXFP4 operands (CUDA uint8 codes [T, d/2] / [N, d/2], uint8 scale bytes
+    [T, d/32] / [N, d/32]); returns CUDA float32 [T, N]."""
+    import torch
+    T, N, d = a_codes.shape[0], w_codes.shape[0], a_codes.shape[1] * 2
+    if w_codes.shape[1] * 2 != d or not a_codes.is_contiguous() or not w_codes.is_contiguous():
+        raise ValueError("a_codes [T, d/2] and w_codes [N, d/2] must be contiguous with the same d")
+    if not a_scales.is_contiguous() or not w_scales.is_contiguous():
+        raise ValueError("scale bytes must be contiguous")
+    if out is None:
+        out = torch.empty((T, N), dtype=torch.float32, device=a_codes.device)
+    st = load().perq_w4a4_mxfp4_gemm_ref(_dev_ptr(a_codes), _dev_ptr(a_scales), T, _dev_ptr(w_codes),
+                                         _dev_ptr(w_scales), N, d, _dev_ptr(out), out.stride(0) if T else N,
+                                         _stream_ptr(stream))
+    _check(st, "perq_w4a4_mxfp4_gemm_ref")
     return out
 
 

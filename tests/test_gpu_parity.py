@@ -359,6 +359,39 @@ def test_w4a4_gemm_against_oracle_and_unrotated_product(T, N, d, b):
     assert np.all(np.abs(y @ wy.T - ref) <= 1e-5 * ny[:, None] * nw[None, :] * 2)
 
 
+@pytest.mark.parametrize("T,N,d,b", [(70, 50, 256, 32), (33, 130, 4096, 128), (5, 3, 1024, 1024), (9, 40, 3584, 896),
+                                     (37, 33, 96, 32)])
+def test_w4a4_mxfp4_gemm_on_the_scaled_matrix_unit(T, N, d, b):
+    """The packed MXFP4 output (codes and scale bytes) goes into gfx950's scaled fp4 matrix instruction
+    as it is; the product equals the oracle's product of the decoded operands."""
+    torch = _torch()
+    rng = np.random.default_rng(T * 7 + N + d)
+    x_bits = synth.f64_to_bf16_bits(rng.standard_t(5, size=(T, d)) * np.exp(rng.uniform(-6, 6, size=(T, 1))))
+    wt_bits = synth.f64_to_bf16_bits(rng.standard_normal((N, d)) * 0.05)        # rows of W^T
+    perm = rng.permutation(d).astype(np.int32)
+    # (1) the product itself, on operands that the oracle quantized
+    ra, rw = orc.perq_apply(x_bits, perm, b, "mxfp4"), orc.perq_apply(wt_bits, perm, b, "mxfp4")
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    got = binding.perq_w4a4_mxfp4_gemm_ref(dev(ra["packed"]), dev(ra["scales"]), dev(rw["packed"]), dev(rw["scales"]))
+    got = got.cpu().numpy().astype(np.float64)
+    want = orc.w4a4_mxfp4_matmul(ra["codes"], ra["scales"], rw["codes"], rw["scales"])
+    da, dw = np.abs(orc.dequant_mxfp4(ra["codes"], ra["scales"])), np.abs(orc.dequant_mxfp4(rw["codes"], rw["scales"]))
+    # exact products, fp32 sums in the unit's own order: d rounding errors of 2^-24 on the sum of magnitudes
+    assert np.all(np.abs(got - want) <= d * 2.0 ** -24 * (da @ dw.T) + 1e-37)
+    # (2) end to end on the library's own output: it stands for X W within the format's error
+    xa, wa = binding.bits_to_device(x_bits), binding.bits_to_device(wt_bits)
+    perm_t = torch.from_numpy(perm).cuda()
+    ca, sa = binding.perq_permute_rotate_quant(xa, perm_t, b, "mxfp4")
+    cw, sw = binding.perq_permute_rotate_quant(wa, perm_t, b, "mxfp4")
+    out = binding.perq_w4a4_mxfp4_gemm_ref(ca, sa, cw, sw).cpu().numpy().astype(np.float64)
+    X, Wt = orc.bf16_bits_to_f64(x_bits), orc.bf16_bits_to_f64(wt_bits)
+    # an element is off by at most a quarter of its group's maximum (half a step of the coarsest e2m1
+    # interval), so each operand keeps most of its norm; a loose bound is enough to catch a wrong layout
+    ny, nw = np.linalg.norm(X, axis=1), np.linalg.norm(Wt, axis=1)
+    assert np.all(np.abs(out - X @ Wt.T) <= 0.6 * ny[:, None] * nw[None, :])
+    assert np.corrcoef(out.ravel(), (X @ Wt.T).ravel())[0, 1] > 0.97
+
+
 def test_w4a4_gemm_argument_checks():
     torch = _torch()
     a = torch.zeros((4, 16), dtype=torch.uint8, device="cuda")

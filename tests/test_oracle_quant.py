@@ -368,3 +368,22 @@ def test_w4a4_end_to_end_error_is_quantisation_error_only():
     ny, nw = np.linalg.norm(Y, axis=1), np.linalg.norm(Wt, axis=1)
     bound = ey[:, None] * nw[None, :] + ny[:, None] * ew[None, :] + ey[:, None] * ew[None, :]
     assert np.all(np.abs(out - X @ W) <= bound * (1 + 1e-12))
+
+
+def test_mxfp4_product_of_hand_decoded_operands():
+    # two rows of 32 against one: codes decoded by hand from the e2m1 definition (sign, 2-bit exponent
+    # with bias 1, 1 mantissa bit; exponent field 0 is subnormal: 0 or 0.5), group scales 2^(E-127)
+    def e2m1(c):
+        s, e, m = (c >> 3) & 1, (c >> 1) & 3, c & 1
+        v = (0.5 * m) if e == 0 else (1.0 + 0.5 * m) * 2.0 ** (e - 1)
+        return -v if s else v
+    rng = np.random.default_rng(4)
+    ca, cw = rng.integers(0, 16, size=(2, 64)), rng.integers(0, 16, size=(1, 64))
+    Ea, Ew = np.array([[120, 131], [127, 125]]), np.array([[126, 129]])
+    want = np.zeros((2, 1))
+    for t in range(2):
+        for i in range(64):
+            want[t, 0] += e2m1(int(ca[t, i])) * 2.0 ** (int(Ea[t, i // 32]) - 127) * \
+                          e2m1(int(cw[0, i])) * 2.0 ** (int(Ew[0, i // 32]) - 127)
+    got = orc.w4a4_mxfp4_matmul(ca.astype(np.uint8), Ea.astype(np.uint8), cw.astype(np.uint8), Ew.astype(np.uint8))
+    assert np.array_equal(got, want)
