@@ -54,6 +54,7 @@ struct MfmaGeom {
     uint32_t ctr_set;    // which set of ticket counters this launch draws from
     uint32_t dynamic;    // 1: units dealt at run time through the ticket counters; 0: fixed stride
     uint32_t fold_mask;  // rows folded into 4096-wide ones: width of a real row - 1; else all ones
+    int32_t row_c_bits;  // low bits of c = lane & 31 that stay inside one real row: 5, or 2..4 when folded
 };
 
 // Ticket counters of the run-time row schedule: kWorkSets sets (consecutive launches rotate through
@@ -501,12 +502,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     m[0] = absmax(v);
                 }
 #pragma unroll
+                // (folded rows, low-K modes only: a real row is 4, 8 or 16 neighbouring values of c and
+                //  both half-waves, so the exchange stops at the row's edge)
                 for (int j = 0; j < kRed; ++j) {
                     m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
                     m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
-                    m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
-                    m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
-                    m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
+                    if (g.row_c_bits > 2) m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
+                    if (g.row_c_bits > 3) m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
+                    if (g.row_c_bits > 4) m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
                     m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
                 }
                 if (!wave_local) {
@@ -605,14 +608,19 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                         for (int q = 0; q < kQ; ++q)
                             if ((c & 1) == 0 && qvalid[q]) srow[hk_run(q) >> 5] = (uint8_t)(ebytes >> (8 * q));
                     }
-                } else if constexpr (OUT == OUT_INT4_ASYM) {
-                    if (lane == 0 && tile_base == 0)
-                        static_cast<float2*>(p.scales)[row] =
-                            make_float2((float)((double)row_max * p.inv_15sqrt_b), (float)row_zero);
                 } else {
-                    if (lane == 0 && tile_base == 0)
-                        static_cast<float*>(p.scales)[row] =
-                            (float)((double)row_max * (OUT == OUT_INT4 ? p.inv_7sqrt_b : p.inv_6sqrt_b));
+                    // one scale per real row: the first lane of the row writes it (a folded tile holds
+                    // 32 >> row_c_bits rows)
+                    const int in_row = c & ((1 << g.row_c_bits) - 1);
+                    const int64_t real_row = (row << (5 - g.row_c_bits)) + (c >> g.row_c_bits);
+                    if (in_row == 0 && h == 0 && tile_base == 0) {
+                        if constexpr (OUT == OUT_INT4_ASYM)
+                            static_cast<float2*>(p.scales)[real_row] =
+                                make_float2((float)((double)row_max * p.inv_15sqrt_b), (float)row_zero);
+                        else
+                            static_cast<float*>(p.scales)[real_row] =
+                                (float)((double)row_max * (OUT == OUT_INT4 ? p.inv_7sqrt_b : p.inv_6sqrt_b));
+                    }
                 }
             }
         }
@@ -870,6 +878,9 @@ hipError_t launch_mfma_st(const ApplyParams& p, uint32_t fold_mask, hipStream_t 
     g.ctr_set = 0;
     g.dynamic = 0;
     g.fold_mask = fold_mask;
+    g.row_c_bits = 5;
+    if (fold_mask != 0xFFFFFFFFu)
+        for (g.row_c_bits = 2; (128u << g.row_c_bits) < fold_mask + 1u; ++g.row_c_bits) {}
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
     auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
@@ -922,8 +933,14 @@ bool mfma_supports(const ApplyParams& p) {
 // whatever d is): blocks and 32-groups do not straddle rows, and codes, e8m0 bytes and fp32 outputs
 // of consecutive rows are contiguous, so only the operand addresses through `perm` know about it.
 // Not for the per-token scale, which needs one maximum per real row.
+// Rows of 512, 1024 or 2048 stored back to back are taken as 4096-wide ones.  The formats with one
+// scale per token need the row's extremes: their exchange between lanes follows the real rows in the
+// modes where a lane's values lie inside one row (b <= 512).
 static bool folds(const ApplyParams& p, int out_kind) {
-    return (out_kind == OUT_MXFP4 || out_kind == OUT_F32) && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 && p.T % (kTile / p.d) == 0;
+    const bool per_token = out_kind == OUT_INT4 || out_kind == OUT_INT4_ASYM || out_kind == OUT_FP4_TOKEN;
+    if (per_token && p.b > 512) return false;
+    return out_kind != OUT_DIAG && p.d >= 512 && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 &&
+           p.T % (kTile / p.d) == 0;
 }
 
 bool mfma_preferred(const ApplyParams& p, int out_kind) {

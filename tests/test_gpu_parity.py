@@ -273,6 +273,11 @@ TOKEN_FORMAT_SHAPES = [
     (7, 8192, [32, 2048, 8192]),
     (5, 14336, [128, 2048]),                 # ragged last tile: absent sub-blocks must not enter min / max
     (4, 20480, [256, 4096]),
+    # narrow rows stored back to back, T a multiple of 4096 / d: folded into 4096-wide ones for b <= 512
+    # (the row extremes are then exchanged inside 4, 8 or 16 lanes of a half-wave pair), not folded above
+    (24, 2048, [32, 128, 512, 1024, 2048]),
+    (40, 1024, [16, 64, 256, 1024]),
+    (64, 512, [32, 128, 512]),
 ]
 
 
