@@ -55,6 +55,7 @@ struct MfmaGeom {
     uint32_t dynamic;    // 1: units dealt at run time through the ticket counters; 0: fixed stride
     uint32_t fold_mask;  // rows folded into 4096-wide ones: width of a real row - 1; else all ones
     int32_t row_c_bits;  // low bits of c = lane & 31 that stay inside one real row: 5, or 2..4 when folded
+    int32_t row_per_half; // 1: folded rows of 2048 in the high-K modes, one real row per half-wave
 };
 
 // Ticket counters of the run-time row schedule: kWorkSets sets (consecutive launches rotate through
@@ -510,7 +511,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     if (g.row_c_bits > 2) m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
                     if (g.row_c_bits > 3) m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
                     if (g.row_c_bits > 4) m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
-                    m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+                    if (!g.row_per_half) m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
                 }
                 if (!wave_local) {
                     // extremes across the row's waves; scratch alternates with the group parity so
@@ -612,8 +613,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     // one scale per real row: the first lane of the row writes it (a folded tile holds
                     // 32 >> row_c_bits rows)
                     const int in_row = c & ((1 << g.row_c_bits) - 1);
-                    const int64_t real_row = (row << (5 - g.row_c_bits)) + (c >> g.row_c_bits);
-                    if (in_row == 0 && h == 0 && tile_base == 0) {
+                    const int64_t real_row = g.row_per_half ? 2 * row + h : (row << (5 - g.row_c_bits)) + (c >> g.row_c_bits);
+                    if (in_row == 0 && (h == 0 || g.row_per_half) && tile_base == 0) {
                         if constexpr (OUT == OUT_INT4_ASYM)
                             static_cast<float2*>(p.scales)[real_row] =
                                 make_float2((float)((double)row_max * p.inv_15sqrt_b), (float)row_zero);
@@ -879,8 +880,11 @@ hipError_t launch_mfma_st(const ApplyParams& p, uint32_t fold_mask, hipStream_t 
     g.dynamic = 0;
     g.fold_mask = fold_mask;
     g.row_c_bits = 5;
-    if (fold_mask != 0xFFFFFFFFu)
-        for (g.row_c_bits = 2; (128u << g.row_c_bits) < fold_mask + 1u; ++g.row_c_bits) {}
+    g.row_per_half = 0;
+    if (fold_mask != 0xFFFFFFFFu) {
+        if (STAGES >= 5) g.row_per_half = 1;        // (high-K modes fold rows of 2048 only, see folds())
+        else for (g.row_c_bits = 2; (128u << g.row_c_bits) < fold_mask + 1u; ++g.row_c_bits) {}
+    }
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
     auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
@@ -934,11 +938,13 @@ bool mfma_supports(const ApplyParams& p) {
 // of consecutive rows are contiguous, so only the operand addresses through `perm` know about it.
 // Not for the per-token scale, which needs one maximum per real row.
 // Rows of 512, 1024 or 2048 stored back to back are taken as 4096-wide ones.  The formats with one
-// scale per token need the row's extremes: their exchange between lanes follows the real rows in the
-// modes where a lane's values lie inside one row (b <= 512).
+// scale per token need the row's extremes: their exchange between lanes follows the real rows where a
+// lane's values lie inside one row (b <= 512, and rows of 2048 for b >= 1024).
 static bool folds(const ApplyParams& p, int out_kind) {
     const bool per_token = out_kind == OUT_INT4 || out_kind == OUT_INT4_ASYM || out_kind == OUT_FP4_TOKEN;
-    if (per_token && p.b > 512) return false;
+    // (b >= 1024: a half-wave holds positions 2048 h .. 2048 h + 2047, one real row when d = 2048; rows
+    //  of 1024 would split a lane's registers between two rows)
+    if (per_token && p.b > 512 && p.d != 2048) return false;
     return out_kind != OUT_DIAG && p.d >= 512 && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 &&
            p.T % (kTile / p.d) == 0;
 }
