@@ -936,17 +936,17 @@ bool mfma_supports(const ApplyParams& p) {
 // Narrow rows stored back to back can be folded into 4096-wide ones (a wave's tile is 4096 wide
 // whatever d is): blocks and 32-groups do not straddle rows, and codes, e8m0 bytes and fp32 outputs
 // of consecutive rows are contiguous, so only the operand addresses through `perm` know about it.
-// Not for the per-token scale, which needs one maximum per real row.
-// Rows of 512, 1024 or 2048 stored back to back are taken as 4096-wide ones.  The formats with one
-// scale per token need the row's extremes: their exchange between lanes follows the real rows where a
-// lane's values lie inside one row (b <= 512, and rows of 2048 for b >= 1024).
+// Rows of 512, 1024 or 2048 fold.  The formats with one scale per token need the row's extremes:
+// their exchange between lanes follows the real rows where a lane's values lie inside one row
+// (b <= 512, and rows of 2048 for b >= 1024).  Rows that do not fill a last 4096-wide one (fewer
+// than 4096 / d of them) take a second, unfolded launch.
 static bool folds(const ApplyParams& p, int out_kind) {
     const bool per_token = out_kind == OUT_INT4 || out_kind == OUT_INT4_ASYM || out_kind == OUT_FP4_TOKEN;
     // (b >= 1024: a half-wave holds positions 2048 h .. 2048 h + 2047, one real row when d = 2048; rows
     //  of 1024 would split a lane's registers between two rows)
     if (per_token && p.b > 512 && p.d != 2048) return false;
-    return out_kind != OUT_DIAG && p.d >= 512 && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d && p.T > 0 &&
-           p.T % (kTile / p.d) == 0;
+    return out_kind != OUT_DIAG && p.d >= 512 && p.d < kTile && kTile % p.d == 0 && p.ldx == p.d &&
+           p.T >= kTile / p.d;
 }
 
 bool mfma_preferred(const ApplyParams& p, int out_kind) {
@@ -960,8 +960,25 @@ hipError_t launch_mfma(const ApplyParams& p0, int out_kind, hipStream_t stream) 
     ApplyParams p = p0;
     uint32_t fold_mask = 0xFFFFFFFFu;
     if (folds(p, out_kind)) {
+        const int64_t per_tile = kTile / p.d, rest = p.T % per_tile;
+        if (rest != 0) {
+            // the last rows, too few for a 4096-wide one: a launch of their own, unfolded (folds() says no
+            // to fewer rows than fill one)
+            ApplyParams q = p0;
+            const int64_t done = p.T - rest;
+            q.T = rest;
+            q.x = p0.x + done * p0.ldx;
+            if (p0.codes != nullptr) q.codes = p0.codes + done * (p0.d >> 1);
+            if (p0.y != nullptr) q.y = p0.y + done * p0.d;
+            if (p0.scales != nullptr) {
+                const int64_t per_row = out_kind == OUT_MXFP4 ? (p0.d >> 5) : (out_kind == OUT_INT4_ASYM ? 8 : 4);
+                q.scales = static_cast<unsigned char*>(p0.scales) + done * per_row;
+            }
+            const hipError_t e = launch_mfma(q, out_kind, stream);
+            if (e != hipSuccess) return e;
+        }
         fold_mask = (uint32_t)p.d - 1u;
-        p.T = p.T / (kTile / p.d);
+        p.T = p.T / per_tile;
         p.d = kTile;
         p.ldx = kTile;
     }

@@ -117,6 +117,8 @@ SHAPES = [
     (24, 2048, [32, 128, 1024, 2048]),       # rows of d < 4096 stored back to back: folded into 4096-wide ones
     (40, 1024, [16, 64, 1024]),
     (64, 512, [32, 512]),
+    (69, 512, [32, 512]),                    # 8 rows fold into one; the last 5 take a launch of their own
+    (27, 2048, [32, 2048]),
     (9, 8192, [16, 32, 64, 128, 2048, 4096, 8192]),
     (5, 14336, [32, 128, 512, 1024, 2048]),
     (6, 20480, [256, 1024, 4096]),           # 8-wave groups, ragged last tile
@@ -278,6 +280,10 @@ TOKEN_FORMAT_SHAPES = [
     (24, 2048, [32, 128, 512, 1024, 2048]),
     (40, 1024, [16, 64, 256, 1024]),
     (64, 512, [32, 128, 512]),
+    # the same with rows left over that do not fill a folded row (they take a second launch)
+    (25, 2048, [128, 2048]),
+    (43, 1024, [64]),
+    (67, 512, [32]),
 ]
 
 
