@@ -170,3 +170,20 @@ def calib_apply() -> Workload:
 ALL = {"tiny": tiny, "llama1b_down": llama1b_down, "block_vs_full": block_vs_full,
        "llama8b_d4096": lambda: llama8b(4096), "llama8b_d14336": lambda: llama8b(14336),
        "calib_apply": calib_apply, "qwen3_d9728": lambda: qwen3(9728), "qwen3_d12288": lambda: qwen3(12288)}
+
+
+def device_rows(T: int, d: int, seed: int, device="cuda", rows_per_draw: int = 65536):
+    """T x d bfloat16 rows drawn on the device, for inputs too large to draw on the host (several
+    GiB): N(0, 1) entries, every 97th channel scaled by 24 (channel-concentrated outliers).
+    Seeded: draw k of rows_per_draw rows uses torch's device generator seeded with (seed, k)."""
+    import torch
+    x = torch.empty((T, d), dtype=torch.bfloat16, device=device)
+    scale = torch.ones(d, dtype=torch.float32, device=device)
+    scale[5::97] = 24.0
+    gen = torch.Generator(device=device)
+    for k, r0 in enumerate(range(0, T, rows_per_draw)):
+        r1 = min(T, r0 + rows_per_draw)
+        gen.manual_seed(seed * 1000003 + k)
+        block = torch.randn((r1 - r0, d), generator=gen, device=device, dtype=torch.float32)
+        x[r0:r1] = (block * scale).to(torch.bfloat16)
+    return x
