@@ -273,7 +273,9 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
             }
             uint8_t* crow = p.codes + row * (int64_t)(d >> 1) + 16 * t;
             if constexpr (OUT == OUT_INT4) {
-                const float inv = m[0] > 0.0f ? 7.0f / m[0] : 0.0f;
+                float mx = m[0];
+                if (tiny_row(mx)) { lift_values(v); mx *= kTinyRowLift; }
+                const float inv = mx > 0.0f ? 7.0f / mx : 0.0f;
                 if (live) {
                     const uint4 c = make_uint4(int4_pack8(v, inv), int4_pack8(v + 8, inv),
                                                int4_pack8(v + 16, inv), int4_pack8(v + 24, inv));
@@ -281,7 +283,9 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
                     if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_7sqrt_b);
                 }
             } else if constexpr (OUT == OUT_FP4_TOKEN) {
-                const float inv = m[0] > 0.0f ? 6.0f / m[0] : 0.0f;
+                float mx = m[0];
+                if (tiny_row(mx)) { lift_values(v); mx *= kTinyRowLift; }
+                const float inv = mx > 0.0f ? 6.0f / mx : 0.0f;
                 if (live) {
                     const uint4 c = make_uint4(fp4_pack8(v, inv), fp4_pack8(v + 8, inv),
                                                fp4_pack8(v + 16, inv), fp4_pack8(v + 24, inv));
@@ -289,7 +293,9 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
                     if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_6sqrt_b);
                 }
             } else {
-                const float lo = -m[1], hi = m[0];
+                float lo = -m[1], hi = m[0];
+                const float range = hi - lo;
+                if (tiny_row(range)) { lift_values(v); lo *= kTinyRowLift; hi *= kTinyRowLift; }
                 const Int4Asym q = int4_asym_row(lo, hi);
                 if (live) {
                     uint4 c;
@@ -304,7 +310,7 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
                     store_stream16(crow, c);
                     if (t == 0) {
                         float2* so = static_cast<float2*>(p.scales) + row;
-                        *so = make_float2((float)((double)(hi - lo) * p.inv_15sqrt_b), (float)q.z);
+                        *so = make_float2((float)((double)range * p.inv_15sqrt_b), (float)q.z);
                     }
                 }
             }

@@ -138,6 +138,21 @@ __device__ __forceinline__ float absmax(const float (&v)[N]) {
     return m;
 }
 
+// ---- rows of vanishing magnitude -----------------------------------------------------------
+// The per-token formats multiply every value by qmax / (row maximum) (or 15 / (max - min)).  Below
+// an extent of 2^-100 -- a row of bf16 subnormals -- that quotient leaves the fp32 range, so such a
+// row is multiplied by 2^100 first: exact, and the codes depend on ratios only.  The scale written
+// out is computed from the extent as it was.
+constexpr float kTinyRow = 0x1p-100f, kTinyRowLift = 0x1p100f;
+__device__ __forceinline__ bool tiny_row(float extent) {
+    return __builtin_expect(extent < kTinyRow && extent > 0.0f, 0);
+}
+template <int N>
+__device__ __forceinline__ void lift_values(float (&v)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] *= kTinyRowLift;
+}
+
 // ---- INT4: 8 values -> one dword of two's-complement nibbles, element 0 in bits 3:0 ------
 // fma(y, inv, 1.5*2^23 + 8) rounds y*inv to an integer c (ties to even) in one step and leaves
 // the word 0x4B400000 + (c + 8): the low nibble is c in offset binary (1..15, so nothing

@@ -530,7 +530,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 }
                 if constexpr (OUT == OUT_INT4) {
                     row_max = m[0];
-                    const float inv = m[0] > 0.0f ? 7.0f / m[0] : 0.0f;
+                    float mx = m[0];
+                    if (tiny_row(mx)) { lift_values(v); mx *= kTinyRowLift; }
+                    const float inv = mx > 0.0f ? 7.0f / mx : 0.0f;
 #pragma unroll
                     for (int q = 0; q < kQ; ++q) {
                         pk[q][0] = int4_pack8(v + q * 16, inv);
@@ -538,7 +540,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 } else if constexpr (OUT == OUT_FP4_TOKEN) {
                     row_max = m[0];
-                    const float inv = m[0] > 0.0f ? 6.0f / m[0] : 0.0f;
+                    float mx = m[0];
+                    if (tiny_row(mx)) { lift_values(v); mx *= kTinyRowLift; }
+                    const float inv = mx > 0.0f ? 6.0f / mx : 0.0f;
 #pragma unroll
                     for (int q = 0; q < kQ; ++q) {
                         pk[q][0] = fp4_pack8(v + q * 16, inv);
@@ -546,7 +550,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 } else {
                     row_max = m[0] + m[1];                 // hi - lo
-                    const Int4Asym qa = int4_asym_row(-m[1], m[0]);
+                    float lo = -m[1], hi = m[0];
+                    if (tiny_row(row_max)) { lift_values(v); lo *= kTinyRowLift; hi *= kTinyRowLift; }
+                    const Int4Asym qa = int4_asym_row(lo, hi);
                     row_zero = qa.z;
                     if (!qa.clamp) {
                         const uint32_t zn = (uint32_t)qa.z * 0x11111111u;

@@ -427,9 +427,21 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         // ---- quantize, pack, store ---------------------------------------------------------------
         float inv = 0.0f;
         Int4Asym qa = {0.0f, 0, false};
-        if constexpr (OUT == OUT_INT4) inv = m[0] > 0.0f ? 7.0f / m[0] : 0.0f;
-        if constexpr (OUT == OUT_FP4_TOKEN) inv = m[0] > 0.0f ? 6.0f / m[0] : 0.0f;
-        if constexpr (OUT == OUT_INT4_ASYM) qa = int4_asym_row(-m[1], m[0]);
+        if constexpr (kTokenStat) {
+            float hi = m[0], lo = OUT == OUT_INT4_ASYM ? -m[1] : 0.0f;
+            if (tiny_row(hi - lo)) {
+#pragma unroll
+                for (int it = 0; it < kIts; ++it) {
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) lift_values(f[it][ch]);
+                }
+                hi *= kTinyRowLift;
+                lo *= kTinyRowLift;
+            }
+            if constexpr (OUT == OUT_INT4) inv = hi > 0.0f ? 7.0f / hi : 0.0f;
+            if constexpr (OUT == OUT_FP4_TOKEN) inv = hi > 0.0f ? 6.0f / hi : 0.0f;
+            if constexpr (OUT == OUT_INT4_ASYM) qa = int4_asym_row(lo, hi);
+        }
 #pragma unroll
         for (int it = 0; it < kIts; ++it) {
             const int gI = t_row + kThreadsPerRow * it;

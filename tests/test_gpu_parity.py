@@ -679,6 +679,26 @@ def test_nonpo2_row_stride_single_row_empty_and_repeat():
         assert torch.equal(c1, c2) and torch.equal(s1, s2)
 
 
+# ---- rows of extreme magnitude ------------------------------------------------------------------
+@pytest.mark.parametrize("d,b", [(256, 16), (512, 512), (4096, 128), (4096, 4096), (8192, 32), (2048, 2048),
+                                 (3584, 3584), (8192, 8192)])
+def test_rows_from_subnormal_to_huge(d, b):
+    """Rows scaled by 2^-132 ... 2^110: bf16 subnormals (the quotient 7 / max of a per-token format is
+    then beyond fp32), the smallest normals, and values whose block sums stay just inside fp32."""
+    rng = np.random.default_rng(d + b)
+    exps = [-132, -131, -130, -128, -126, -125, -120, -110, -101, -100, -99, -64, 0, 64, 100, 110]
+    x = rng.standard_normal((len(exps), d)) * (2.0 ** np.array(exps, dtype=np.float64))[:, None]
+    bits = synth.f64_to_bf16_bits(x)
+    rotate = orc.fwht_f64 if (b > 4096 and b & (b - 1) == 0) else None
+    for fmt in ("int4", "mxfp4", "int4_asym", "fp4_token"):
+        for algo in ALGOS:
+            if algo == "butterfly" and b & (b - 1):
+                continue
+            if algo == "mfma" and (b & (b - 1) or b > 4096):
+                continue
+            assert_parity(bits, None, b, fmt, algo, rotate=rotate, label="extreme magnitudes")
+
+
 # ---- a seeded sweep over shapes, block sizes, formats, permutations and row pitches ---------------
 def _random_cases(n, seed):
     rng = np.random.default_rng(seed)

@@ -39,7 +39,7 @@ def test_int4_ties_go_to_even_and_zero_row():
 def test_int4_scale_and_sign_equivariance():
     Y = _rng(2).standard_normal((8, 64))
     c, s = orc.quant_int4_sym_token(Y)
-    for k in (-9, 3, 20):
+    for k in (-140, -9, 3, 20, 100):         # down to magnitudes below the smallest normal fp32
         c2, s2 = orc.quant_int4_sym_token(np.ldexp(Y, k))
         assert np.array_equal(c, c2) and np.array_equal(np.ldexp(s, k), s2)
     c3, s3 = orc.quant_int4_sym_token(-Y)
