@@ -92,6 +92,9 @@ def test_statistics_past_4_gib():
         part = orc.bf16_bits_to_f64(_bits(x[r0:r0 + 65536]))
         total += orc.colabs_mean(part) * part.shape[0]
     a_orc = total / T
+    # fp32 partial sums of 1024+ rows per slice: the worst case is (rows per slice + 1) * 2^-24, the
+    # rounding errors of random data stay far below it; 33 * 2^-24 is about the weight 1/T of one row,
+    # so a row left out or counted twice fails
     assert np.all(np.abs(a - a_orc) <= 33 * 2.0 ** -24 * a_orc)
     perm = orc.massdiff_greedy(a_orc, b)
     diag = binding.perq_block_diagnostics(x, torch.from_numpy(perm.astype(np.int32)).cuda(), b)
