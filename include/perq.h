@@ -145,6 +145,27 @@ perq_status_t perq_hadamard_base(int32_t m, int8_t* out);
 perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
 
 /*
+ * Host.  perm arranged for the fused kernel's operand gather.  With a permutation the kernel
+ * fetches every operand element with a 2-byte LDS read of its own, and on arbitrary channel
+ * orders the lanes of one read instruction meet in the same LDS banks.  Algorithm 1 decides which
+ * channels share a block -- that fixes the block masses and with them the bound of Proposition 2
+ * and Corollary 3.3 -- while the order inside a block is free: P is merged into the neighbouring
+ * weights whatever it is (Section 4, remark on merging permutations).  perq_perm_arrange keeps
+ * the channel set of every block of b positions and orders it so that the lanes of a read
+ * instruction meet different banks (measured: d = 14336, b = 128, INT4, T = 32768: 238 -> 208 us).
+ * The result is a different permutation with the same blocks: whatever is merged offline must be
+ * merged with perm_out.  Shapes the arrangement does not apply to (d < 4096, d % 512 != 0,
+ * b > 4096, b not a power of two) are copied unchanged.
+ *   perm, perm_out  host, int32 [d]; perm must be a bijection on [0,d); may be the same array
+ * perq_perm_gather_cost reports what the arrangement is about: `reads` = read instructions per
+ * half-wave and row, `passes` = the sum over them of the largest number of lanes that meet in one
+ * bank on different words (passes == reads: no conflicts).  PERQ_ERR_UNSUPPORTED for the shapes
+ * listed above.
+ */
+perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32_t b, int32_t* perm_out);
+perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, int32_t b, int64_t* passes, int64_t* reads);
+
+/*
  * The fused online path: gather through perm, rotate every b-block, quantize, pack.
  *
  *   x_bf16   device, bf16 [T, ldx]; ldx >= d; base 16-byte aligned and ldx % 8 == 0

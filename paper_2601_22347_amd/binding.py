@@ -25,7 +25,8 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_massdiff_perm", "perq_perm_validate", "perq_permute_rotate_quant",
            "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
-           "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref"]
+           "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref", "perq_perm_arrange",
+           "perq_perm_gather_cost"]
 
 _lib = None
 
@@ -58,6 +59,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_massdiff_perm.argtypes = [vp, i32, i32, vp]
     lib.perq_perm_validate.restype = ctypes.c_int
     lib.perq_perm_validate.argtypes = [vp, i32]
+    lib.perq_perm_arrange.restype = ctypes.c_int
+    lib.perq_perm_arrange.argtypes = [vp, i32, i32, vp]
+    lib.perq_perm_gather_cost.restype = ctypes.c_int
+    lib.perq_perm_gather_cost.argtypes = [vp, i32, i32, vp, vp]
     lib.perq_permute_rotate_quant.restype = ctypes.c_int
     lib.perq_permute_rotate_quant.argtypes = [vp, i64, i32, i64, vp, i32, ctypes.c_int, vp, vp, vp]
     lib.perq_permute_rotate_quant_algo.restype = ctypes.c_int
@@ -152,6 +157,25 @@ def perq_perm_zigzag(stat: np.ndarray, b: int) -> np.ndarray:
     _check(load().perq_perm_zigzag(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], int(b),
                                    perm.ctypes.data_as(ctypes.c_void_p)), "perq_perm_zigzag")
     return perm
+
+
+def perq_perm_arrange(perm: np.ndarray, b: int) -> np.ndarray:
+    """perm with the channels of every block reordered for the kernel's LDS gather (same blocks)."""
+    p = np.ascontiguousarray(perm, dtype=np.int32)
+    out = np.empty_like(p)
+    st = load().perq_perm_arrange(p.ctypes.data_as(ctypes.c_void_p), p.size, int(b), out.ctypes.data_as(ctypes.c_void_p))
+    _check(st, "perq_perm_arrange")
+    return out
+
+
+def perq_perm_gather_cost(perm: np.ndarray, b: int):
+    """(passes, reads) of the element-wise LDS gather for this permutation; passes == reads: conflict free."""
+    p = np.ascontiguousarray(perm, dtype=np.int32)
+    passes, reads = ctypes.c_int64(0), ctypes.c_int64(0)
+    st = load().perq_perm_gather_cost(p.ctypes.data_as(ctypes.c_void_p), p.size, int(b), ctypes.byref(passes),
+                                      ctypes.byref(reads))
+    _check(st, "perq_perm_gather_cost")
+    return passes.value, reads.value
 
 
 def perq_perm_validate(perm: np.ndarray) -> bool:

@@ -2,6 +2,7 @@
 // validator and the base matrices of the non-power-of-two rotation.  No device code here.
 #include "perq.h"
 #include "perq_base.h"
+#include "perq_layout.h"
 
 #include <algorithm>
 #include <cmath>
@@ -176,5 +177,159 @@ extern "C" perq_status_t perq_hadamard_base(int32_t m, int8_t* out) {
     if (kind == 0) return PERQ_ERR_INVALID_ARG;
     for (int32_t r = 0; r < m; ++r)
         for (int32_t c = 0; c < m; ++c) out[(int64_t)r * m + c] = (int8_t)perq::hadamard_base_entry(m, kind, r, c);
+    return PERQ_OK;
+}
+
+
+// ---- a permutation arranged for the operand gather of the matrix-core kernel ---------------------
+// With a permutation every operand element is a 2-byte LDS read at an address of its own; one read
+// instruction fetches, for the 32 lanes of each half-wave, one position each (perq_layout.h), and on
+// arbitrary addresses several lanes meet in one of the 32 four-byte banks.  Which channels a block
+// holds is Algorithm 1's result and fixes the block masses, hence the bound of Proposition 2; the
+// order inside a block is free (P is merged into the weights either way).  The routine below keeps
+// every block's set and orders it so that the lanes of a read instruction meet different banks.
+namespace {
+
+struct GatherShape {
+    bool ok;        // the shape runs on the matrix-core kernel with the element-wise gather
+    bool high_k;    // b >= 1024
+    int tiles;
+};
+
+GatherShape gather_shape(int32_t d, int32_t b) {
+    GatherShape s{false, false, 0};
+    if (d < 4096 || d > PERQ_MAX_D || d % 512 != 0) return s;
+    if (b < 16 || b > 4096 || (b & (b - 1)) != 0 || d % b != 0) return s;
+    s.ok = true;
+    s.high_k = b >= 1024;
+    s.tiles = (d + 4095) / 4096;
+    return s;
+}
+
+inline int bank_of(int32_t channel) { return (int)((perq::layout::channel_offset((uint32_t)channel) >> 2) & 31u); }
+
+// Calls visit(positions, n) once per read instruction and half-wave with the positions (in the row)
+// that its lanes fetch; lanes past the end of a ragged last tile are left out.
+template <class F>
+void for_each_read(int32_t d, const GatherShape& s, F&& visit) {
+    int32_t pos[32];
+    for (int t = 0; t < s.tiles; ++t) {
+        const int32_t tile_len = std::min<int32_t>(4096, d - 4096 * t);
+        for (uint32_t f = 0; f < 8; ++f)
+            for (uint32_t e = 0; e < 8; ++e)
+                for (uint32_t h = 0; h < 2; ++h) {
+                    int n = 0;
+                    for (uint32_t l = 0; l < 32; ++l) {
+                        const int32_t in_tile = (int32_t)perq::layout::gather_pos(s.high_k, l, h, f, e);
+                        if (in_tile < tile_len) pos[n++] = 4096 * t + in_tile;
+                    }
+                    if (n > 0) visit(pos, n);
+                }
+    }
+}
+
+}  // namespace
+
+extern "C" perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, int32_t b, int64_t* passes,
+                                               int64_t* reads) {
+    if (perm == nullptr || passes == nullptr || reads == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
+    if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
+    const GatherShape s = gather_shape(d, b);
+    if (!s.ok) return PERQ_ERR_UNSUPPORTED;
+    int64_t total = 0, count = 0;
+    for_each_read(d, s, [&](const int32_t* pos, int n) {
+        // lanes in one bank are served one after another unless they want the same four bytes
+        int load[32] = {0};
+        int32_t seen[32][32];
+        for (int i = 0; i < n; ++i) {
+            const uint32_t off = perq::layout::channel_offset((uint32_t)perm[pos[i]]);
+            const int bank = (int)((off >> 2) & 31u);
+            const int32_t word = (int32_t)(off >> 2);
+            bool dup = false;
+            for (int k = 0; k < load[bank]; ++k) dup = dup || seen[bank][k] == word;
+            if (!dup) seen[bank][load[bank]++] = word;
+        }
+        total += *std::max_element(load, load + 32);
+        ++count;
+    });
+    *passes = total;
+    *reads = count;
+    return PERQ_OK;
+}
+
+extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32_t b, int32_t* perm_out) {
+    if (perm == nullptr || perm_out == nullptr || d <= 0 || b <= 0 || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
+    const GatherShape s = gather_shape(d, b);
+    if (!s.ok) {                       // no such gather for this shape: nothing to gain, nothing changed
+        std::copy(perm, perm + d, perm_out);
+        return PERQ_OK;
+    }
+    // the channels of every block, by bank (ascending inside a bank: the result is deterministic)
+    const int32_t nblocks = d / b;
+    std::vector<std::vector<int32_t>> pool((size_t)nblocks * 32);
+    for (int32_t j = 0; j < nblocks; ++j) {
+        std::vector<int32_t> chans(perm + (size_t)j * b, perm + (size_t)(j + 1) * b);
+        std::sort(chans.begin(), chans.end(), std::greater<int32_t>());
+        for (int32_t c : chans) pool[(size_t)j * 32 + bank_of(c)].push_back(c);     // taken from the back
+    }
+    for_each_read(d, s, [&](const int32_t* pos, int n) {
+        // a matching of lanes to banks (Kuhn's augmenting paths), lanes with the fewest banks on
+        // offer first, banks tried in the order of what the lane's block still holds most of
+        int order[32], lane_bank[32], bank_lane[32];
+        std::vector<int> adj[32];
+        for (int i = 0; i < n; ++i) {
+            const size_t blk = (size_t)(pos[i] / b) * 32;
+            for (int k = 0; k < 32; ++k)
+                if (!pool[blk + k].empty()) adj[i].push_back(k);
+            std::stable_sort(adj[i].begin(), adj[i].end(), [&](int x, int y) { return pool[blk + x].size() > pool[blk + y].size(); });
+            order[i] = i;
+            lane_bank[i] = -1;
+        }
+        std::fill(bank_lane, bank_lane + 32, -1);
+        std::stable_sort(order, order + n, [&](int x, int y) { return adj[x].size() < adj[y].size(); });
+        // (for the lanes left over below) two lanes of one block may not both count on the last channel of a bank
+        auto free_in = [&](int lane, int bank) {
+            const size_t blk = (size_t)(pos[lane] / b) * 32;
+            size_t taken = 0;
+            for (int i = 0; i < n; ++i)
+                if (i != lane && lane_bank[i] == bank && (size_t)(pos[i] / b) * 32 == blk) ++taken;
+            return pool[blk + bank].size() > taken;
+        };
+        bool visited[32];
+        auto augment = [&](auto&& self, int lane) -> bool {
+            for (int k : adj[lane]) {
+                if (visited[k]) continue;      // (a bank holds one lane here, so its pool is never short)
+                visited[k] = true;
+                if (bank_lane[k] < 0 || self(self, bank_lane[k])) {
+                    bank_lane[k] = lane;
+                    lane_bank[lane] = k;
+                    return true;
+                }
+            }
+            return false;
+        };
+        for (int q = 0; q < n; ++q) {
+            std::fill(visited, visited + 32, false);
+            augment(augment, order[q]);
+        }
+        // lanes left over share a bank: the least loaded one their block can still serve
+        int load[32];
+        for (int k = 0; k < 32; ++k) load[k] = bank_lane[k] >= 0 ? 1 : 0;
+        for (int q = 0; q < n; ++q) {
+            const int lane = order[q];
+            if (lane_bank[lane] >= 0) continue;
+            int best = -1;
+            for (int k : adj[lane])
+                if (free_in(lane, k) && (best < 0 || load[k] < load[best])) best = k;
+            lane_bank[lane] = best;
+            ++load[best];
+        }
+        for (int i = 0; i < n; ++i) {
+            std::vector<int32_t>& from = pool[(size_t)(pos[i] / b) * 32 + lane_bank[i]];
+            perm_out[pos[i]] = from.back();
+            from.pop_back();
+        }
+    });
     return PERQ_OK;
 }

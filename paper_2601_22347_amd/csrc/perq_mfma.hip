@@ -33,6 +33,7 @@
 // over all banks; the swizzle is applied on the global side of the direct-to-LDS load.
 #include "perq_device.h"
 #include "perq_launch.h"
+#include "perq_layout.h"
 
 #include <atomic>
 #include <type_traits>
@@ -66,16 +67,11 @@ constexpr uint32_t kWorkSets = 64;
 __device__ uint32_t work_ctr[kWorkSets][kWorkQueues][64];
 std::atomic<uint32_t> launch_seq{0};     // host side: launches of this process so far
 
-// granule -> slot inside a row (an involution: bits 4..6 select the xor pattern for bits 0..2)
-__device__ __forceinline__ uint32_t granule_slot(uint32_t g) {
-    const uint32_t c = (g >> 4) & 7u;
-    return g ^ (((c & 3u) << 1) | (c >> 2));
-}
+using layout::granule_slot;      // granule -> slot inside a staged row
+using layout::hk_pos;            // high-K mode: position inside the tile of row m, contraction index K
 
 __device__ __forceinline__ uint32_t popc_parity(uint32_t v) { return __builtin_popcount(v) & 1u; }
 
-// high-K mode (b >= 1024): position inside the tile of row m (5 bits), contraction index K (7 bits)
-__device__ __forceinline__ uint32_t hk_pos(uint32_t m, uint32_t K) { return (m & 15u) | (K << 4) | ((m >> 4) << 11); }
 
 // Stores to LDS and workgroup barriers of the main loop, written as instructions.  The compiler
 // makes every LDS store it knows of wait until no direct-to-LDS load is outstanding (it cannot
@@ -155,8 +151,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     constexpr bool kHighK = STAGES >= 5;
     constexpr bool kElem = PERM || kHighK;          // operands gathered element by element
     bf16x8_t afrag[2], afrag_neg[2];
-    const uint32_t sigma_i = 16u * ((((uint32_t)lane & 31u) >> 2) & 1u) + 4u * (((uint32_t)lane & 31u) >> 3) +
-                             ((uint32_t)lane & 3u);
+    const uint32_t sigma_i = layout::lane_sigma((uint32_t)lane & 31u);
     {
         const uint32_t n = kHighK ? ((uint32_t)lane & 31u) : sigma_i;
 #pragma unroll

@@ -679,6 +679,21 @@ def test_nonpo2_row_stride_single_row_empty_and_repeat():
         assert torch.equal(c1, c2) and torch.equal(s1, s2)
 
 
+# ---- a permutation arranged for the LDS gather is a permutation like any other -------------------
+@pytest.mark.parametrize("d,b,fmt", [(4096, 128, "int4"), (14336, 128, "int4"), (14336, 2048, "mxfp4"),
+                                     (8192, 32, "mxfp4"), (4096, 4096, "int4_asym"), (16384, 1024, "fp4_token")])
+def test_arranged_permutation(d, b, fmt):
+    rng = np.random.default_rng(d * 3 + b)
+    a = np.exp(rng.normal(0, 1.5, d)).astype(np.float32)
+    greedy = binding.perq_massdiff_perm(a, b)
+    assert np.array_equal(greedy, orc.massdiff_greedy(a.astype(np.float64), b))
+    perm = binding.perq_perm_arrange(greedy, b)
+    assert not np.array_equal(perm, greedy)
+    x = _heavy_rows(11, d, 77 + d)
+    for algo in ("mfma", "auto"):
+        assert_parity(x, perm, b, fmt, algo, label="arranged perm")
+
+
 # ---- rows of extreme magnitude ------------------------------------------------------------------
 @pytest.mark.parametrize("d,b", [(256, 16), (512, 512), (4096, 128), (4096, 4096), (8192, 32), (2048, 2048),
                                  (3584, 3584), (8192, 8192)])

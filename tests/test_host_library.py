@@ -140,3 +140,50 @@ def test_random_permutation_matches_oracle_generator():
     with pytest.raises(binding.PerqError) as ei:
         binding.perq_perm_random(0, 1)
     assert ei.value.status == binding.PERQ_ERR_INVALID_ARG
+
+
+# ---- perq_perm_arrange: same blocks, an order that suits the kernel's LDS gather -----------------
+@pytest.mark.parametrize("d,b", [(4096, 128), (4096, 16), (4096, 4096), (8192, 32), (14336, 128), (14336, 2048),
+                                 (12288, 1024), (32768, 512)])
+def test_perm_arrange_keeps_every_block_and_lowers_the_gather_cost(d, b):
+    rng = np.random.default_rng(d + b)
+    a = np.exp(rng.normal(0, 1.5, d)).astype(np.float32)
+    for perm in (rng.permutation(d).astype(np.int32), binding.perq_massdiff_perm(a, b)):
+        out = binding.perq_perm_arrange(perm, b)
+        assert binding.perq_perm_validate(out)
+        # what is unique: the channel set of every block (and so every block mass of Algorithm 1)
+        assert np.array_equal(np.sort(out.reshape(-1, b), axis=1), np.sort(perm.reshape(-1, b), axis=1))
+        assert np.array_equal(binding.perq_perm_arrange(perm, b), out)          # deterministic
+        p0, r0 = binding.perq_perm_gather_cost(perm, b)
+        p1, r1 = binding.perq_perm_gather_cost(out, b)
+        assert r0 == r1 and r0 <= 128 * ((d + 4095) // 4096)
+        assert p1 >= r1 and p0 >= r0
+        assert p1 <= 0.65 * p0, (p0, p1, r1)       # a random order costs about 3.4 passes per read
+        if b >= 128:
+            assert p1 <= 1.35 * r1, (p1, r1)
+
+
+def test_perm_arrange_gather_cost_model_on_known_orders():
+    d, b = 4096, 128
+    ident = np.arange(d, dtype=np.int32)
+    # the identity read element by element: the 32 lanes of a half-wave are 128 channels apart,
+    # eight granule slots four banks apart each -> four lanes per bank
+    assert binding.perq_perm_gather_cost(ident, b) == (512, 128)
+    # all lanes on the same word: one pass
+    with pytest.raises(binding.PerqError):
+        binding.perq_perm_gather_cost(np.zeros(d, dtype=np.int32), b)          # not a permutation
+
+
+def test_perm_arrange_leaves_other_shapes_alone_and_checks_arguments():
+    rng = np.random.default_rng(9)
+    for d, b in [(2048, 128), (3584, 3584), (4096 + 32, 32), (8192, 8192), (512, 64)]:
+        perm = rng.permutation(d).astype(np.int32)
+        assert np.array_equal(binding.perq_perm_arrange(perm, b), perm)
+        with pytest.raises(binding.PerqError) as ei:
+            binding.perq_perm_gather_cost(perm, b)
+        assert ei.value.status == binding.PERQ_ERR_UNSUPPORTED
+    bad = np.arange(4096, dtype=np.int32); bad[5] = 6
+    with pytest.raises(binding.PerqError):
+        binding.perq_perm_arrange(bad, 128)
+    with pytest.raises(binding.PerqError):
+        binding.perq_perm_arrange(np.arange(4096, dtype=np.int32), 100)        # b does not divide d
