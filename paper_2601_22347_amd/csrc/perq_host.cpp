@@ -5,6 +5,7 @@
 #include "perq_layout.h"
 
 #include <algorithm>
+#include <array>
 #include <cmath>
 #include <cstdint>
 #include <numeric>
@@ -265,11 +266,83 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         std::copy(perm, perm + d, perm_out);
         return PERQ_OK;
     }
-    // the channels of every block, by bank (ascending inside a bank: the result is deterministic)
     const int32_t nblocks = d / b;
+    // Which block sits where in the row is as free as the order inside a block.  A read can only be
+    // free of conflicts if the channels of its tile are spread evenly over the banks (a tile of a
+    // wide row holds an arbitrary 4096 of the d channels), so the blocks are first dealt to the
+    // tiles with that in mind: each to the tile whose fullest bank it raises least above the level
+    // of an even spread, then pairs of blocks are exchanged between tiles while that lowers the
+    // sum of the tiles' fullest banks.  Inside a tile the blocks keep their order.
+    std::vector<int32_t> block_at(nblocks);                 // block_at[place] = block of perm
+    {
+        std::vector<std::array<int32_t, 32>> hist(nblocks);
+        for (int32_t j = 0; j < nblocks; ++j) {
+            hist[j].fill(0);
+            for (int32_t i = 0; i < b; ++i) ++hist[j][bank_of(perm[(size_t)j * b + i])];
+        }
+        const int tiles = s.tiles;
+        std::vector<int32_t> cap(tiles), tile_of(nblocks, -1);
+        std::vector<std::array<int32_t, 32>> total(tiles);
+        std::vector<int32_t> filled(tiles, 0);
+        for (int t = 0; t < tiles; ++t) {
+            cap[t] = std::min<int32_t>(4096, d - 4096 * t) / b;
+            total[t].fill(0);
+        }
+        auto peak_with = [&](int t, int32_t add, int32_t drop) {
+            int32_t m = 0;
+            for (int k = 0; k < 32; ++k)
+                m = std::max(m, total[t][k] + (add >= 0 ? hist[add][k] : 0) - (drop >= 0 ? hist[drop][k] : 0));
+            return m;
+        };
+        if (tiles > 1 && cap[0] > 1) {
+            for (int32_t j = 0; j < nblocks; ++j) {
+                int best = -1;
+                int64_t best_cost = 0;
+                for (int t = 0; t < tiles; ++t) {
+                    if (filled[t] == cap[t]) continue;
+                    // excess of the fullest bank over an even spread, in units of 1/32 channel
+                    const int64_t cost = (int64_t)peak_with(t, j, -1) * 32 - (int64_t)(filled[t] + 1) * b;
+                    if (best < 0 || cost < best_cost || (cost == best_cost && cap[t] - filled[t] > cap[best] - filled[best])) {
+                        best = t;
+                        best_cost = cost;
+                    }
+                }
+                tile_of[j] = best;
+                ++filled[best];
+                for (int k = 0; k < 32; ++k) total[best][k] += hist[j][k];
+            }
+            for (int pass = 0; pass < 4; ++pass) {
+                bool changed = false;
+                for (int32_t x = 0; x < nblocks; ++x)
+                    for (int32_t y = x + 1; y < nblocks; ++y) {
+                        const int tx = tile_of[x], ty = tile_of[y];
+                        if (tx == ty) continue;
+                        const int32_t before = peak_with(tx, -1, -1) + peak_with(ty, -1, -1);
+                        const int32_t after = peak_with(tx, y, x) + peak_with(ty, x, y);
+                        if (after < before) {
+                            for (int k = 0; k < 32; ++k) {
+                                total[tx][k] += hist[y][k] - hist[x][k];
+                                total[ty][k] += hist[x][k] - hist[y][k];
+                            }
+                            std::swap(tile_of[x], tile_of[y]);
+                            changed = true;
+                        }
+                    }
+                if (!changed) break;
+            }
+            int32_t place = 0;
+            for (int t = 0; t < tiles; ++t)
+                for (int32_t j = 0; j < nblocks; ++j)
+                    if (tile_of[j] == t) block_at[place++] = j;
+        } else {
+            std::iota(block_at.begin(), block_at.end(), 0);
+        }
+    }
+    // the channels of every block, by bank (ascending inside a bank: the result is deterministic)
     std::vector<std::vector<int32_t>> pool((size_t)nblocks * 32);
     for (int32_t j = 0; j < nblocks; ++j) {
-        std::vector<int32_t> chans(perm + (size_t)j * b, perm + (size_t)(j + 1) * b);
+        const int32_t* src = perm + (size_t)block_at[j] * b;
+        std::vector<int32_t> chans(src, src + b);
         std::sort(chans.begin(), chans.end(), std::greater<int32_t>());
         for (int32_t c : chans) pool[(size_t)j * 32 + bank_of(c)].push_back(c);     // taken from the back
     }
