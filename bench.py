@@ -55,10 +55,12 @@ def algorithmic_bytes(T: int, d: int, fmt: str) -> int:
     return T * d * 2 + T * d // 2 + scales
 
 
-def read_traffic(name: str, algo: str = "auto", identity: bool = False):
+def read_traffic(name: str, algo: str = "auto", identity: bool = False, arranged: bool = False):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
     if identity:
         name = name.replace("_perm", "_identity")
+    elif arranged:
+        name = name.replace("_perm", "_perm_arranged")
     if algo == "butterfly":
         name += "_butterfly"
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
@@ -80,6 +82,8 @@ def main() -> int:
     ap.add_argument("--pool-bytes", type=float, default=1.5e9,
                     help="input+output bytes cycled through so that no step re-reads cached data")
     ap.add_argument("--identity", action="store_true", help="run the workload with P = I (no gather)")
+    ap.add_argument("--arranged", action="store_true",
+                    help="time the calibrated permutation in the order perq_perm_arrange gives its blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-context", action="store_true", help="skip the single-buffer-set and device-copy figures")
@@ -124,6 +128,9 @@ def main() -> int:
         perm_np = binding.perq_massdiff_perm(a_np, b)
         greedy_ms = (time.perf_counter() - h0) * 1e3
         assert binding.perq_perm_validate(perm_np)
+        if args.arranged:
+            perm_np = binding.perq_perm_arrange(perm_np, b)
+            assert binding.perq_perm_validate(perm_np)
         perm_t = torch.from_numpy(perm_np).to(dev)
         calib = {"colabs_mean_tokens": wl.calib_tokens, "colabs_mean_ms": e0.elapsed_time(e1) / 10,
                  "greedy_host_ms": greedy_ms}
@@ -272,10 +279,11 @@ def main() -> int:
         "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.workload, "T": T, "d": d, "b": b, "fmt": fmt,
-                   "perm": "greedy-calibrated, gather fused" if use_perm else "identity",
+                   "perm": ("greedy-calibrated, blocks arranged for the LDS gather, gather fused" if args.arranged
+                            else "greedy-calibrated, gather fused") if use_perm else "identity",
                    "algo": args.algo, "buffer_sets": nsets, "input_gen_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload, args.algo, args.identity),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload, args.algo, args.identity, args.arranged and use_perm),
                      "algorithmic_bytes": alg_bytes, "kernel_ms": kern_ms},
         "cpu_baseline": cpu,
         "calibration": calib,
