@@ -346,7 +346,10 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         std::sort(chans.begin(), chans.end(), std::greater<int32_t>());
         for (int32_t c : chans) pool[(size_t)j * 32 + bank_of(c)].push_back(c);     // taken from the back
     }
+    std::vector<int32_t> arranged(d);
+    bool broken = false;
     for_each_read(d, s, [&](const int32_t* pos, int n) {
+        if (broken) return;
         // a matching of lanes to banks (Kuhn's augmenting paths), lanes with the fewest banks on
         // offer first, banks tried in the order of what the lane's block still holds most of
         int order[32], lane_bank[32], bank_lane[32];
@@ -395,14 +398,20 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
             int best = -1;
             for (int k : adj[lane])
                 if (free_in(lane, k) && (best < 0 || load[k] < load[best])) best = k;
+            if (best < 0) {            // cannot happen: a block holds as many channels as positions are left
+                broken = true;
+                return;
+            }
             lane_bank[lane] = best;
             ++load[best];
         }
         for (int i = 0; i < n; ++i) {
             std::vector<int32_t>& from = pool[(size_t)(pos[i] / b) * 32 + lane_bank[i]];
-            perm_out[pos[i]] = from.back();
+            arranged[pos[i]] = from.back();
             from.pop_back();
         }
     });
+    if (broken) return PERQ_ERR_LAUNCH;
+    std::copy(arranged.begin(), arranged.end(), perm_out);
     return PERQ_OK;
 }
