@@ -337,7 +337,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         }
         workgroup_barrier_lds();                                   // all chunks of all rows are in LDS
 
-        // ---- phase 2: 16 consecutive positions of every chunk of the row per thread ------------
+        // ---- phase 2: runs of kRun = 8 consecutive positions of every chunk of the row per thread ---
         const int t_row = tid - my_row * kThreadsPerRow;
         const int64_t row = unit * kRows + my_row;
         const bool row_live = row < p.T;
