@@ -191,3 +191,12 @@ def test_perm_arrange_leaves_other_shapes_alone_and_checks_arguments():
         binding.perq_perm_arrange(bad, 128)
     with pytest.raises(binding.PerqError):
         binding.perq_perm_arrange(np.arange(4096, dtype=np.int32), 100)        # b does not divide d
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                         text=True, timeout=120, cwd=root)
+    assert res.returncode != 0 and "one GPU" in res.stderr
