@@ -267,12 +267,14 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         return PERQ_OK;
     }
     const int32_t nblocks = d / b;
-    // Which block sits where in the row is as free as the order inside a block.  A read can only be
-    // free of conflicts if the channels of its tile are spread evenly over the banks (a tile of a
-    // wide row holds an arbitrary 4096 of the d channels), so the blocks are first dealt to the
-    // tiles with that in mind: each to the tile whose fullest bank it raises least above the level
-    // of an even spread, then pairs of blocks are exchanged between tiles while that lowers the
-    // sum of the tiles' fullest banks.  Inside a tile the blocks keep their order.
+    // Which block sits where in the row is as free as the order inside a block.  The lanes of a read
+    // fetch from the blocks of one "bin": a 4096-wide tile, or for b < 128 in the low-K modes the
+    // blocks of a tile with the same index modulo 128 / b (block k * (128 / b) + m of the tile is the
+    // m-th of lane k).  A read can only be free of conflicts if the channels of its bin are spread
+    // evenly over the banks (a bin holds an arbitrary subset of the d channels), so the blocks are
+    // first dealt to the bins with that in mind: each to the bin whose fullest bank it raises least
+    // above the level of an even spread, then pairs of blocks are exchanged between bins while that
+    // lowers the sum of the bins' fullest banks.  Inside a bin the blocks keep their order.
     std::vector<int32_t> block_at(nblocks);                 // block_at[place] = block of perm
     {
         std::vector<std::array<int32_t, 32>> hist(nblocks);
@@ -280,60 +282,69 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
             hist[j].fill(0);
             for (int32_t i = 0; i < b; ++i) ++hist[j][bank_of(perm[(size_t)j * b + i])];
         }
-        const int tiles = s.tiles;
-        std::vector<int32_t> cap(tiles), tile_of(nblocks, -1);
-        std::vector<std::array<int32_t, 32>> total(tiles);
-        std::vector<int32_t> filled(tiles, 0);
-        for (int t = 0; t < tiles; ++t) {
-            cap[t] = std::min<int32_t>(4096, d - 4096 * t) / b;
-            total[t].fill(0);
+        const int ndom = (!s.high_k && b < 128) ? 128 / b : 1;
+        const int bins = s.tiles * ndom;
+        std::vector<int32_t> cap(bins), bin_of(nblocks, -1);
+        std::vector<std::array<int32_t, 32>> total(bins);
+        std::vector<int32_t> filled(bins, 0);
+        for (int q = 0; q < bins; ++q) {
+            cap[q] = std::min<int32_t>(4096, d - 4096 * (q / ndom)) / b / ndom;
+            total[q].fill(0);
         }
-        auto peak_with = [&](int t, int32_t add, int32_t drop) {
+        auto peak_with = [&](int q, int32_t add, int32_t drop) {
             int32_t m = 0;
             for (int k = 0; k < 32; ++k)
-                m = std::max(m, total[t][k] + (add >= 0 ? hist[add][k] : 0) - (drop >= 0 ? hist[drop][k] : 0));
+                m = std::max(m, total[q][k] + (add >= 0 ? hist[add][k] : 0) - (drop >= 0 ? hist[drop][k] : 0));
             return m;
         };
-        if (tiles > 1 && cap[0] > 1) {
+        if (bins > 1 && cap[0] > 1) {
             for (int32_t j = 0; j < nblocks; ++j) {
                 int best = -1;
                 int64_t best_cost = 0;
-                for (int t = 0; t < tiles; ++t) {
-                    if (filled[t] == cap[t]) continue;
+                for (int q = 0; q < bins; ++q) {
+                    if (filled[q] == cap[q]) continue;
                     // excess of the fullest bank over an even spread, in units of 1/32 channel
-                    const int64_t cost = (int64_t)peak_with(t, j, -1) * 32 - (int64_t)(filled[t] + 1) * b;
-                    if (best < 0 || cost < best_cost || (cost == best_cost && cap[t] - filled[t] > cap[best] - filled[best])) {
-                        best = t;
+                    const int64_t cost = (int64_t)peak_with(q, j, -1) * 32 - (int64_t)(filled[q] + 1) * b;
+                    if (best < 0 || cost < best_cost || (cost == best_cost && cap[q] - filled[q] > cap[best] - filled[best])) {
+                        best = q;
                         best_cost = cost;
                     }
                 }
-                tile_of[j] = best;
+                bin_of[j] = best;
                 ++filled[best];
                 for (int k = 0; k < 32; ++k) total[best][k] += hist[j][k];
             }
-            for (int pass = 0; pass < 4; ++pass) {
+            const int passes = nblocks > 1024 ? 1 : 4;      // (pairs of blocks: quadratic)
+            for (int pass = 0; pass < passes; ++pass) {
                 bool changed = false;
                 for (int32_t x = 0; x < nblocks; ++x)
                     for (int32_t y = x + 1; y < nblocks; ++y) {
-                        const int tx = tile_of[x], ty = tile_of[y];
-                        if (tx == ty) continue;
-                        const int32_t before = peak_with(tx, -1, -1) + peak_with(ty, -1, -1);
-                        const int32_t after = peak_with(tx, y, x) + peak_with(ty, x, y);
+                        const int qx = bin_of[x], qy = bin_of[y];
+                        if (qx == qy) continue;
+                        const int32_t before = peak_with(qx, -1, -1) + peak_with(qy, -1, -1);
+                        const int32_t after = peak_with(qx, y, x) + peak_with(qy, x, y);
                         if (after < before) {
                             for (int k = 0; k < 32; ++k) {
-                                total[tx][k] += hist[y][k] - hist[x][k];
-                                total[ty][k] += hist[x][k] - hist[y][k];
+                                total[qx][k] += hist[y][k] - hist[x][k];
+                                total[qy][k] += hist[x][k] - hist[y][k];
                             }
-                            std::swap(tile_of[x], tile_of[y]);
+                            std::swap(bin_of[x], bin_of[y]);
                             changed = true;
                         }
                     }
                 if (!changed) break;
             }
-            int32_t place = 0;
-            for (int t = 0; t < tiles; ++t)
-                for (int32_t j = 0; j < nblocks; ++j)
-                    if (tile_of[j] == t) block_at[place++] = j;
+            std::vector<int32_t> next(bins, 0);             // blocks placed so far, per bin
+            int32_t tile_first = 0;                         // first block place of the tile
+            for (int t = 0; t < s.tiles; ++t) {
+                for (int32_t j = 0; j < nblocks; ++j) {
+                    const int q = bin_of[j];
+                    if (q / ndom != t) continue;
+                    block_at[tile_first + next[q] * ndom + q % ndom] = j;
+                    ++next[q];
+                }
+                tile_first += std::min<int32_t>(4096, d - 4096 * t) / b;
+            }
         } else {
             std::iota(block_at.begin(), block_at.end(), 0);
         }
