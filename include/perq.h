@@ -158,13 +158,21 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  * The result is a different permutation with the same blocks: whatever is merged offline must be
  * merged with perm_out.  Shapes the arrangement does not apply to (d < 4096, d % 512 != 0,
  * b > 4096, b not a power of two) are copied unchanged.
+ * The order inside a block is not free in every respect: Algorithm 1 fills a block heaviest channel
+ * first, so the outlier channels of a block meet the first columns of H_b, whose sums take few
+ * distinct values.  On blocks that hold several outliers (b >= 512) the per-token INT4 error of the
+ * synthetic workloads is 2-15 % lower in that order than in any other order of the same sets
+ * (MXFP4, and any format at b <= 256: no difference).  `head` positions at the start of every
+ * block therefore keep the channels they were given: head < 0 means 64 for b >= 512 and 0 below,
+ * head = 0 moves everything.
  *   perm, perm_out  host, int32 [d]; perm must be a bijection on [0,d); may be the same array
+ *   head            -1, or 0 .. b
  * perq_perm_gather_cost reports what the arrangement is about: `reads` = read instructions per
  * half-wave and row, `passes` = the sum over them of the largest number of lanes that meet in one
  * bank on different words (passes == reads: no conflicts).  PERQ_ERR_UNSUPPORTED for the shapes
  * listed above.
  */
-perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32_t b, int32_t* perm_out);
+perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32_t b, int32_t head, int32_t* perm_out);
 perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, int32_t b, int64_t* passes, int64_t* reads);
 
 /*

@@ -60,7 +60,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_perm_validate.restype = ctypes.c_int
     lib.perq_perm_validate.argtypes = [vp, i32]
     lib.perq_perm_arrange.restype = ctypes.c_int
-    lib.perq_perm_arrange.argtypes = [vp, i32, i32, vp]
+    lib.perq_perm_arrange.argtypes = [vp, i32, i32, i32, vp]
     lib.perq_perm_gather_cost.restype = ctypes.c_int
     lib.perq_perm_gather_cost.argtypes = [vp, i32, i32, vp, vp]
     lib.perq_permute_rotate_quant.restype = ctypes.c_int
@@ -159,11 +159,13 @@ def perq_perm_zigzag(stat: np.ndarray, b: int) -> np.ndarray:
     return perm
 
 
-def perq_perm_arrange(perm: np.ndarray, b: int) -> np.ndarray:
-    """perm with the channels of every block reordered for the kernel's LDS gather (same blocks)."""
+def perq_perm_arrange(perm: np.ndarray, b: int, head: int = -1) -> np.ndarray:
+    """perm with the channels of every block reordered for the kernel's LDS gather (same blocks);
+    the first `head` positions of every block stay as given (-1: 64 for b >= 512, else 0)."""
     p = np.ascontiguousarray(perm, dtype=np.int32)
     out = np.empty_like(p)
-    st = load().perq_perm_arrange(p.ctypes.data_as(ctypes.c_void_p), p.size, int(b), out.ctypes.data_as(ctypes.c_void_p))
+    st = load().perq_perm_arrange(p.ctypes.data_as(ctypes.c_void_p), p.size, int(b), int(head),
+                                  out.ctypes.data_as(ctypes.c_void_p))
     _check(st, "perq_perm_arrange")
     return out
 

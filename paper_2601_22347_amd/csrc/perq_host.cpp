@@ -258,8 +258,10 @@ extern "C" perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, i
     return PERQ_OK;
 }
 
-extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32_t b, int32_t* perm_out) {
+extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32_t b, int32_t head, int32_t* perm_out) {
     if (perm == nullptr || perm_out == nullptr || d <= 0 || b <= 0 || d % b != 0) return PERQ_ERR_INVALID_ARG;
+    if (head < 0) head = b >= 512 ? 64 : 0;
+    if (head > b) return PERQ_ERR_INVALID_ARG;
     if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
     const GatherShape s = gather_shape(d, b);
     if (!s.ok) {                       // no such gather for this shape: nothing to gain, nothing changed
@@ -350,10 +352,18 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         }
     }
     // the channels of every block, by bank (ascending inside a bank: the result is deterministic)
-    std::vector<std::vector<int32_t>> pool((size_t)nblocks * 32);
+    // The first `head` positions of every block keep the channels they were given (each is a pool of
+    // its own with one channel); the others share the pool of their block.
+    std::vector<int32_t> pool_of(d);
+    {
+        int32_t next_pool = nblocks;
+        for (int32_t pos = 0; pos < d; ++pos) pool_of[pos] = pos % b < head ? next_pool++ : pos / b;
+    }
+    std::vector<std::vector<int32_t>> pool((size_t)(nblocks + (size_t)nblocks * head) * 32);
     for (int32_t j = 0; j < nblocks; ++j) {
         const int32_t* src = perm + (size_t)block_at[j] * b;
-        std::vector<int32_t> chans(src, src + b);
+        for (int32_t i = 0; i < head; ++i) pool[(size_t)pool_of[j * b + i] * 32 + bank_of(src[i])].push_back(src[i]);
+        std::vector<int32_t> chans(src + head, src + b);
         std::sort(chans.begin(), chans.end(), std::greater<int32_t>());
         for (int32_t c : chans) pool[(size_t)j * 32 + bank_of(c)].push_back(c);     // taken from the back
     }
@@ -366,7 +376,7 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         int order[32], lane_bank[32], bank_lane[32];
         std::vector<int> adj[32];
         for (int i = 0; i < n; ++i) {
-            const size_t blk = (size_t)(pos[i] / b) * 32;
+            const size_t blk = (size_t)pool_of[pos[i]] * 32;
             for (int k = 0; k < 32; ++k)
                 if (!pool[blk + k].empty()) adj[i].push_back(k);
             std::stable_sort(adj[i].begin(), adj[i].end(), [&](int x, int y) { return pool[blk + x].size() > pool[blk + y].size(); });
@@ -377,10 +387,10 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         std::stable_sort(order, order + n, [&](int x, int y) { return adj[x].size() < adj[y].size(); });
         // (for the lanes left over below) two lanes of one block may not both count on the last channel of a bank
         auto free_in = [&](int lane, int bank) {
-            const size_t blk = (size_t)(pos[lane] / b) * 32;
+            const size_t blk = (size_t)pool_of[pos[lane]] * 32;
             size_t taken = 0;
             for (int i = 0; i < n; ++i)
-                if (i != lane && lane_bank[i] == bank && (size_t)(pos[i] / b) * 32 == blk) ++taken;
+                if (i != lane && lane_bank[i] == bank && (size_t)pool_of[pos[i]] * 32 == blk) ++taken;
             return pool[blk + bank].size() > taken;
         };
         bool visited[32];
@@ -417,7 +427,7 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
             ++load[best];
         }
         for (int i = 0; i < n; ++i) {
-            std::vector<int32_t>& from = pool[(size_t)(pos[i] / b) * 32 + lane_bank[i]];
+            std::vector<int32_t>& from = pool[(size_t)pool_of[pos[i]] * 32 + lane_bank[i]];
             arranged[pos[i]] = from.back();
             from.pop_back();
         }

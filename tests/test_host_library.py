@@ -163,8 +163,47 @@ def test_perm_arrange_keeps_every_block_and_lowers_the_gather_cost(d, b):
         assert r0 == r1 and r0 <= 128 * ((d + 4095) // 4096)
         assert p1 >= r1 and p0 >= r0
         assert p1 <= 0.65 * p0, (p0, p1, r1)       # a random order costs about 3.4 passes per read
-        if b >= 128:
-            assert p1 <= 1.4 * r1, (p1, r1)
+        if b >= 128:        # (from b = 512 on, 64 positions per block stay where they are)
+            assert p1 <= (1.65 if b >= 512 else 1.4) * r1, (p1, r1)
+
+
+def test_perm_arrange_keeps_the_head_of_every_block():
+    """The first `head` positions of a block stay as Algorithm 1 filled them (heaviest channels first)."""
+    rng = np.random.default_rng(12)
+    for d, b, head in [(4096, 1024, -1), (8192, 512, -1), (14336, 2048, 32), (4096, 4096, 128), (4096, 128, 16)]:
+        a = np.exp(rng.normal(0, 1.5, d)).astype(np.float32)
+        perm = binding.perq_massdiff_perm(a, b)
+        out = binding.perq_perm_arrange(perm, b, head)
+        h = 64 if head < 0 else head
+        given = {tuple(sorted(blk)): blk for blk in perm.reshape(-1, b)}
+        for blk in out.reshape(-1, b):
+            src = given[tuple(sorted(blk))]
+            assert np.array_equal(blk[:h], src[:h])
+        assert not np.array_equal(out, perm)
+    with pytest.raises(binding.PerqError):
+        binding.perq_perm_arrange(np.arange(4096, dtype=np.int32), 128, 129)
+
+
+def test_order_inside_large_blocks_matters_for_int4_and_the_default_head_keeps_it():
+    """On blocks with several outlier channels the per-token INT4 error (oracle) is lower in
+    Algorithm 1's order than in an order that moves the heavy channels; with the default head the
+    arranged permutation quantizes as well as the given one."""
+    from oracle import perq_oracle as orc
+    from paper_2601_22347_amd import synth
+    wl = synth.ALL["llama8b_d4096"]()
+    a = orc.colabs_mean(orc.bf16_bits_to_f64(wl.calib_rows()))
+    x = wl.apply_rows(0, 96)
+
+    def err(p, b):
+        r = orc.perq_apply(x, p, b, "int4")
+        return np.linalg.norm(r["y"] - orc.dequant_int4(r["codes"], r["scales"])) / np.linalg.norm(r["y"])
+    for b in (2048,):
+        g = orc.massdiff_greedy(a, b)
+        e_given, e_default, e_all = err(g, b), err(binding.perq_perm_arrange(g, b), b), err(binding.perq_perm_arrange(g, b, 0), b)
+        assert abs(e_default / e_given - 1) < 0.02, (e_given, e_default)
+        assert e_all > 1.05 * e_given, (e_given, e_all)
+    g = orc.massdiff_greedy(a, 128)
+    assert abs(err(binding.perq_perm_arrange(g, 128), 128) / err(g, 128) - 1) < 0.01     # small blocks: no difference
 
 
 def test_perm_arrange_gather_cost_model_on_known_orders():
