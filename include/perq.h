@@ -149,16 +149,16 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  * fetches every operand element with a 2-byte LDS read of its own, and on arbitrary channel
  * orders the lanes of one read instruction meet in the same LDS banks.  Algorithm 1 decides which
  * channels share a block -- that fixes the block masses and with them the bound of Proposition 2
- * and Corollary 3.3 -- while the order inside a block is free: P is merged into the neighbouring
- * weights whatever it is (Section 4, remark on merging permutations), and so is the place of a
- * block in the row.  perq_perm_arrange keeps the channel set of every block of b positions, deals
+ * and Corollary 3.3 -- while those bounds do not depend on the order inside a block or on the
+ * place of a block in the row, and P is merged into the neighbouring weights whatever it is
+ * (Section 4, remark on merging permutations).  perq_perm_arrange keeps the channel set of every block of b positions, deals
  * the blocks to the kernel's 4096-wide tiles so that every tile's channels spread evenly over the
  * banks, and orders every block so that the lanes of a read instruction meet different banks
  * (measured: d = 14336, b = 128, INT4, T = 32768: 237 -> 212 us).
  * The result is a different permutation with the same blocks: whatever is merged offline must be
  * merged with perm_out.  Shapes the arrangement does not apply to (d < 4096, d % 512 != 0,
  * b > 4096, b not a power of two) are copied unchanged.
- * The order inside a block is not free in every respect: Algorithm 1 fills a block heaviest channel
+ * The typical error does depend on the order in one respect: Algorithm 1 fills a block heaviest channel
  * first, so the outlier channels of a block meet the first columns of H_b, whose sums take few
  * distinct values.  On blocks that hold several outliers (b >= 512) the per-token INT4 error of the
  * synthetic workloads is 2-15 % lower in that order than in any other order of the same sets
