@@ -231,12 +231,11 @@ void for_each_read(int32_t d, const GatherShape& s, F&& visit) {
 
 }  // namespace
 
-extern "C" perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, int32_t b, int64_t* passes,
-                                               int64_t* reads) {
-    if (perm == nullptr || passes == nullptr || reads == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
-    if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
-    const GatherShape s = gather_shape(d, b);
-    if (!s.ok) return PERQ_ERR_UNSUPPORTED;
+namespace {
+
+// sum over the read instructions (per half-wave) of the largest number of lanes that meet in one bank
+// on different words; *reads = number of such instructions
+int64_t gather_passes(const int32_t* perm, int32_t d, const GatherShape& s, int64_t* reads) {
     int64_t total = 0, count = 0;
     for_each_read(d, s, [&](const int32_t* pos, int n) {
         // lanes in one bank are served one after another unless they want the same four bytes
@@ -253,8 +252,19 @@ extern "C" perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, i
         total += *std::max_element(load, load + 32);
         ++count;
     });
-    *passes = total;
-    *reads = count;
+    if (reads != nullptr) *reads = count;
+    return total;
+}
+
+}  // namespace
+
+extern "C" perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, int32_t b, int64_t* passes,
+                                               int64_t* reads) {
+    if (perm == nullptr || passes == nullptr || reads == nullptr || d <= 0) return PERQ_ERR_INVALID_ARG;
+    if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
+    const GatherShape s = gather_shape(d, b);
+    if (!s.ok) return PERQ_ERR_UNSUPPORTED;
+    *passes = gather_passes(perm, d, s, reads);
     return PERQ_OK;
 }
 
@@ -433,6 +443,10 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
         }
     });
     if (broken) return PERQ_ERR_LAUNCH;
+    // never worse than what was given (heads that stay in place can meet in one bank when the given
+    // order is regular, e.g. blocks of consecutive channels)
+    if (gather_passes(arranged.data(), d, s, nullptr) >= gather_passes(perm, d, s, nullptr))
+        std::copy(perm, perm + d, arranged.begin());
     std::copy(arranged.begin(), arranged.end(), perm_out);
     return PERQ_OK;
 }
