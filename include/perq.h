@@ -164,7 +164,8 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  * synthetic workloads is 2-15 % lower in that order than in any other order of the same sets
  * (MXFP4, and any format at b <= 256: no difference).  `head` positions at the start of every
  * block therefore keep the channels they were given: head < 0 means 64 for b >= 512 and 0 below,
- * head = 0 moves everything.
+ * head = 0 moves everything.  If the result would cost more passes (perq_perm_gather_cost) than
+ * perm itself, perm is returned.
  *   perm, perm_out  host, int32 [d]; perm must be a bijection on [0,d); may be the same array
  *   head            -1, or 0 .. b
  * perq_perm_gather_cost reports what the arrangement is about: `reads` = read instructions per
