@@ -73,6 +73,17 @@ def test_full_size_config(name, bs, count):
         print("       ", rep.summary(), flush=True)
         assert rep.ok(), (rep.summary(), rep.notes[:5])
         del codes, scales, codes2, scales2
+        if perm is not None and b == 128 and name.startswith("llama8b"):
+            # the same launch with the permutation's blocks arranged for the LDS gather
+            arranged = binding.perq_perm_arrange(perm, b)
+            assert binding.perq_perm_gather_cost(arranged, b)[0] < binding.perq_perm_gather_cost(perm, b)[0]
+            codes, scales = binding.perq_permute_rotate_quant(x, torch.from_numpy(arranged).cuda(), b, wl.fmt)
+            torch.cuda.synchronize()
+            rep = parity.compare_apply(x_bits[rows], arranged, b, wl.fmt, codes[rows_t].cpu().numpy(),
+                                       scales[rows_t].cpu().numpy())
+            print("        arranged:", rep.summary(), flush=True)
+            assert rep.ok(), (rep.summary(), rep.notes[:5])
+            del codes, scales
 
 
 def test_calibration_equalises_block_mass_and_lowers_the_rotated_maximum():
