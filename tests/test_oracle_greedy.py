@@ -118,6 +118,34 @@ def test_sorted_and_zigzag_permutations_closed_forms():
     assert orc.block_masses(g, orc.perm_zigzag(g, 4), 4).max() < orc.block_masses(g, orc.perm_sorted_desc(g), 4).max()
 
 
+def test_colabs_max_hand_case_and_relations():
+    """Per-channel l_inf over the tokens (the statistic of the ablation's absmax / ZigZag rows,
+    Appendix C): a hand-worked case, then what any maximum of magnitudes must satisfy."""
+    # channel 0: the largest magnitude is negative; 1: +2 and -2 tie; 2: all zero; 3: a maximum in the
+    # last row, smaller negative entries before it
+    X = np.array([[-5.0, 2.0, 0.0, -0.25],
+                  [3.0, -2.0, -0.0, -0.5],
+                  [-1.0, 1.0, 0.0, 0.75]])
+    assert orc.colabs_max(X).tolist() == [5.0, 2.0, 0.0, 0.75]
+    # a transposed reading (maximum per token instead of per channel) gives another shape and values
+    assert orc.colabs_max(X).shape == (4,)
+    R = np.random.default_rng(8).standard_t(3, size=(257, 41))
+    m = orc.colabs_max(R)
+    a = orc.colabs_mean(R)
+    assert np.all(m >= a) and np.all(m <= 257 * a * (1 + 1e-12))        # mean <= max <= sum
+    # entry by entry against plain Python, and the maximum is attained by some token
+    for i in range(41):
+        col = [abs(float(v)) for v in R[:, i]]
+        assert m[i] == max(col) and m[i] in col
+    # invariances: sign flips and a reordering of the tokens change nothing; one row: |x|
+    assert np.array_equal(orc.colabs_max(-R), m) and np.array_equal(orc.colabs_max(R[::-1]), m)
+    assert np.array_equal(orc.colabs_max(R[:1]), np.abs(R[0]))
+    # scaling one channel scales its statistic only
+    S = R.copy(); S[:, 7] *= -3.0
+    want = m.copy(); want[7] *= 3.0
+    assert np.array_equal(orc.colabs_max(S), want)
+
+
 def test_block_diagnostics_bounds_and_special_cases():
     from paper_2601_22347_amd import synth
     rng = np.random.default_rng(6)
