@@ -15,10 +15,15 @@
  * Conventions
  *   - "device" pointers are HIP device memory on the current device, "host" pointers are
  *     ordinary host memory.  Every buffer is owned by the caller; the library allocates nothing
- *     and frees nothing.  Its only state is a small table of scheduling counters in device
- *     memory that every launch leaves at zero (consecutive launches rotate through 64 sets of
- *     them, so launches overlapping on different streams do not meet in one set unless 64
- *     launches lie between them while the older is still running).
+ *     and frees nothing.  Its only state on a device is a table of scheduling counters (64 sets of
+ *     32, in device memory of the library's own) for the run-time row schedule of its main kernel.
+ *     Every launch leaves its counters at zero, and a set belongs to one stream: the first 64
+ *     streams per device that reach that kernel get a set each and keep it for the life of the
+ *     process.  Launches of one stream never run side by side, so no two launches draw from one
+ *     set at the same time, however many streams overlap.  A launch from a 65th stream, and any
+ *     launch that is being captured into a graph (a graph can be replayed beside anything), takes
+ *     a fixed split of the rows instead (same results; the schedule only balances run time,
+ *     about 10 % on the largest shapes).  See perq_schedule_set / perq_reset_schedule.
  *   - bf16 tensors are passed as uint16_t bit patterns, row-major, leading dimension in
  *     elements.
  *   - Device entry points enqueue on `hip_stream` (a hipStream_t, NULL = default stream) and
@@ -43,7 +48,8 @@ typedef enum {
     PERQ_OK = 0,
     PERQ_ERR_INVALID_ARG = 1,  /* null pointer, bad size, b not a power of two in [16,d], ... */
     PERQ_ERR_UNSUPPORTED = 2,  /* valid problem the kernels do not cover (alignment, d too large) */
-    PERQ_ERR_LAUNCH = 3        /* HIP reported an error at launch */
+    PERQ_ERR_LAUNCH = 3,       /* HIP reported an error at launch */
+    PERQ_ERR_INTERNAL = 4      /* a consistency check of the library's own failed (never expected) */
 } perq_status_t;
 
 typedef enum {
@@ -85,6 +91,9 @@ const char* perq_status_string(perq_status_t status);
  *
  * Two deterministic passes (row-slice partial sums in fp32, then a fixed-order reduction);
  * the result does not depend on scheduling.  M == 0 is INVALID_ARG (the mean is undefined).
+ * Accuracy: a partial sum adds at most r - 1 non-negative fp32 terms, r = rows per slice =
+ * max(8, ceil(M / floor(512 / ceil(d / 2048)))), and the second pass works in double, so
+ * |out_mean[i] - a_i| < (r + 1) 2^-24 a_i  (r <= 32 for M <= 4096: below 2.0e-6 relative).
  */
 size_t perq_colabs_mean_workspace_bytes(int64_t M, int32_t d);
 perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
@@ -153,8 +162,7 @@ perq_status_t perq_perm_validate(const int32_t* perm_host, int32_t d);
  * place of a block in the row, and P is merged into the neighbouring weights whatever it is
  * (Section 4, remark on merging permutations).  perq_perm_arrange keeps the channel set of every block of b positions, deals
  * the blocks to the kernel's 4096-wide tiles so that every tile's channels spread evenly over the
- * banks, and orders every block so that the lanes of a read instruction meet different banks
- * (measured: d = 14336, b = 128, INT4, T = 32768: 237 -> 212 us).
+ * banks, and orders every block so that the lanes of a read instruction meet different banks.
  * The result is a different permutation with the same blocks: whatever is merged offline must be
  * merged with perm_out.  Shapes the arrangement does not apply to (d < 4096, d % 512 != 0,
  * b > 4096, b not a power of two) are copied unchanged.
@@ -260,6 +268,29 @@ perq_status_t perq_w4a4_gemm_ref(const uint8_t* a_codes, const float* a_scales, 
 perq_status_t perq_w4a4_mxfp4_gemm_ref(const uint8_t* a_codes, const uint8_t* a_scales, int64_t T,
                                        const uint8_t* w_codes, const uint8_t* w_scales, int32_t N, int32_t d,
                                        float* out, int64_t ldo, void* hip_stream);
+
+/*
+ * The run-time row schedule of the main kernel (see "Conventions" above).
+ *   perq_schedule_set    the counter set launches on `hip_stream` draw from, 0 .. 63 (assigned at
+ *                        the first call for that stream, by this function or by a launch), or -1
+ *                        when such launches take the fixed split: the stream is capturing, or 64
+ *                        other streams of the current device came first.
+ *   perq_reset_schedule  enqueues a small kernel on `hip_stream` that puts every counter of the
+ *                        current device back to zero.  Never needed after launches that ran to
+ *                        their end; for a process that goes on after a kernel of the library was
+ *                        cut short.  Must not overlap a launch of the fused path on another stream.
+ *   perq_schedule_selftest  host only: a model of the schedule on the kernel's own queue
+ *                        arithmetic -- n_blocks workgroups of workers_per_block workers each draw
+ *                        their units in a seeded random interleaving, `launches` times on the same
+ *                        counters.  OK iff every unit was taken exactly once, every queue handed out
+ *                        units + workers tickets and every counter ended at zero; UNSUPPORTED for a
+ *                        shape that would not use the queues (n_blocks % 256 != 0 or fewer than two
+ *                        units per worker); INTERNAL on a violation.
+ */
+int32_t perq_schedule_set(void* hip_stream);
+perq_status_t perq_reset_schedule(void* hip_stream);
+perq_status_t perq_schedule_selftest(int64_t n_units, int32_t n_blocks, int32_t workers_per_block,
+                                     uint64_t seed, int32_t launches);
 
 #ifdef __cplusplus
 }

@@ -14,7 +14,7 @@ import numpy as np
 PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(PKG, "libperq.so")
 
-PERQ_OK, PERQ_ERR_INVALID_ARG, PERQ_ERR_UNSUPPORTED, PERQ_ERR_LAUNCH = 0, 1, 2, 3
+PERQ_OK, PERQ_ERR_INVALID_ARG, PERQ_ERR_UNSUPPORTED, PERQ_ERR_LAUNCH, PERQ_ERR_INTERNAL = 0, 1, 2, 3, 4
 PERQ_FMT_INT4_SYM_TOKEN, PERQ_FMT_MXFP4, PERQ_FMT_INT4_ASYM_TOKEN, PERQ_FMT_FP4_TOKEN = 0, 1, 2, 3
 PERQ_ALGO_AUTO, PERQ_ALGO_BUTTERFLY, PERQ_ALGO_MFMA = 0, 1, 2
 FMT = {"int4": PERQ_FMT_INT4_SYM_TOKEN, "mxfp4": PERQ_FMT_MXFP4, "int4_asym": PERQ_FMT_INT4_ASYM_TOKEN,
@@ -26,7 +26,7 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
            "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref", "perq_perm_arrange",
-           "perq_perm_gather_cost"]
+           "perq_perm_gather_cost", "perq_schedule_set", "perq_reset_schedule", "perq_schedule_selftest"]
 
 _lib = None
 
@@ -86,6 +86,12 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_perm_random.restype = ctypes.c_int
     lib.perq_block_diagnostics.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
     lib.perq_block_diagnostics.restype = ctypes.c_int
+    lib.perq_schedule_set.argtypes = [vp]
+    lib.perq_schedule_set.restype = ctypes.c_int32
+    lib.perq_reset_schedule.argtypes = [vp]
+    lib.perq_reset_schedule.restype = ctypes.c_int
+    lib.perq_schedule_selftest.argtypes = [i64, i32, i32, ctypes.c_uint64, i32]
+    lib.perq_schedule_selftest.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -185,7 +191,21 @@ def perq_perm_validate(perm: np.ndarray) -> bool:
     return load().perq_perm_validate(p.ctypes.data_as(ctypes.c_void_p), p.shape[0]) == PERQ_OK
 
 
+def perq_schedule_selftest(n_units: int, n_blocks: int, workers_per_block: int, seed: int = 0, launches: int = 1) -> int:
+    """Status of the host model of the run-time row schedule (PERQ_OK: consistent)."""
+    return load().perq_schedule_selftest(int(n_units), int(n_blocks), int(workers_per_block), int(seed), int(launches))
+
+
 # ---- device entry points ------------------------------------------------------------------
+def perq_schedule_set(stream=None) -> int:
+    """Counter set of the run-time row schedule for launches on `stream`; -1: fixed split."""
+    return load().perq_schedule_set(_stream_ptr(stream))
+
+
+def perq_reset_schedule(stream=None) -> None:
+    _check(load().perq_reset_schedule(_stream_ptr(stream)), "perq_reset_schedule")
+
+
 def perq_colabs_mean(x, out=None, stream=None):
     """x: CUDA bf16 [M, d] -> CUDA float32 [d]."""
     import torch

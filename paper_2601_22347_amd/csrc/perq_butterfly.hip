@@ -299,13 +299,13 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
                 const Int4Asym q = int4_asym_row(lo, hi);
                 if (live) {
                     uint4 c;
-                    if (!q.clamp) {
+                    if (q.mode == 0) {
                         const uint32_t zn = (uint32_t)q.z * 0x11111111u;
                         c = make_uint4(int4a_pack8(v, q.inv, zn), int4a_pack8(v + 8, q.inv, zn),
                                        int4a_pack8(v + 16, q.inv, zn), int4a_pack8(v + 24, q.inv, zn));
                     } else {
-                        c = make_uint4(int4a_pack8_clamped(v, q.inv, q.z), int4a_pack8_clamped(v + 8, q.inv, q.z),
-                                       int4a_pack8_clamped(v + 16, q.inv, q.z), int4a_pack8_clamped(v + 24, q.inv, q.z));
+                        c = make_uint4(int4a_pack8_clamped(v, q), int4a_pack8_clamped(v + 8, q),
+                                       int4a_pack8_clamped(v + 16, q), int4a_pack8_clamped(v + 24, q));
                     }
                     store_stream16(crow, c);
                     if (t == 0) {

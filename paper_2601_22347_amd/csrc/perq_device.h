@@ -172,24 +172,16 @@ __device__ __forceinline__ uint32_t int4_pack8(const float* v, float inv) {
 // all arithmetic is modulo 2^32 and linear).  As long as every c - z lies in [0, 15] the eight
 // words can be merged first and K + z * 0x11111111 removed once.  c - z = 16 happens only for
 // values within half a step of the row maximum, and only in rows whose two ends round 16 steps
-// apart; such rows take the second routine, which clamps element by element.
+// apart; such rows take the second routine, which clamps element by element (see Int4Asym).
 constexpr uint32_t kInt4AsymBias = (uint32_t)(0x4B400000ull * 0x11111111ull);
-__device__ __forceinline__ int int4a_round(float y, float inv);
 __device__ __forceinline__ uint32_t int4a_pack8(const float* v, float inv, uint32_t z_nibbles) {
     uint32_t acc = __float_as_uint(__builtin_fmaf(v[7], inv, 12582912.0f));
 #pragma unroll
     for (int i = 6; i >= 0; --i) acc = (acc << 4) + __float_as_uint(__builtin_fmaf(v[i], inv, 12582912.0f));
     return acc - kInt4AsymBias - z_nibbles;
 }
-__device__ __forceinline__ uint32_t int4a_pack8_clamped(const float* v, float inv, int z) {
-    uint32_t acc = 0;
-#pragma unroll
-    for (int i = 7; i >= 0; --i) {
-        const int c = int4a_round(v[i], inv) - z;
-        acc = (acc << 4) | (uint32_t)(c < 0 ? 0 : (c > 15 ? 15 : c));
-    }
-    return acc;
-}
+struct Int4Asym;
+__device__ __forceinline__ uint32_t int4a_pack8_clamped(const float* v, const Int4Asym& q);
 
 // ---- FP4 with a real-valued scale: 8 values -> one dword of e2m1 nibbles --------------------
 // y * inv (inv = 6 / row maximum) is handed to the same convert with scale 1.
@@ -209,19 +201,51 @@ __device__ __forceinline__ uint32_t fp4_pack8(const float* v, float inv) {
 struct Int4Asym {
     float inv;          // 15 / (hi - lo), 0 for a constant row
     int z;              // rne(lo * inv), rounded by the very instruction that rounds the elements
-    bool clamp;         // the two ends round 16 steps apart
+    int mode;           // 0: eight elements at a time (int4a_pack8); 1: the two ends round 16 steps apart,
+                        // element-wise with a clip; 2: an offset row, element-wise in double
+    float range;        // hi - lo
 };
 __device__ __forceinline__ int int4a_round(float y, float inv) {
     return (int)(__float_as_uint(__builtin_fmaf(y, inv, 12582912.0f)) - 0x4B400000u);
 }
+// The rounding word is an integer only while |y * inv| < 2^22.  A row that is a large offset plus a
+// small spread (every block one value at its first position, tiny values elsewhere: the rotated row
+// is nearly constant) leaves that range: |lo| * 15 / (hi - lo) can reach 15 * 2^24, the spread being
+// at least one fp32 step of the offset.  Such rows are rounded in double, where lo * inv, y * inv and
+// their difference are exact integers after rint (hi - lo is exact in fp32 there: both ends lie
+// within a factor of two).  z stays below 2^28 and is written out as a float: exact up to 2^24.
+constexpr float kInt4AsymFast = 0x1p21f;
 __device__ __forceinline__ Int4Asym int4_asym_row(float lo, float hi) {
     Int4Asym q;
-    const float range = hi - lo;
-    q.inv = range > 0.0f ? 15.0f / range : 0.0f;
-    // (the rounding is monotonic, so every element of the row lands in [z, round(hi)])
-    q.z = int4a_round(lo, q.inv);
-    q.clamp = int4a_round(hi, q.inv) - q.z > 15;
+    q.range = hi - lo;
+    q.inv = q.range > 0.0f ? 15.0f / q.range : 0.0f;
+    if (__builtin_expect(fmaxf(fabsf(lo), fabsf(hi)) * q.inv < kInt4AsymFast, 1)) {
+        // (the rounding is monotonic, so every element of the row lands in [z, round(hi)])
+        q.z = int4a_round(lo, q.inv);
+        q.mode = int4a_round(hi, q.inv) - q.z > 15 ? 1 : 0;
+    } else {
+        q.z = (int)__builtin_rint((double)lo * (15.0 / (double)q.range));
+        q.mode = 2;
+    }
     return q;
+}
+__device__ __forceinline__ uint32_t int4a_pack8_clamped(const float* v, const Int4Asym& q) {
+    uint32_t acc = 0;
+    if (q.mode == 2) {
+        const double invd = 15.0 / (double)q.range;
+#pragma unroll
+        for (int i = 7; i >= 0; --i) {
+            const int c = (int)(__builtin_rint((double)v[i] * invd) - (double)q.z);
+            acc = (acc << 4) | (uint32_t)(c < 0 ? 0 : (c > 15 ? 15 : c));
+        }
+        return acc;
+    }
+#pragma unroll
+    for (int i = 7; i >= 0; --i) {
+        const int c = int4a_round(v[i], q.inv) - q.z;
+        acc = (acc << 4) | (uint32_t)(c < 0 ? 0 : (c > 15 ? 15 : c));
+    }
+    return acc;
 }
 
 template <int N>

@@ -3,6 +3,7 @@
 #include "perq.h"
 #include "perq_base.h"
 #include "perq_layout.h"
+#include "perq_schedule.h"
 
 #include <algorithm>
 #include <array>
@@ -19,6 +20,7 @@ extern "C" const char* perq_status_string(perq_status_t status) {
         case PERQ_ERR_INVALID_ARG: return "PERQ_ERR_INVALID_ARG";
         case PERQ_ERR_UNSUPPORTED: return "PERQ_ERR_UNSUPPORTED";
         case PERQ_ERR_LAUNCH: return "PERQ_ERR_LAUNCH";
+        case PERQ_ERR_INTERNAL: return "PERQ_ERR_INTERNAL";
     }
     return "PERQ_ERR_UNKNOWN";
 }
@@ -442,11 +444,98 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
             from.pop_back();
         }
     });
-    if (broken) return PERQ_ERR_LAUNCH;
+    if (broken) return PERQ_ERR_INTERNAL;
     // never worse than what was given (heads that stay in place can meet in one bank when the given
     // order is regular, e.g. blocks of consecutive channels)
     if (gather_passes(arranged.data(), d, s, nullptr) >= gather_passes(perm, d, s, nullptr))
         std::copy(perm, perm + d, arranged.begin());
     std::copy(arranged.begin(), arranged.end(), perm_out);
+    return PERQ_OK;
+}
+
+// Host model of the matrix-core kernel's run-time row schedule, on the kernel's own queue
+// arithmetic (perq_schedule.h).  Every worker goes through the kernel's sequence -- two fixed
+// units, one ticket drawn ahead per unit, stop at the first ticket past the queue's end, the
+// drawer of the last ticket stores zero -- while a seeded generator decides whose turn it is, which
+// stands for any timing of the waves.  Checked: every unit is taken exactly once, every queue
+// hands out units + workers tickets, every counter is zero afterwards.
+extern "C" perq_status_t perq_schedule_selftest(int64_t n_units, int32_t n_blocks, int32_t workers_per_block,
+                                                uint64_t seed, int32_t launches) {
+    namespace sch = perq::schedule;
+    if (n_units <= 0 || n_blocks <= 0 || workers_per_block <= 0 || launches <= 0) return PERQ_ERR_INVALID_ARG;
+    if (n_units >= ((int64_t)1 << 31) || (int64_t)n_blocks * workers_per_block >= ((int64_t)1 << 24))
+        return PERQ_ERR_INVALID_ARG;
+    const uint32_t W = (uint32_t)n_blocks * (uint32_t)workers_per_block, U = (uint32_t)n_units;
+    if (!sch::queues_usable(n_blocks, W, n_units)) return PERQ_ERR_UNSUPPORTED;
+    std::vector<uint32_t> ctr(sch::kQueues, 0u);            // one set, kept across the launches
+    struct Worker {
+        uint32_t queue, cur, nxt, nw;
+        uint32_t pending;      // ticket drawn and not yet read
+        bool has_pending, drawing;
+    };
+    uint64_t rng = seed * 0x9E3779B97F4A7C15ull + 0x632BE59BD9B4E019ull;
+    auto next_rand = [&]() {
+        rng ^= rng << 13; rng ^= rng >> 7; rng ^= rng << 17;
+        return rng;
+    };
+    for (int32_t launch = 0; launch < launches; ++launch) {
+        std::vector<uint32_t> taken(U, 0u), tickets(sch::kQueues, 0u);
+        std::vector<Worker> wk(W);
+        std::vector<uint32_t> active(W);
+        for (uint32_t w = 0; w < W; ++w) {
+            const uint32_t block = w / (uint32_t)workers_per_block;
+            wk[w] = Worker{sch::queue_of_block(block), w, w + W, U, 0u, false, true};
+            active[w] = w;
+        }
+        auto draw = [&](Worker& k) {
+            k.pending = ctr[k.queue]++;
+            ++tickets[k.queue];
+            k.has_pending = true;
+        };
+        auto fetch = [&](Worker& k) -> uint32_t {
+            if (!k.drawing) return U;
+            if (!k.has_pending) return U + 1u;                  // (a read without a draw: flagged below)
+            k.has_pending = false;
+            const sch::QueuePlan qp = sch::queue_plan(U, W, k.queue);
+            if (k.pending == qp.last_ticket) ctr[k.queue] = 0u;
+            if (k.pending < qp.units) return sch::unit_of_ticket(qp, k.pending);
+            k.drawing = false;
+            return U;
+        };
+        std::vector<bool> started(W, false);
+        while (!active.empty()) {
+            const size_t pick = (size_t)(next_rand() % active.size());
+            const uint32_t w = active[pick];
+            Worker& k = wk[w];
+            if (!started[w]) {
+                // start of the kernel: the first two units are requested, one ticket drawn and read
+                started[w] = true;
+                draw(k);
+                k.nw = fetch(k);
+                if (k.nw > U) return PERQ_ERR_INTERNAL;
+                continue;
+            }
+            // one pass of the kernel's loop body: the unit is processed, the next ticket drawn at the
+            // refill of the buffer and read at the end
+            if (k.cur >= U) return PERQ_ERR_INTERNAL;
+            ++taken[k.cur];
+            if (k.drawing) draw(k);
+            k.cur = k.nxt;
+            k.nxt = k.nw;
+            k.nw = fetch(k);
+            if (k.nw > U) return PERQ_ERR_INTERNAL;
+            if (k.cur >= U) {
+                if (k.has_pending) return PERQ_ERR_INTERNAL;
+                active[pick] = active.back();
+                active.pop_back();
+            }
+        }
+        for (uint32_t u = 0; u < U; ++u)
+            if (taken[u] != 1u) return PERQ_ERR_INTERNAL;
+        for (uint32_t q = 0; q < sch::kQueues; ++q) {
+            const sch::QueuePlan qp = sch::queue_plan(U, W, q);
+            if (tickets[q] != qp.units + W / sch::kQueues || ctr[q] != 0u) return PERQ_ERR_INTERNAL;
+        }
+    }
     return PERQ_OK;
 }

@@ -31,11 +31,16 @@
 // through `perm`, whose LDS byte addresses each lane computes once and keeps for every row.
 // 16-byte granule g of a row lives in slot g ^ f((g >> 4) & 7), which spreads both patterns
 // over all banks; the swizzle is applied on the global side of the direct-to-LDS load.
+#include "perq.h"
 #include "perq_device.h"
 #include "perq_launch.h"
 #include "perq_layout.h"
+#include "perq_schedule.h"
 
-#include <atomic>
+#include <map>
+#include <mutex>
+#include <thread>
+#include <tuple>
 #include <type_traits>
 
 namespace perq {
@@ -59,13 +64,58 @@ struct MfmaGeom {
     int32_t row_per_half; // 1: folded rows of 2048 in the high-K modes, one real row per half-wave
 };
 
-// Ticket counters of the run-time row schedule: kWorkSets sets (consecutive launches rotate through
-// them, so launches that overlap on different streams do not share one) of kWorkQueues counters,
-// each on a 256-byte line of its own.  Zero at load; every launch leaves its set at zero again.
-constexpr uint32_t kWorkQueues = 32;
-constexpr uint32_t kWorkSets = 64;
-__device__ uint32_t work_ctr[kWorkSets][kWorkQueues][64];
-std::atomic<uint32_t> launch_seq{0};     // host side: launches of this process so far
+// Ticket counters of the run-time row schedule (perq_schedule.h): kSets sets of kQueues counters,
+// each counter on a 256-byte line of its own.  Zero at load; every launch leaves its set at zero.
+// A set belongs to one stream for the life of the process (see stream_counter_set below): launches
+// of one stream run one after the other, so no two launches ever draw from the same set at the same
+// time, whatever the streams do between them.
+using schedule::kQueues;
+using schedule::kSets;
+__device__ uint32_t work_ctr[kSets][kQueues][64];
+
+// Which set of counters a launch on `stream` draws from, or -1: none, the launch takes the fixed
+// stride.  A stream keeps the set it was given first; a launch being captured into a graph gets
+// none (the graph may be replayed on any stream, beside anything), nor does a stream that comes
+// when every set of its device is taken.  The per-thread default stream is a different stream in
+// every host thread and is told apart by the thread.
+struct StreamKey {
+    int device;
+    hipStream_t stream;
+    std::thread::id thread;
+    bool operator<(const StreamKey& o) const {
+        return std::tie(device, stream, thread) < std::tie(o.device, o.stream, o.thread);
+    }
+};
+std::mutex sched_mu;
+std::map<StreamKey, int> sched_sets;
+int sched_taken[64] = {};          // sets handed out so far, per device
+
+int stream_counter_set(hipStream_t stream) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return -1;
+    }
+    if (cs != hipStreamCaptureStatusNone) return -1;
+    StreamKey key;
+    key.device = 0;
+    (void)hipGetDevice(&key.device);
+    if (key.device < 0 || key.device >= 64) return -1;
+    key.stream = stream;
+    key.thread = stream == hipStreamPerThread ? std::this_thread::get_id() : std::thread::id();
+    std::lock_guard<std::mutex> lock(sched_mu);
+    const auto it = sched_sets.find(key);
+    if (it != sched_sets.end()) return it->second;
+    if (sched_taken[key.device] >= (int)kSets) return -1;
+    const int set = sched_taken[key.device]++;
+    sched_sets[key] = set;
+    return set;
+}
+
+__global__ void clear_counters_kernel() {
+    uint32_t* c = &work_ctr[0][0][0];
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < kSets * kQueues * 64u; i += gridDim.x * blockDim.x) c[i] = 0u;
+}
 
 using layout::granule_slot;      // granule -> slot inside a staged row
 using layout::hk_pos;            // high-K mode: position inside the tile of row m, contraction index K
@@ -272,10 +322,10 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // The XCDs of the chip do not get equal shares of the memory bandwidth, and which of them falls
     // behind changes from launch to launch; with a fixed split the launch lasts as long as the
     // slowest one.  So, given enough units, only the first two of every worker are fixed (worker w
-    // takes w and w + W); every further unit is drawn from one of kWorkQueues ticket counters
-    // (queue q owns units 2W + q + kWorkQueues * t).  A queue is shared by the workgroups 8k .. 8k+7
+    // takes w and w + W); every further unit is drawn from one of kQueues ticket counters
+    // (queue q owns units 2W + q + kQueues * t).  A queue is shared by the workgroups 8k .. 8k+7
     // for a few k, one per XCD each, so every queue balances across XCDs, while one counter sees
-    // only 1/kWorkQueues of the atomics (same-address atomics from different XCDs retire at roughly
+    // only 1/kQueues of the atomics (same-address atomics from different XCDs retire at roughly
     // 90 per microsecond).
     //   A ticket is drawn right before the loads of an iteration are issued and read at the end of
     // that iteration, after the wait that leaves only those loads outstanding: vector-memory
@@ -291,10 +341,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     const uint32_t n_workers = wave_local ? gridDim.x * NWAVES : gridDim.x;
     const uint32_t worker = wave_local ? blockIdx.x * NWAVES + (uint32_t)wave : blockIdx.x;
     const uint32_t n_units = (uint32_t)((p.T + unit_rows - 1) / unit_rows);      // (T < 2^31 here)
-    const uint32_t qid = (blockIdx.x >> 3) & (kWorkQueues - 1u);
-    const uint32_t dyn0 = 2u * n_workers + qid;
-    const uint32_t units_q = n_units > dyn0 ? (n_units - dyn0 + kWorkQueues - 1u) / kWorkQueues : 0u;
-    const uint32_t last_ticket = units_q + n_workers / kWorkQueues - 1u;
+    const uint32_t qid = schedule::queue_of_block(blockIdx.x);
+    const schedule::QueuePlan qp = schedule::queue_plan(n_units, n_workers, qid);
     uint32_t* ctr = &work_ctr[g.ctr_set][qid][0];
     bool drawing = dyn && (wave_local || wave == 0);     // one wave draws for a workgroup
     uint32_t own_next = 2;                               // fixed stride: place in the worker's own sequence
@@ -307,8 +355,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             if (!drawing) return n_units;
             uint32_t t;
             asm volatile("v_readfirstlane_b32 %0, v255" : "=s"(t)::"memory");
-            if (t == last_ticket && lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (t < units_q) return dyn0 + kWorkQueues * t;
+            if (t == qp.last_ticket && lane == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (t < qp.units) return schedule::unit_of_ticket(qp, t);
             drawing = false;
             return n_units;
         }
@@ -549,7 +597,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     if (tiny_row(row_max)) { lift_values(v); lo *= kTinyRowLift; hi *= kTinyRowLift; }
                     const Int4Asym qa = int4_asym_row(lo, hi);
                     row_zero = qa.z;
-                    if (!qa.clamp) {
+                    if (qa.mode == 0) {
                         const uint32_t zn = (uint32_t)qa.z * 0x11111111u;
 #pragma unroll
                         for (int q = 0; q < kQ; ++q) {
@@ -559,8 +607,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     } else {
 #pragma unroll
                         for (int q = 0; q < kQ; ++q) {
-                            pk[q][0] = int4a_pack8_clamped(v + q * 16, qa.inv, qa.z);
-                            pk[q][1] = int4a_pack8_clamped(v + q * 16 + 8, qa.inv, qa.z);
+                            pk[q][0] = int4a_pack8_clamped(v + q * 16, qa);
+                            pk[q][1] = int4a_pack8_clamped(v + q * 16 + 8, qa);
                         }
                     }
                 }
@@ -904,9 +952,13 @@ hipError_t launch_mfma_st(const ApplyParams& p, uint32_t fold_mask, hipStream_t 
         const bool wave_local = g.tiles_per_row == 1;
         const int64_t workers = wave_local ? grid * NWAVES : grid;
         const int64_t units = wave_local ? p.T : ngroups;
-        g.dynamic = (grid % (8 * kWorkQueues) == 0 && units >= 2 * workers) ? 1u : 0u;
-        if (g.dynamic) {
-            g.ctr_set = launch_seq.fetch_add(1, std::memory_order_relaxed) % kWorkSets;
+        g.dynamic = 0;
+        if (schedule::queues_usable(grid, workers, units)) {
+            const int set = stream_counter_set(stream);
+            if (set >= 0) {
+                g.dynamic = 1;
+                g.ctr_set = (uint32_t)set;
+            }
         }
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NWAVES * 64), lds_bytes, stream, p, g);
@@ -1001,3 +1053,12 @@ hipError_t launch_mfma(const ApplyParams& p0, int out_kind, hipStream_t stream) 
 }
 
 }  // namespace perq
+
+extern "C" int32_t perq_schedule_set(void* hip_stream) {
+    return perq::stream_counter_set(static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" perq_status_t perq_reset_schedule(void* hip_stream) {
+    hipLaunchKernelGGL(perq::clear_counters_kernel, dim3(64), dim3(256), 0, static_cast<hipStream_t>(hip_stream));
+    return hipGetLastError() == hipSuccess ? PERQ_OK : PERQ_ERR_LAUNCH;
+}

@@ -484,8 +484,8 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                                 } else if constexpr (OUT == OUT_FP4_TOKEN) {
                                     w[k] = fp4_pack8(val + 8 * k, inv);
                                 } else {
-                                    if (!qa.clamp) w[k] = int4a_pack8(val + 8 * k, qa.inv, (uint32_t)qa.z * 0x11111111u);
-                                    else w[k] = int4a_pack8_clamped(val + 8 * k, qa.inv, qa.z);
+                                    if (qa.mode == 0) w[k] = int4a_pack8(val + 8 * k, qa.inv, (uint32_t)qa.z * 0x11111111u);
+                                    else w[k] = int4a_pack8_clamped(val + 8 * k, qa);
                                 }
                             }
                         }

@@ -248,8 +248,8 @@ def test_run_time_schedule_all_rows(T, d, b, fmt, with_perm):
 
 
 def test_run_time_schedule_counters_come_back_to_zero():
-    """More launches in a row than there are sets of ticket counters: a counter that a launch
-    left non-zero would hand the next user of its set the wrong rows."""
+    """Many launches in a row on one stream, i.e. on one set of ticket counters: a counter that a
+    launch left non-zero would hand the next launch the wrong rows."""
     torch = _torch()
     T, d = 4200, 4096
     rng = np.random.default_rng(99)
@@ -328,6 +328,53 @@ def test_token_formats_run_time_schedule(fmt, T, d, b, with_perm):
     rep = parity.compare_apply(x, perm, b, fmt, codes, scales, None)
     print("       ", rep.summary(), flush=True)
     assert rep.ok(), (rep.summary(), rep.notes[:5])
+
+
+# ---- asymmetric INT4 on rows that are a large offset plus a small spread ----------------------------
+@pytest.mark.parametrize("d,b,algo", [(4096, 128, "mfma"), (4096, 4096, "mfma"), (14336, 2048, "mfma"),
+                                      (1024, 64, "butterfly"), (3072, 768, "auto"), (8192, 8192, "auto")])
+def test_int4_asym_offset_rows(d, b, algo):
+    """One value at the head of every block and tiny values elsewhere: the rotated row is a constant
+    plus a spread of a few fp32 steps to a few thousand, and the zero point reaches 10^7.  Against the
+    oracle under the stated tolerance (which is wider than a step on such rows), and, as properties of
+    the device's own fp32 outputs: every code decodes to within half a step (plus the fp32 rounding of
+    the offset) of its value, the row minimum has code 0 and the maximum 14 or 15."""
+    rng = np.random.default_rng(d + b)
+    T = 48
+    x = np.zeros((T, d))
+    eps = 2.0 ** -rng.integers(14, 23, size=(T, 1)).astype(np.float64)          # spread from coarse to a few steps
+    x[:] = eps * rng.standard_normal((T, d))
+    if b & (b - 1) == 0:
+        x[:, ::b] = 16.0 * np.where(rng.random((T, 1)) < 0.5, -1.0, 1.0)
+    else:
+        x[:, ::b] = 16.0                                                        # (first row of a Paley base: all ones)
+    x[T - 1] = 0.0
+    x[T - 1, ::b] = 16.0                                                        # exactly constant after the rotation
+    x_bits = synth.f64_to_bf16_bits(x)
+    print(f"[case] int4_asym offset rows d={d} b={b} algo={algo}", flush=True)
+    codes, scales, y = run_gpu(x_bits, None, b, "int4_asym", algo)
+    rep = parity.compare_apply(x_bits, None, b, "int4_asym", codes, scales, y)
+    print("       ", rep.summary(), flush=True)
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
+    c = parity.unpack_nibbles(codes).astype(np.float64)
+    s, z = scales[:, 0].astype(np.float64), scales[:, 1].astype(np.float64)
+    y = y.astype(np.float64)
+    lo, hi = y.min(axis=1), y.max(axis=1)
+    assert np.all(np.abs(z[:-1]) > 1e3) and np.all(np.abs(z) < 2.0 ** 28) and np.all(z == np.rint(z))
+    exact_z = np.abs(z) < 2.0 ** 24                # (a zero point is handed over as a float: exact up to 2^24)
+    assert exact_z.sum() >= T // 2
+    # (the fp32 test output is the kernel's value times fl(1/sqrt(b)), rounded once more: each end of
+    #  the row carries up to a step of the offset's fp32 grid)
+    assert np.all(np.abs(s - (hi - lo) / 15.0) <= 1e-5 * s + 4.0 * 2.0 ** -24 * np.abs(y).max(axis=1) / 15.0)
+    dq = s[:, None] * (c + z[:, None])
+    slack = 0.5 * s[:, None] * (1 + 1e-3) + 6.0 * 2.0 ** -24 * np.abs(y)
+    worst = (np.abs(dq - y) - slack).max(axis=1)
+    worst[T - 1] = 0.0                                       # (the constant row has no step: nothing decodes)
+    worst[~exact_z] = 0.0
+    assert np.all(worst <= 0), (int(np.argmax(worst)), float(worst.max()), float(s[np.argmax(worst)]))
+    rows = np.arange(T - 1)
+    assert np.all(c[rows, y[:-1].argmin(axis=1)] == 0) and np.all(c[rows, y[:-1].argmax(axis=1)] >= 14)
+    assert np.all(c[T - 1] == 0) and s[T - 1] == 0 and z[T - 1] == 0            # constant row
 
 
 # ---- the codes consumed: W4A4 product with P and the rotation merged into the weights -----------
@@ -472,8 +519,9 @@ def test_calibrated_permutations_ranked_by_the_bound():
 
 # ---- the ticket counters under concurrency and graph replay ------------------------------------------
 def test_run_time_schedule_on_two_streams_and_in_a_graph():
-    """Launches that overlap on two streams draw from different counter sets, and a captured launch
-    can be replayed: every result equals the eager one."""
+    """Every stream has a counter set of its own, so launches that overlap on two streams never draw
+    from the same counters; a launch that is being captured takes the fixed split and can be replayed
+    beside eager launches: every result equals the eager one."""
     torch = _torch()
     rng = np.random.default_rng(123)
     cases = []
@@ -484,6 +532,9 @@ def test_run_time_schedule_on_two_streams_and_in_a_graph():
         cases.append((x, perm, b, fmt, ref))
     torch.cuda.synchronize()
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    sets = [binding.perq_schedule_set(st) for st in streams]
+    assert sets[0] != sets[1] and min(sets) >= 0
+    assert sets == [binding.perq_schedule_set(st) for st in streams]            # a stream keeps its set
     outs = [[], []]
     for rep in range(40):
         for k, st in enumerate(streams):
@@ -506,17 +557,68 @@ def test_run_time_schedule_on_two_streams_and_in_a_graph():
         binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales, stream=st, algo="mfma")   # warm
         st.synchronize()
         with torch.cuda.graph(g, stream=st):
+            assert binding.perq_schedule_set(torch.cuda.current_stream()) == -1   # capturing: fixed split
             binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales,
                                               stream=torch.cuda.current_stream(), algo="mfma")
+    other = torch.cuda.Stream()
     for rep in range(4):
         codes.fill_(0xAA); scales.fill_(-1.0)
         torch.cuda.synchronize()
+        # the replay runs beside eager launches of the same shape on another stream
+        with torch.cuda.stream(other):
+            e1 = binding.perq_permute_rotate_quant(x, perm, b, fmt, stream=other, algo="mfma")
         g.replay()
+        with torch.cuda.stream(other):
+            e2 = binding.perq_permute_rotate_quant(x, perm, b, fmt, stream=other, algo="mfma")
         torch.cuda.synchronize()
         assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"replay {rep}"
+        for e in (e1, e2):
+            assert torch.equal(e[0], ref[0]) and torch.equal(e[1], ref[1]), f"eager beside replay {rep}"
         eager = binding.perq_permute_rotate_quant(x, perm, b, fmt, algo="mfma")
         torch.cuda.synchronize()
         assert torch.equal(eager[0], ref[0])
+
+
+def test_run_time_schedule_more_streams_than_counter_sets_and_reset():
+    """The 65th stream of a device gets no counter set: its launches take the fixed split.  All
+    streams launch at once; every result equals the reference.  perq_reset_schedule leaves the
+    counters usable."""
+    torch = _torch()
+    rng = np.random.default_rng(321)
+    T, d, b, fmt = 4300, 4096, 128, "int4"
+    x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_normal((T, d))))
+    perm = torch.from_numpy(rng.permutation(d).astype(np.int32)).cuda()
+    ref = binding.perq_permute_rotate_quant(x, perm, b, fmt, algo="mfma")
+    torch.cuda.synchronize()
+    # (torch hands out streams from a pool of 32; 80 distinct ones come from the runtime itself)
+    import ctypes
+    hip = ctypes.CDLL("libamdhip64.so")
+    raw = []
+    for _ in range(80):
+        h = ctypes.c_void_p()
+        assert hip.hipStreamCreate(ctypes.byref(h)) == 0
+        raw.append(h)
+    streams = [torch.cuda.ExternalStream(h.value) for h in raw]
+    sets = [binding.perq_schedule_set(st) for st in streams]
+    with_set = [s for s in sets if s >= 0]
+    assert len(set(with_set)) == len(with_set) and max(sets) <= 63          # one set per stream
+    assert sets.count(-1) >= 80 - 64                                         # the late-comers have none
+    outs = []
+    for st in streams:
+        codes, scales = binding.alloc_outputs(T, d, fmt, x.device)
+        with torch.cuda.stream(st):
+            binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales, stream=st, algo="mfma")
+        outs.append((codes, scales))
+    torch.cuda.synchronize()
+    for i, (codes, scales) in enumerate(outs):
+        assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"stream {i} (set {sets[i]})"
+    binding.perq_reset_schedule()
+    again = binding.perq_permute_rotate_quant(x, perm, b, fmt, algo="mfma")
+    torch.cuda.synchronize()
+    assert torch.equal(again[0], ref[0]) and torch.equal(again[1], ref[1])
+    del streams
+    for h in raw:
+        assert hip.hipStreamDestroy(h) == 0
 
 
 # ---- edges of the run-time schedule: exactly two units per worker, one more, strided rows, long T ----

@@ -254,3 +254,25 @@ def test_perm_arrange_is_never_worse_than_the_given_order_on_regular_permutation
                 assert binding.perq_perm_validate(q)
                 assert sorted(map(tuple, np.sort(q.reshape(-1, b), axis=1))) == sorted(map(tuple, np.sort(p.reshape(-1, b), axis=1)))
                 assert binding.perq_perm_gather_cost(q, b)[0] <= binding.perq_perm_gather_cost(p, b)[0]
+
+
+# ---- run-time row schedule of the matrix-core kernel: the host model on the kernel's own arithmetic ----
+@pytest.mark.parametrize("n_units,n_blocks,per_block", [
+    (4096, 512, 4),        # d = 4096: a wave per row, T = 4096 is the first size on the queues (nothing left to draw)
+    (4097, 512, 4), (4160, 512, 4), (32768, 512, 4), (9999, 512, 4),
+    (1024, 512, 1),        # a workgroup per unit, exactly two units each
+    (1025, 512, 1), (8192, 512, 1), (32768, 256, 1), (700, 256, 1),
+])
+def test_schedule_model_takes_every_unit_once_and_leaves_the_counters_at_zero(n_units, n_blocks, per_block):
+    for seed in range(4):
+        # three launches on the same counters: a counter left non-zero would skew the next launch
+        assert binding.perq_schedule_selftest(n_units, n_blocks, per_block, seed, 3) == binding.PERQ_OK
+
+
+def test_schedule_model_rejects_shapes_off_the_queues():
+    UNS, INV = binding.PERQ_ERR_UNSUPPORTED, binding.PERQ_ERR_INVALID_ARG
+    assert binding.perq_schedule_selftest(4095, 512, 4, 0, 1) == UNS       # fewer than two units per worker
+    assert binding.perq_schedule_selftest(8192, 500, 1, 0, 1) == UNS       # queues would not fill evenly
+    assert binding.perq_schedule_selftest(0, 512, 4, 0, 1) == INV
+    assert binding.perq_schedule_selftest(8192, 512, 0, 0, 1) == INV
+    assert binding.status_string(4) == "PERQ_ERR_INTERNAL"

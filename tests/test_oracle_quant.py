@@ -240,6 +240,39 @@ def test_int4_asym_error_bound_end_codes_and_constant_row():
     assert np.all(c0 == 0) and np.all(s0 == 0) and np.all(z0 == 0)
 
 
+def test_int4_asym_offset_rows_with_a_small_spread():
+    """Rows that are a large offset plus a small spread (zero points up to 15 * 2^24 in magnitude, the
+    most an fp32 row allows): the quotients are large integers plus a fraction; the half-step error
+    bound, the end codes and exact rational arithmetic still hold."""
+    from fractions import Fraction
+    rng = _rng(21)
+    for offset, spread in ((1024.0, 2.0 ** -9), (-3.0e4, 2.0 ** -7), (1.0, 2.0 ** -20), (-7.0, 2.0 ** -18)):
+        # dyadic values, so every quotient below is an exact rational of small height
+        Y = offset + spread * np.rint(rng.uniform(-1, 1, size=(6, 64)) * 256) / 256
+        c, s, z = orc.quant_int4_asym_token(Y)
+        assert np.all(np.abs(z) > 1e5) and np.all(z == np.rint(z))
+        dq = orc.dequant_int4_asym(c, s, z)
+        assert np.all(np.abs(Y - dq) <= s[:, None] / 2 * (1 + 1e-6))
+        rows = np.arange(6)
+        assert np.all(c[rows, Y.argmin(axis=1)] == 0) and np.all(c[rows, Y.argmax(axis=1)] >= 14)
+        for r in range(2):
+            lo, hi = Fraction(float(Y[r].min())), Fraction(float(Y[r].max()))
+            step = (hi - lo) / 15
+            def rne(q):
+                f = q.numerator // q.denominator
+                rem = q - f
+                return f + (1 if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and f % 2) else 0)
+            zq = rne(lo / step)
+            near_tie = False
+            want = []
+            for v in Y[r]:
+                q = Fraction(float(v)) / step
+                near_tie |= abs(abs(q - (q.numerator // q.denominator)) - Fraction(1, 2)) < Fraction(1, 10 ** 6)
+                want.append(min(15, max(0, rne(q) - zq)))
+            if not near_tie:           # fp64 decides a quotient of this size to about 1e-9 of a step
+                assert int(z[r]) == zq and c[r].tolist() == want
+
+
 def test_int4_asym_scale_shift_and_reflection():
     Y = _rng(14).standard_normal((10, 64))
     c, s, z = orc.quant_int4_asym_token(Y)
