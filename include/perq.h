@@ -101,6 +101,22 @@ perq_status_t perq_colabs_mean(const uint16_t* x_bf16, int64_t M, int32_t d, int
                                void* hip_stream);
 
 /*
+ * perq_colabs_mean for callers that cannot allocate device memory or hand any over: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same result
+ * bit for bit; the partial sums live in a 4 MiB array that is part of the library's code object
+ * (one copy per device, held until the process ends) instead of a caller's workspace.  The call
+ * itself allocates and frees nothing.  The very first call on a device looks up the array's
+ * address there; make that call outside a capture.
+ *   Limit: perq_colabs_mean_workspace_bytes(M, d) <= 4 MiB, which holds for every M when
+ *   d <= 1048576; beyond it PERQ_ERR_UNSUPPORTED.  Other arguments and errors as perq_colabs_mean.
+ *   All calls on one device share the array: two calls that overlap there (different streams, or
+ *   graph replays side by side) race and give undefined means; calls on one stream are safe.
+ *   Nothing needs clearing between calls (the first pass overwrites every partial the second reads).
+ */
+perq_status_t perq_colabs_mean_static(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                                      float* out_mean, void* hip_stream);
+
+/*
  * max_k |x[k, i]| per channel, the statistic of the "absmax" and ZigZag permutations compared in
  * Appendix C ("Permutations").  Arguments, workspace size and errors as perq_colabs_mean; exact.
  */

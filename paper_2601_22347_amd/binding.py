@@ -26,7 +26,8 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_permute_rotate_quant_algo", "perq_permute_rotate_f32", "perq_w4a4_gemm_ref",
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
            "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref", "perq_perm_arrange",
-           "perq_perm_gather_cost", "perq_schedule_set", "perq_reset_schedule", "perq_schedule_selftest"]
+           "perq_perm_gather_cost", "perq_schedule_set", "perq_reset_schedule", "perq_schedule_selftest",
+           "perq_colabs_mean_static"]
 
 _lib = None
 
@@ -86,6 +87,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_perm_random.restype = ctypes.c_int
     lib.perq_block_diagnostics.argtypes = [vp, i64, i32, i64, vp, i32, vp, vp]
     lib.perq_block_diagnostics.restype = ctypes.c_int
+    lib.perq_colabs_mean_static.argtypes = [vp, i64, i32, i64, vp, vp]
+    lib.perq_colabs_mean_static.restype = ctypes.c_int
     lib.perq_schedule_set.argtypes = [vp]
     lib.perq_schedule_set.restype = ctypes.c_int32
     lib.perq_reset_schedule.argtypes = [vp]
@@ -217,6 +220,14 @@ def perq_colabs_mean(x, out=None, stream=None):
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=x.device)
     st = lib.perq_colabs_mean(_dev_ptr(x), M, d, ldx, _dev_ptr(out), _dev_ptr(ws), nbytes, _stream_ptr(stream))
     _check(st, "perq_colabs_mean")
+    return out
+
+
+def perq_colabs_mean_static(x, out, stream=None):
+    """x: CUDA bf16 [M, d], out: CUDA float32 [d] (caller's); the call allocates nothing."""
+    M, d, ldx = _check_x(x)
+    st = load().perq_colabs_mean_static(_dev_ptr(x), M, d, ldx, _dev_ptr(out), _stream_ptr(stream))
+    _check(st, "perq_colabs_mean_static")
     return out
 
 

@@ -11,6 +11,8 @@
 #include "perq.h"
 #include "perq_launch.h"
 
+#include <mutex>
+
 namespace perq {
 namespace {
 
@@ -101,28 +103,64 @@ extern "C" size_t perq_colabs_mean_workspace_bytes(int64_t M, int32_t d) {
     return (size_t)pl.slices * (size_t)d * sizeof(float);
 }
 
+// Partial sums of perq_colabs_mean_static, for callers that cannot hand over device memory of their
+// own.  In host code this name only stands for the array: its device address is looked up once per
+// device (scratch_of_current_device) and that pointer is what kernels are given.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / sizeof(float)];
+
 namespace perq {
 namespace {
-template <bool MAXSTAT>
-perq_status_t colabs_stat(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx, float* out, void* workspace,
-                          size_t workspace_bytes, void* hip_stream) {
+perq_status_t colabs_check(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx, const float* out) {
     if (x_bf16 == nullptr || out == nullptr) return PERQ_ERR_INVALID_ARG;
     if (M <= 0 || d <= 0 || ldx < d) return PERQ_ERR_INVALID_ARG;
     if (d % 8 != 0 || ldx % 8 != 0 || (reinterpret_cast<uintptr_t>(x_bf16) & 15u) != 0)
         return PERQ_ERR_UNSUPPORTED;
-    const size_t need = perq_colabs_mean_workspace_bytes(M, d);
-    if (workspace == nullptr || workspace_bytes < need) return PERQ_ERR_INVALID_ARG;
-    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return PERQ_ERR_INVALID_ARG;
+    return PERQ_OK;
+}
 
+template <bool MAXSTAT>
+perq_status_t colabs_launch(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx, float* out, float* part,
+                            void* hip_stream) {
     const ColabsPlan pl = colabs_plan(M, d);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    float* part = static_cast<float*>(workspace);
     hipLaunchKernelGGL(colabs_partial_kernel<MAXSTAT>, dim3(pl.col_tiles, pl.slices), dim3(kThreads), 0, stream, x_bf16,
                        M, d, ldx, pl.rows_per_slice, part);
     if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
     hipLaunchKernelGGL(colabs_finish_kernel<MAXSTAT>, dim3((d + kFinishCols - 1) / kFinishCols), dim3(kThreads), 0,
                        stream, part, pl.slices, d, (float)M, out);
     if (hipGetLastError() != hipSuccess) return PERQ_ERR_LAUNCH;
+    return PERQ_OK;
+}
+
+template <bool MAXSTAT>
+perq_status_t colabs_stat(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx, float* out, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    const perq_status_t st = colabs_check(x_bf16, M, d, ldx, out);
+    if (st != PERQ_OK) return st;
+    const size_t need = perq_colabs_mean_workspace_bytes(M, d);
+    if (workspace == nullptr || workspace_bytes < need) return PERQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return PERQ_ERR_INVALID_ARG;
+    return colabs_launch<MAXSTAT>(x_bf16, M, d, ldx, out, static_cast<float*>(workspace), hip_stream);
+}
+
+// Device address of `scratch` on the current device: every device holds its own copy of the array
+// at an address of its own, looked up at the first call with that device current.
+perq_status_t scratch_of_current_device(float** out) {
+    static std::mutex mu;
+    static float* known[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return PERQ_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (known[dev] == nullptr) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+            (void)hipGetLastError();
+            return PERQ_ERR_LAUNCH;
+        }
+        known[dev] = static_cast<float*>(ptr);
+    }
+    *out = known[dev];
     return PERQ_OK;
 }
 }  // namespace
@@ -138,4 +176,15 @@ extern "C" perq_status_t perq_colabs_absmax(const uint16_t* x_bf16, int64_t M, i
                                             float* out_max, void* workspace, size_t workspace_bytes,
                                             void* hip_stream) {
     return perq::colabs_stat<true>(x_bf16, M, d, ldx, out_max, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" perq_status_t perq_colabs_mean_static(const uint16_t* x_bf16, int64_t M, int32_t d, int64_t ldx,
+                                                 float* out_mean, void* hip_stream) {
+    const perq_status_t st = perq::colabs_check(x_bf16, M, d, ldx, out_mean);
+    if (st != PERQ_OK) return st;
+    if (perq_colabs_mean_workspace_bytes(M, d) > kStaticScratchBytes) return PERQ_ERR_UNSUPPORTED;
+    float* part = nullptr;
+    const perq_status_t sp = perq::scratch_of_current_device(&part);
+    if (sp != PERQ_OK) return sp;
+    return perq::colabs_launch<false>(x_bf16, M, d, ldx, out_mean, part, hip_stream);
 }
