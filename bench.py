@@ -56,20 +56,91 @@ def algorithmic_bytes(T: int, d: int, fmt: str) -> int:
 
 
 def read_traffic(name: str, algo: str = "auto", identity: bool = False, arranged: bool = False):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if there is one."""
+    """(HBM bytes per launch, where from) out of the committed rocprofv3 --pmc summary of this
+    workload, if there is one: the figure is that of the profiled build, not of this run, so the
+    file and the kernel line it was taken for are reported with it."""
     if identity:
         name = name.replace("_perm", "_identity")
     elif arranged:
         name = name.replace("_perm", "_perm_arranged")
     if algo == "butterfly":
         name += "_butterfly"
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{name}.txt")
+    rel = os.path.join("profiles", f"hbm_traffic_{name}.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
-        return None
+        return None, None
+    value, kernel = None, None
     for line in open(path):
         if line.startswith("HBM_BYTES_PER_LAUNCH="):
-            return float(line.split("=", 1)[1])
-    return None
+            value = float(line.split("=", 1)[1])
+        if kernel is None and " calls " in line and "perq::" in line and "colabs" not in line:
+            kernel = " ".join(line.split())
+    return value, {"file": rel, "kernel_line": kernel, "note": "committed rocprofv3 summary, not measured in this run"}
+
+
+# The configurations the bandwidth target (T >= 16384, d >= 4096) is quoted on: the headline and the
+# five others, every one timed by the default invocation.
+TARGET_SHAPES = ["llama8b_d4096_b128_int4_perm", "llama8b_d4096_b4096_int4_perm", "llama8b_d14336_b128_int4_perm",
+                 "llama8b_d14336_b2048_int4_perm", "calib_apply_b32_mxfp4_perm", "calib_apply_b16_mxfp4_perm"]
+
+
+def time_target_shape(name, steps, warmup, pool_bytes, algo, check):
+    """One of the other target-size workloads: calibrate, time `steps` launches with HIP events over
+    cycled buffer sets, compare sampled rows with the oracle.  Returns a dict for the report."""
+    import torch
+    from paper_2601_22347_amd import binding, synth
+    key, b, fmt, use_perm = WORKLOADS[name]
+    wl = synth.ALL[key]()
+    T, d = wl.T, wl.d
+    dev = torch.device("cuda:0")
+    x_bits = wl.apply_rows_parallel()
+    perm_np = perm_t = None
+    if use_perm:
+        a_np = binding.perq_colabs_mean(binding.bits_to_device(wl.calib_rows())).cpu().numpy()
+        perm_np = binding.perq_massdiff_perm(a_np, b)
+        perm_t = torch.from_numpy(perm_np).to(dev)
+    per_set = T * d * 2 + T * d // 2
+    nsets = max(2, int(np.ceil(pool_bytes / per_set)))
+    x0 = binding.bits_to_device(x_bits, dev)
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    outs = [binding.alloc_outputs(T, d, fmt, dev) for _ in range(nsets)]
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        k = i % nsets
+        binding.perq_permute_rotate_quant(xs[k], perm_t, b, fmt, codes=outs[k][0], scales=outs[k][1],
+                                          stream=stream, algo=algo)
+    t_ramp = time.perf_counter()
+    while time.perf_counter() - t_ramp < 0.15:
+        for i in range(20):
+            step(i)
+        torch.cuda.synchronize()
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for i in range(steps):
+        step(i)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    alg = algorithmic_bytes(T, d, fmt)
+    res = {"workload": name, "T": T, "d": d, "b": b, "fmt": fmt, "kernel_ms": kern_ms, "algorithmic_bytes": alg,
+           "achieved_GBs": alg / (kern_ms * 1e-3) / 1e9, "frac": alg / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "tokens_per_s": T / (kern_ms * 1e-3)}
+    if check:
+        import parity
+        rng = np.random.default_rng(0)
+        rows = np.unique(np.concatenate([np.arange(16), T - 1 - np.arange(16), rng.choice(T, size=32, replace=False)]))
+        rt = torch.from_numpy(rows).to(dev)
+        last = (steps - 1) % nsets
+        rep = parity.compare_apply(x_bits[rows], perm_np, b, fmt, outs[last][0][rt].cpu().numpy(),
+                                   outs[last][1][rt].cpu().numpy())
+        res["check"] = dict(rep.summary(), rows=int(rows.size), ok=rep.ok())
+    del xs, outs, x0
+    torch.cuda.empty_cache()
+    return res
 
 
 def main() -> int:
@@ -86,7 +157,10 @@ def main() -> int:
                     help="time the calibrated permutation in the order perq_perm_arrange gives its blocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
-    ap.add_argument("--no-context", action="store_true", help="skip the single-buffer-set and device-copy figures")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the single-buffer-set and device-copy figures and the other target-size workloads")
+    ap.add_argument("--no-target-shapes", action="store_true",
+                    help="skip timing the other target-size workloads after the headline")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (token rows would be sharded across GPUs "
@@ -270,6 +344,21 @@ def main() -> int:
             cpu["butterfly_variant"] = {"value": n3 / f_s, "unit": "tokens/s",
                                         "sample": f"first {n3} tokens, fp64 radix-2 butterflies, {f_s:.1f} s"}
 
+    traffic, traffic_source = read_traffic(args.workload, args.algo, args.identity, args.arranged and use_perm)
+
+    # ---- the other target-size workloads, same number of steps each (context, not the value) ----
+    if context is not None and not args.no_target_shapes and args.workload == DEFAULT and not (args.identity or args.arranged):
+        del xs, outs, x0
+        torch.cuda.empty_cache()
+        shapes = [{"workload": args.workload, "T": T, "d": d, "b": b, "fmt": fmt, "kernel_ms": kern_ms,
+                   "algorithmic_bytes": alg_bytes, "achieved_GBs": achieved, "frac": achieved / HBM_PEAK_GBS,
+                   "tokens_per_s": T / (kern_ms * 1e-3), "check": check}]
+        for name in TARGET_SHAPES:
+            if name != args.workload:
+                shapes.append(time_target_shape(name, args.steps, args.warmup, args.pool_bytes, args.algo,
+                                                not (args.no_check or args.no_cpu_baseline)))
+        context["target_shapes"] = shapes
+
     line = {
         "metric": "fused permute+block-Hadamard+quant tokens/s",
         "value": tokens_per_s,
@@ -288,7 +377,7 @@ def main() -> int:
                             else "greedy-calibrated, gather fused") if use_perm else "identity",
                    "algo": args.algo, "buffer_sets": nsets, "input_gen_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(args.workload, args.algo, args.identity, args.arranged and use_perm),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,
                      "algorithmic_bytes": alg_bytes, "kernel_ms": kern_ms},
         "cpu_baseline": cpu,
         "calibration": calib,
@@ -296,7 +385,10 @@ def main() -> int:
         "check": check,
     }
     print(json.dumps(line))
-    return 0 if (check is None or check["ok"]) else 1
+    ok = check is None or check["ok"]
+    for sh in (context or {}).get("target_shapes", []):
+        ok = ok and (sh.get("check") is None or sh["check"]["ok"])
+    return 0 if ok else 1
 
 
 if __name__ == "__main__":
