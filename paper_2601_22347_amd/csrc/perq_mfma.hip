@@ -162,6 +162,50 @@ __device__ __forceinline__ uint32_t lds_load4(const void* p) {
     return v;
 }
 
+// Element-wise operand gather, written as instructions.  gather8 issues the eight 2-byte reads of
+// one operand fragment (byte addresses a[0..7], plus a constant offset that selects the staging
+// buffer) and returns with them in flight; the values may be used only after a gather_wait that
+// names them.  Reads of LDS return in issue order, so "at most N operations outstanding" proves
+// every read but the last N complete.  Through the compiler the same reads came with a mask of
+// every result and a byte permute per pair (96 vector instructions per tile where 32 do), and all
+// 64 were waited for before the first product could start.
+template <uint32_t OFF>
+__device__ __forceinline__ void gather8(uint32_t (&t)[8], const uint32_t* a) {
+    asm volatile(
+        "ds_read_u16 %0, %8 offset:%16\n\t"
+        "ds_read_u16 %1, %9 offset:%16\n\t"
+        "ds_read_u16 %2, %10 offset:%16\n\t"
+        "ds_read_u16 %3, %11 offset:%16\n\t"
+        "ds_read_u16 %4, %12 offset:%16\n\t"
+        "ds_read_u16 %5, %13 offset:%16\n\t"
+        "ds_read_u16 %6, %14 offset:%16\n\t"
+        "ds_read_u16 %7, %15 offset:%16"
+        : "=&v"(t[0]), "=&v"(t[1]), "=&v"(t[2]), "=&v"(t[3]), "=&v"(t[4]), "=&v"(t[5]), "=&v"(t[6]), "=&v"(t[7])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "n"(OFF)
+        : "memory");
+}
+// Wait until at most N LDS operations of this wave are outstanding; the sixteen values of the two
+// fragments named are valid afterwards (they are operands of the statements so that no use of
+// them can be moved ahead of the wait).
+template <int N>
+__device__ __forceinline__ void gather_wait(uint32_t (&t0)[8], uint32_t (&t1)[8]) {
+    static_assert(N == 0 || N == 12, "");
+    if constexpr (N == 0)
+        asm volatile("s_waitcnt lgkmcnt(0)"
+                     : "+v"(t0[0]), "+v"(t0[1]), "+v"(t0[2]), "+v"(t0[3]), "+v"(t0[4]), "+v"(t0[5]), "+v"(t0[6]), "+v"(t0[7])
+                     :: "memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(12)"
+                     : "+v"(t0[0]), "+v"(t0[1]), "+v"(t0[2]), "+v"(t0[3]), "+v"(t0[4]), "+v"(t0[5]), "+v"(t0[6]), "+v"(t0[7])
+                     :: "memory");
+    asm volatile(""
+                 : "+v"(t1[0]), "+v"(t1[1]), "+v"(t1[2]), "+v"(t1[3]), "+v"(t1[4]), "+v"(t1[5]), "+v"(t1[6]), "+v"(t1[7])
+                 :: "memory");
+}
+__device__ __forceinline__ uint4 pack_fragment(const uint32_t (&t)[8]) {
+    return make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
+}
+
 // STAGES = number of +-1 butterfly stages after the matrix product: log2(b) - 5, 0 for b <= 32.
 // A template parameter so that the accumulators stay in registers along one straight path.
 // SHARED: d = 4096 exactly with a permutation: the four waves of a workgroup, each on whole rows of
@@ -379,45 +423,32 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             if (boxed) u_new = __builtin_amdgcn_readfirstlane(lds_load4(unit_box));   // (uniform: keep it scalar)
         }
 
-        // ---- B operands out of LDS ----------------------------------------------------------
-        uint4 bfrag[kQ][2];
-#pragma unroll
-        for (int q = 0; q < kQ; ++q) {
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt) {
-                if constexpr (kElem) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) {
-                        const uint32_t lo = *reinterpret_cast<const uint16_t*>(lds + kOff + src[(q * 2 + kt) * 8 + e]);
-                        const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds + kOff + src[(q * 2 + kt) * 8 + e + 1]);
-                        w[e >> 1] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);   // low halves of (lo, hi)
-                    }
-                    bfrag[q][kt] = make_uint4(w[0], w[1], w[2], w[3]);
-                } else {
-                    bfrag[q][kt] = *reinterpret_cast<const uint4*>(lds + kOff + src[q * 2 + kt]);
-                }
-            }
-        }
-        // The operands are in registers: refill this buffer right away.  With two buffers the
-        // unit after next goes here, so two units' loads are in flight during the arithmetic.
-        if (!wave_local) workgroup_barrier_lds();
-        {
+        // The refill of this buffer, once its operands are in registers.  With two buffers the unit
+        // after next goes here, so two units' loads are in flight during the arithmetic.
+        auto refill = [&]() {
+            if (!wave_local) workgroup_barrier_lds();
             const uint32_t u_load = kDouble ? u_new : u_nxt;
             if (drawing) draw();
             n_behind = u_load < n_units ? issue_loads(u_load, kOff) : 0;
-        }
-
-        // ---- the matrix product ------------------------------------------------------------------
+        };
+        const f32x16_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         float v[64];
-        if constexpr (!kHighK) {
+        if constexpr (!kElem) {
+            // ---- P = I, b <= 512: one 16-byte read per operand fragment --------------------------
+            uint4 bfrag[kQ][2];
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) {
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt) bfrag[q][kt] = *reinterpret_cast<const uint4*>(lds + kOff + src[q * 2 + kt]);
+            }
+            refill();
             // H_32 (b <= 32), H_64 or H_128: accumulator tile qo = sum over the sub-blocks qi of its
             // block of (+-H_32) * X_qi, the sign being entry (qo, qi) of the Sylvester matrix of
             // order kDense
             constexpr int kDense = STAGES == 0 ? 1 : (STAGES == 1 ? 2 : 4);
 #pragma unroll
             for (int qo = 0; qo < kQ; ++qo) {
-                f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                f32x16_t acc = zero16;
 #pragma unroll
                 for (int j = 0; j < kDense; ++j) {
                     const int qi = (qo & ~(kDense - 1)) | j;
@@ -431,25 +462,61 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 for (int r = 0; r < 16; ++r) v[qo * 16 + r] = acc[r];
             }
         } else {
-            // D[m][n] = sum_K X[m][K] * S[K][n], S = I (x) H_{b/16} on the 128 middle indices (H_64 (x)
-            // I_2 ... for b = 1024, H_128 for b >= 2048).  With K = 32 Kh + Kl and n = 32 nt + j the entry
-            // is H_kHi[Kh][nt] (zero off the block diagonal) times H_32[Kl][j]; the latter is the
-            // constant fragment.
-            constexpr int kHi = STAGES == 5 ? 2 : 4;          // order of the outer factor on Kh
+            // ---- operands gathered element by element, four groups of two fragments; the products
+            //      of a group are issued while the reads of the next two groups are on their way -----
+            // Low-K modes: group g holds sub-block qi = g of the lane; accumulator tile qo of the same
+            // block of kDense sub-blocks takes (+-H_32) * X_qi, the sign being entry (qo, qi) of the
+            // Sylvester matrix of order kDense.
+            // High-K modes: D[m][n] = sum_K X[m][K] * S[K][n], S = I (x) H_{b/16} on the 128 middle
+            // indices (H_64 (x) I_2 ... for b = 1024, H_128 for b >= 2048).  With K = 32 Kh + Kl and
+            // n = 32 nt + j the entry is H_kHi[Kh][nt] (zero off the block diagonal) times H_32[Kl][j];
+            // the latter is the constant fragment, and group g holds Kh = g.
+            // Every accumulator sums its products in ascending (group, fragment) order.
+            constexpr int kGroup = kHighK ? (STAGES == 5 ? 2 : 4) : (STAGES == 0 ? 1 : (STAGES == 1 ? 2 : 4));
+            f32x16_t acc[kQ] = {zero16, zero16, zero16, zero16};
+            uint32_t t[4][2][8];
+            auto products = [&](int g, const uint4& f0, const uint4& f1) {
 #pragma unroll
-            for (int nt = 0; nt < kQ; ++nt) {
-                f32x16_t acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                for (int kt = 0; kt < 8; ++kt) {
-                    const int Kh = kt >> 1;
-                    if ((Kh / kHi) != (nt / kHi)) continue;
-                    const bool neg = __builtin_popcount((Kh % kHi) & (nt % kHi)) & 1;
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, bfrag[kt >> 1][kt & 1]),
-                                                                  neg ? afrag_neg[kt & 1] : afrag[kt & 1], acc, 0, 0, 0);
+                for (int o = 0; o < kQ; ++o) {
+                    if ((o / kGroup) != (g / kGroup)) continue;
+                    const bool neg = __builtin_popcount((o % kGroup) & (g % kGroup)) & 1;
+                    const bf16x8_t d0 = __builtin_bit_cast(bf16x8_t, f0), d1 = __builtin_bit_cast(bf16x8_t, f1);
+                    if constexpr (!kHighK) {
+                        acc[o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(neg ? afrag_neg[0] : afrag[0], d0, acc[o], 0, 0, 0);
+                        acc[o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(neg ? afrag_neg[1] : afrag[1], d1, acc[o], 0, 0, 0);
+                    } else {
+                        acc[o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(d0, neg ? afrag_neg[0] : afrag[0], acc[o], 0, 0, 0);
+                        acc[o] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(d1, neg ? afrag_neg[1] : afrag[1], acc[o], 0, 0, 0);
+                    }
                 }
+            };
+            gather8<kOff>(t[0][0], src + 0);
+            gather8<kOff>(t[0][1], src + 8);
+            gather8<kOff>(t[1][0], src + 16);
+            gather8<kOff>(t[1][1], src + 24);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) v[nt * 16 + r] = acc[r];
+            for (int g = 0; g < kQ; ++g) {
+                // 32 reads were issued after those of group g (none after the last group's): with at
+                // most 12 outstanding, group g has arrived
+                if (g < kQ - 1) gather_wait<12>(t[g][0], t[g][1]);
+                else gather_wait<0>(t[g][0], t[g][1]);
+                const uint4 f0 = pack_fragment(t[g][0]), f1 = pack_fragment(t[g][1]);
+                if (g + 2 < kQ) {
+                    gather8<kOff>(t[g + 2][0], src + 16 * (g + 2));
+                    gather8<kOff>(t[g + 2][1], src + 16 * (g + 2) + 8);
+                }
+                if (g == kQ - 1) refill();
+                products(g, f0, f1);
+                // (keeps the compiler from moving these products behind the next group's wait)
+                __builtin_amdgcn_sched_barrier(0);
             }
+#pragma unroll
+            for (int o = 0; o < kQ; ++o) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) v[o * 16 + r] = acc[o][r];
+            }
+        }
+        if constexpr (kHighK) {
             // position bits 0..3: the 16 contiguous outputs of every accumulator tile
 #pragma unroll
             for (int hh = 1; hh < 16; hh <<= 1) {
@@ -899,6 +966,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 src[f * 8 + e] = ok ? (uint32_t)rr * g.row_bytes + ((granule_slot(cc >> 3) << 4) | ((cc & 7u) << 1)) : kZeroSlot;
             }
         }
+    }
+
+    // the element-wise gather hands these to its read instructions as they are: LDS addresses, not
+    // offsets into the staging buffers
+    if constexpr (kElem) {
+        const uint32_t staging = lds_addr(lds);
+#pragma unroll
+        for (int i = 0; i < 64; ++i) src[i] += staging;
     }
 
     // the first unit has landed; the ticket drawn behind its loads says which unit comes third
