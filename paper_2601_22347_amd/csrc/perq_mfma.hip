@@ -202,6 +202,33 @@ __device__ __forceinline__ void gather_wait(uint32_t (&t0)[8], uint32_t (&t1)[8]
                  : "+v"(t1[0]), "+v"(t1[1]), "+v"(t1[2]), "+v"(t1[3]), "+v"(t1[4]), "+v"(t1[5]), "+v"(t1[6]), "+v"(t1[7])
                  :: "memory");
 }
+// The same for the eight values of one fragment, N = 0 or 8, with the four shift-or instructions
+// that pack them in the same statement: left to the compiler they sink to where the operands are
+// used, a whole epilogue later, and the eight unpacked values of every fragment stay live until then.
+template <int N>
+__device__ __forceinline__ uint4 gather_wait8_pack(const uint32_t (&t)[8]) {
+    static_assert(N == 0 || N == 8, "");
+    uint32_t w0, w1, w2, w3;
+    if constexpr (N == 0)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\t"
+                     "v_lshl_or_b32 %0, %5, 16, %4\n\t"
+                     "v_lshl_or_b32 %1, %7, 16, %6\n\t"
+                     "v_lshl_or_b32 %2, %9, 16, %8\n\t"
+                     "v_lshl_or_b32 %3, %11, 16, %10"
+                     : "=&v"(w0), "=&v"(w1), "=&v"(w2), "=&v"(w3)
+                     : "v"(t[0]), "v"(t[1]), "v"(t[2]), "v"(t[3]), "v"(t[4]), "v"(t[5]), "v"(t[6]), "v"(t[7])
+                     : "memory");
+    else
+        asm volatile("s_waitcnt lgkmcnt(8)\n\t"
+                     "v_lshl_or_b32 %0, %5, 16, %4\n\t"
+                     "v_lshl_or_b32 %1, %7, 16, %6\n\t"
+                     "v_lshl_or_b32 %2, %9, 16, %8\n\t"
+                     "v_lshl_or_b32 %3, %11, 16, %10"
+                     : "=&v"(w0), "=&v"(w1), "=&v"(w2), "=&v"(w3)
+                     : "v"(t[0]), "v"(t[1]), "v"(t[2]), "v"(t[3]), "v"(t[4]), "v"(t[5]), "v"(t[6]), "v"(t[7])
+                     : "memory");
+    return make_uint4(w0, w1, w2, w3);
+}
 __device__ __forceinline__ uint4 pack_fragment(const uint32_t (&t)[8]) {
     return make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
 }
@@ -210,7 +237,8 @@ __device__ __forceinline__ uint4 pack_fragment(const uint32_t (&t)[8]) {
 // A template parameter so that the accumulators stay in registers along one straight path.
 // SHARED: d = 4096 exactly with a permutation: the four waves of a workgroup, each on whole rows of
 // its own, build one table of operand addresses together (see below).
-template <int OUT, bool PERM, int NWAVES, int STAGES, bool SHARED>
+// PIPE: the element-wise gather runs one unit ahead of the arithmetic (see the main loop).
+template <int OUT, bool PERM, int NWAVES, int STAGES, bool SHARED, bool PIPE>
 // (two 4-wave workgroups fit a CU's LDS, so the register budget is that of 2 waves per SIMD)
 __global__ void __launch_bounds__(NWAVES * 64, NWAVES == 4 ? 2 : 1) __attribute__((amdgpu_num_vgpr(248)))
 mfma_kernel(ApplyParams p, MfmaGeom g) {
@@ -412,25 +440,57 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     uint32_t u_cur = worker, u_nxt = worker + n_workers, u_new = n_units;
 
     // ---- one unit out of staging buffer BUF --------------------------------------------------
-    // On entry the unit's loads have landed (waited for at the end of the iteration before).
+    // P = I with b <= 512 (16-byte operand reads): on entry the unit's loads have landed (waited for
+    // at the end of the iteration before); operands are read, the buffer is refilled, then the
+    // arithmetic.
+    // Gathered operands (kElem): the gather runs one unit ahead of the arithmetic.  On entry F holds
+    // the operands of u_cur, its buffer BUF has been refilled already, and u_nxt sits in the other
+    // buffer.  The products of u_cur are issued, then the wave waits for u_nxt to have landed and
+    // reads its operands into FN in nine small steps placed between the parts of u_cur's epilogue
+    // (64 two-byte reads that meet in the LDS banks take as long as the vector work they now hide
+    // behind), and the other buffer is refilled as soon as the last read has returned.
+    constexpr bool kPiped = kElem && PIPE;
+    uint4 F[kPiped ? 8 : 1];
     auto body = [&](auto buf_const) {
         constexpr uint32_t kOff = kDouble ? decltype(buf_const)::value * kBufStride : 0u;
+        constexpr uint32_t kOffN = kDouble ? (1u - decltype(buf_const)::value) * kBufStride : 0u;   // buffer of u_nxt
         const int64_t row = wave_local ? (int64_t)u_cur : (int64_t)u_cur * g.rows + rr;
         const bool row_live = row < p.T;
+        uint32_t u_after = n_units;            // (piped) the unit the other buffer is refilled with
 
-        if (!wave_local) {
+        if (!kPiped && !wave_local) {
             workgroup_barrier_lds();
             if (boxed) u_new = __builtin_amdgcn_readfirstlane(lds_load4(unit_box));   // (uniform: keep it scalar)
         }
 
-        // The refill of this buffer, once its operands are in registers.  With two buffers the unit
+        // The refill of a buffer, once its operands are in registers.  With two buffers the unit
         // after next goes here, so two units' loads are in flight during the arithmetic.
         auto refill = [&]() {
             if (!wave_local) workgroup_barrier_lds();
-            const uint32_t u_load = kDouble ? u_new : u_nxt;
+            const uint32_t u_load = kPiped ? (kDouble ? u_after : u_new) : (kDouble ? u_new : u_nxt);
             if (drawing) draw();
-            n_behind = u_load < n_units ? issue_loads(u_load, kOff) : 0;
+            n_behind = u_load < n_units ? issue_loads(u_load, kPiped ? kOffN : kOff) : 0;
         };
+        // (piped) steps A .. B-1 of the next unit's gather: step i < 8 issues the reads of fragment i,
+        // step i > 0 waits for fragment i-1 (everything but the eight reads just issued) and packs it;
+        // after step 8 the other buffer is free and is refilled
+        uint4 FN[kPiped ? 8 : 1];
+        uint32_t tg[2][8];
+        auto gather_steps = [&](auto first, auto last) {
+            if constexpr (kPiped) {
+#pragma unroll
+                for (int i = decltype(first)::value; i < decltype(last)::value; ++i) {
+                    if (i < 8) gather8<kOffN>(tg[i & 1], src + 8 * i);
+                    if (i >= 1) {
+                        if (i < 8) FN[i - 1] = gather_wait8_pack<8>(tg[(i - 1) & 1]);
+                        else FN[i - 1] = gather_wait8_pack<0>(tg[(i - 1) & 1]);
+                    }
+                    if (i == 8) refill();
+                }
+                __builtin_amdgcn_sched_barrier(0);     // the steps stay where they were put
+            }
+        };
+#define PERQ_GATHER_STEPS(A, B) gather_steps(std::integral_constant<int, (A)>{}, std::integral_constant<int, (B)>{})
         const f32x16_t zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
         float v[64];
         if constexpr (!kElem) {
@@ -462,8 +522,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 for (int r = 0; r < 16; ++r) v[qo * 16 + r] = acc[r];
             }
         } else {
-            // ---- operands gathered element by element, four groups of two fragments; the products
-            //      of a group are issued while the reads of the next two groups are on their way -----
+            // ---- operands gathered element by element, four groups of two fragments ---------------
             // Low-K modes: group g holds sub-block qi = g of the lane; accumulator tile qo of the same
             // block of kDense sub-blocks takes (+-H_32) * X_qi, the sign being entry (qo, qi) of the
             // Sylvester matrix of order kDense.
@@ -474,7 +533,6 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             // Every accumulator sums its products in ascending (group, fragment) order.
             constexpr int kGroup = kHighK ? (STAGES == 5 ? 2 : 4) : (STAGES == 0 ? 1 : (STAGES == 1 ? 2 : 4));
             f32x16_t acc[kQ] = {zero16, zero16, zero16, zero16};
-            uint32_t t[4][2][8];
             auto products = [&](int g, const uint4& f0, const uint4& f1) {
 #pragma unroll
                 for (int o = 0; o < kQ; ++o) {
@@ -490,25 +548,45 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 }
             };
-            gather8<kOff>(t[0][0], src + 0);
-            gather8<kOff>(t[0][1], src + 8);
-            gather8<kOff>(t[1][0], src + 16);
-            gather8<kOff>(t[1][1], src + 24);
+            if constexpr (kPiped) {
+                // u_nxt has landed (in the other buffer), and with it the ticket drawn at the last refill
+                auto next_unit_landed = [&]() {
+                    wait_vm_le(kDouble ? n_behind : 0);
+                    u_after = fetch_next();
+                    if (!wave_local) {
+                        if (boxed && wave == 0 && lane == 0) lds_store4(unit_box, __uint_as_float(u_after));
+                        workgroup_barrier_lds();
+                        if (boxed) u_after = __builtin_amdgcn_readfirstlane(lds_load4(unit_box));   // (uniform: keep it scalar)
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                };
 #pragma unroll
-            for (int g = 0; g < kQ; ++g) {
-                // 32 reads were issued after those of group g (none after the last group's): with at
-                // most 12 outstanding, group g has arrived
-                if (g < kQ - 1) gather_wait<12>(t[g][0], t[g][1]);
-                else gather_wait<0>(t[g][0], t[g][1]);
-                const uint4 f0 = pack_fragment(t[g][0]), f1 = pack_fragment(t[g][1]);
-                if (g + 2 < kQ) {
-                    gather8<kOff>(t[g + 2][0], src + 16 * (g + 2));
-                    gather8<kOff>(t[g + 2][1], src + 16 * (g + 2) + 8);
+                for (int gq = 0; gq < kQ; ++gq) products(gq, F[2 * gq], F[2 * gq + 1]);
+                next_unit_landed();
+                PERQ_GATHER_STEPS(0, kHighK ? 2 : 3);
+            } else {
+                // the products of a group are issued while the reads of the next two groups are on their way
+                uint32_t t[4][2][8];
+                gather8<kOff>(t[0][0], src + 0);
+                gather8<kOff>(t[0][1], src + 8);
+                gather8<kOff>(t[1][0], src + 16);
+                gather8<kOff>(t[1][1], src + 24);
+#pragma unroll
+                for (int gq = 0; gq < kQ; ++gq) {
+                    // 32 reads were issued after those of group gq (none after the last group's): with at
+                    // most 12 outstanding, group gq has arrived
+                    if (gq < kQ - 1) gather_wait<12>(t[gq][0], t[gq][1]);
+                    else gather_wait<0>(t[gq][0], t[gq][1]);
+                    const uint4 f0 = pack_fragment(t[gq][0]), f1 = pack_fragment(t[gq][1]);
+                    if (gq + 2 < kQ) {
+                        gather8<kOff>(t[gq + 2][0], src + 16 * (gq + 2));
+                        gather8<kOff>(t[gq + 2][1], src + 16 * (gq + 2) + 8);
+                    }
+                    if (gq == kQ - 1) refill();
+                    products(gq, f0, f1);
+                    // (keeps the compiler from moving these products behind the next group's wait)
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (g == kQ - 1) refill();
-                products(g, f0, f1);
-                // (keeps the compiler from moving these products behind the next group's wait)
-                __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int o = 0; o < kQ; ++o) {
@@ -528,6 +606,10 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                         v[i | hh] = a0 - a1;
                     }
                 }
+                if (hh == 1) PERQ_GATHER_STEPS(2, 3);
+                if (hh == 2) PERQ_GATHER_STEPS(3, 4);
+                if (hh == 4) PERQ_GATHER_STEPS(4, 5);
+                if (hh == 8) PERQ_GATHER_STEPS(5, 6);
             }
             if constexpr (STAGES == 7) {
                 // position bit 11 (b = 4096 only): one half-wave swap hands the low lanes both halves
@@ -548,7 +630,9 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
                 for (int i = 0; i < 64; ++i) v[i] = w[i];
             }
+            PERQ_GATHER_STEPS(6, 7);
         }
+        constexpr int kG0 = kHighK ? 7 : 3;        // (piped) gather steps of the next unit done so far
 
         // ---- butterflies across lanes for b = 256, 512 ------------------------------------------
         if constexpr (STAGES == 3 || STAGES == 4) lane_stage<1>(v, sgn[0]);
@@ -557,6 +641,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         // ---- epilogue: lane (c,h) holds outputs 16h..16h+15 of sub-blocks 4c..4c+3 (low-K modes),
         //      or the 16 outputs from hk_run(q) on of every accumulator tile q (high-K mode) -------
         if constexpr (OUT == OUT_F32) {
+            PERQ_GATHER_STEPS(kG0, 9);
 #pragma unroll
             for (int q = 0; q < kQ; ++q) {
                 if (row_live && qvalid[q]) {
@@ -589,6 +674,15 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     pk[q][0] = mxfp4_pack8(v + q * 16, scale);
                     pk[q][1] = mxfp4_pack8(v + q * 16 + 8, scale);
                     ebytes |= (uint32_t)E << (8 * q);
+                    if constexpr (kHighK) {
+                        if (q == 0) PERQ_GATHER_STEPS(7, 8);
+                        if (q == 1) PERQ_GATHER_STEPS(8, 9);
+                    } else {
+                        if (q == 0) PERQ_GATHER_STEPS(3, 5);
+                        if (q == 1) PERQ_GATHER_STEPS(5, 7);
+                        if (q == 2) PERQ_GATHER_STEPS(7, 8);
+                        if (q == 3) PERQ_GATHER_STEPS(8, 9);
+                    }
                 }
             } else {
                 // per-token extremes: m[0] = max |y| (symmetric INT4, FP4) or max y (asymmetric
@@ -612,6 +706,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 } else {
                     m[0] = absmax(v);
                 }
+                PERQ_GATHER_STEPS(kG0, kHighK ? 8 : 5);
 #pragma unroll
                 // (folded rows, low-K modes only: a real row is 4, 8 or 16 neighbouring values of c and
                 //  both half-waves, so the exchange stops at the row's edge)
@@ -638,6 +733,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                         for (int j = 0; j < kRed; ++j) m[j] = fmaxf(m[j], red[2 * (w0 + w) + j]);
                     }
                 }
+                PERQ_GATHER_STEPS(kHighK ? 8 : 5, kHighK ? 9 : 8);
                 if constexpr (OUT == OUT_INT4) {
                     row_max = m[0];
                     float mx = m[0];
@@ -683,6 +779,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             // The wave's 2 KiB of codes take one trip through LDS so that each store instruction
             // writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of short pieces
             // at a pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
+            if constexpr (!kHighK && OUT != OUT_MXFP4) PERQ_GATHER_STEPS(8, 9);
             unsigned char* ob = out_stage + (uint32_t)wave * 2048u;
             if constexpr (!kHighK) {
                 // Give lane (c,0) the whole of its sub-blocks q = 0, 1 and lane (c,1) the whole of
@@ -742,12 +839,21 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             }
         }
 
-        // ---- the next unit's loads have landed, and the ticket with them -----------------------
-        wait_vm_le(kDouble ? n_behind : 0);
-        u_cur = u_nxt;
-        u_nxt = u_new;
-        u_new = fetch_next();
-        if (boxed && wave == 0 && lane == 0) lds_store4(unit_box, __uint_as_float(u_new));
+        if constexpr (kPiped) {
+            u_cur = u_nxt;
+            u_nxt = u_new;
+            u_new = u_after;
+#pragma unroll
+            for (int f = 0; f < 8; ++f) F[f] = FN[f];
+        } else {
+            // ---- the next unit's loads have landed, and the ticket with them -------------------
+            wait_vm_le(kDouble ? n_behind : 0);
+            u_cur = u_nxt;
+            u_nxt = u_new;
+            u_new = fetch_next();
+            if (boxed && wave == 0 && lane == 0) lds_store4(unit_box, __uint_as_float(u_new));
+        }
+#undef PERQ_GATHER_STEPS
     };
 
     // Operand addresses through `perm`, shared case: when every wave of the workgroup owns a whole
@@ -980,6 +1086,26 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     wait_vm_le(kDouble ? n_behind : 0);
     u_new = fetch_next();
     if (boxed && wave == 0 && lane == 0) lds_store4(unit_box, __uint_as_float(u_new));
+    if constexpr (kPiped) {
+        // the operands of the first unit, and the first refill of its buffer
+        if (!wave_local) {
+            workgroup_barrier_lds();
+            if (boxed) u_new = __builtin_amdgcn_readfirstlane(lds_load4(unit_box));
+        }
+        uint32_t t0[8], t1[8];
+#pragma unroll
+        for (int f = 0; f < 8; f += 2) {
+            gather8<0u>(t0, src + 8 * f);
+            gather8<0u>(t1, src + 8 * f + 8);
+            gather_wait<0>(t0, t1);
+            F[f] = pack_fragment(t0);
+            F[f + 1] = pack_fragment(t1);
+        }
+        if (!wave_local) workgroup_barrier_lds();
+        const uint32_t u_load = kDouble ? u_new : u_nxt;
+        if (drawing) draw();
+        n_behind = u_load < n_units ? issue_loads(u_load, 0u) : 0;
+    }
 
     while (u_cur < n_units) {
         body(std::integral_constant<uint32_t, 0>{});
@@ -1011,9 +1137,18 @@ hipError_t launch_mfma_st(const ApplyParams& p, uint32_t fold_mask, hipStream_t 
     }
 
     const int64_t ngroups = (p.T + g.rows - 1) / g.rows;
-    auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false>;
+    auto kern = p.perm ? mfma_kernel<OUT, true, NWAVES, STAGES, false, false> : mfma_kernel<OUT, false, NWAVES, STAGES, false, false>;
     if constexpr (NWAVES == 4) {
-        if (p.perm && p.d == kTile) kern = mfma_kernel<OUT, true, NWAVES, STAGES, true>;
+        if (p.perm && p.d == kTile) kern = mfma_kernel<OUT, true, NWAVES, STAGES, true, false>;
+        // Rows of four tiles with one scale per token (a barrier for the row's extremes in every
+        // iteration) run faster with the gather one unit ahead: d = 14336, b = 2048 with a
+        // permutation 245 -> 234 us, b = 128 226 -> 222 us; rows of one or two tiles and MXFP4 do not.
+        if constexpr (OUT != OUT_MXFP4) {
+            if (g.tiles_per_row == 4) {
+                if (p.perm) kern = mfma_kernel<OUT, true, NWAVES, STAGES, false, true>;
+                else if constexpr (STAGES >= 5) kern = mfma_kernel<OUT, false, NWAVES, STAGES, false, true>;
+            }
+        }
     }
     // (static and dynamic LDS together pass 64 KiB)
     int per_cu = 0;

@@ -268,3 +268,39 @@ def compare_apply(x_bits, perm, b, fmt, packed_gpu, scales_gpu, y_gpu=None, rota
     else:
         check_fp4_token(packed_gpu, scales_gpu, ref, x_bits, rep)
     return rep
+
+
+def merge_reports(reports) -> ParityReport:
+    out = ParityReport()
+    for r in reports:
+        out.elements += r.elements
+        out.code_mismatch_A += r.code_mismatch_A
+        out.code_mismatch_B += r.code_mismatch_B
+        out.code_mismatch_fail += r.code_mismatch_fail
+        out.scale_exceptions += r.scale_exceptions
+        out.scale_fail += r.scale_fail
+        out.neg_zero_seen += r.neg_zero_seen
+        out.max_prequant_rel = max(out.max_prequant_rel, r.max_prequant_rel)
+        out.notes += r.notes[:3]
+    return out
+
+
+def compare_apply_all_rows(x_bits, perm, b, fmt, packed_gpu, scales_gpu, rotate=None, chunk=512, threads=None) -> ParityReport:
+    """compare_apply over every row of a full-size result, in chunks of rows on a few threads (NumPy
+    releases the interpreter lock in its array loops).  The matrix products of the oracle run on one
+    BLAS thread each while several chunks are in flight: concurrent calls into a multi-threaded BLAS
+    from several Python threads gave wrong products on this image."""
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    from threadpoolctl import threadpool_limits
+    T = x_bits.shape[0]
+    threads = threads or min(16, os.cpu_count() or 1)
+
+    def work(s):
+        e = min(T, s + chunk)
+        return compare_apply(x_bits[s:e], perm, b, fmt, packed_gpu[s:e], scales_gpu[s:e], None, rotate=rotate)
+    with threadpool_limits(limits=1):
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            reports = list(ex.map(work, range(0, T, chunk)))
+    return merge_reports(reports)
+

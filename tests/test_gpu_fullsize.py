@@ -1,5 +1,7 @@
-"""Full-size runs of the BASELINE configurations in the launch configuration bench.py times,
-checked on sampled rows the oracle can compute one by one, plus properties that hold at any size."""
+"""Full-size runs of the BASELINE configurations in the launch configuration bench.py times: every
+row against the oracle (the explicit matrix product for b <= 128; for power-of-two b >= 2048 the
+oracle's fp64 butterfly evaluation, which the CPU tests pin to the explicit product up to b = 4096, on
+every row and the explicit product on sampled rows), plus properties that hold at any size."""
 import os
 import sys
 
@@ -23,6 +25,10 @@ CASES = [
     ("qwen3_d12288", (12288, 3072), 96),              # 2^10 * 12
     ("qwen3_d9728", (9728,), 96),                     # 2^7 * 76
 ]
+
+
+# the BASELINE configurations: every row is compared, not only the sample
+ALL_ROWS = ("llama1b_down", "block_vs_full", "llama8b_d4096", "llama8b_d14336", "calib_apply")
 
 
 def _sample_rows(wl, count):
@@ -72,6 +78,12 @@ def test_full_size_config(name, bs, count):
                                    scales[rows_t].cpu().numpy())
         print("       ", rep.summary(), flush=True)
         assert rep.ok(), (rep.summary(), rep.notes[:5])
+        if name in ALL_ROWS and b & (b - 1) == 0 and rows.size < wl.T:
+            rot = orc.fwht_f64 if b >= 2048 else None
+            rep = parity.compare_apply_all_rows(x_bits, perm, b, wl.fmt, codes.cpu().numpy(), scales.cpu().numpy(), rotate=rot)
+            print(f"[full] {name} b={b} every row ({'fp64 butterflies' if rot else 'explicit product'}):",
+                  rep.summary(), flush=True)
+            assert rep.ok() and rep.elements == wl.T * wl.d, (rep.summary(), rep.notes[:5])
         del codes, scales, codes2, scales2
         if perm is not None and b == 128 and name.startswith("llama8b"):
             # the same launch with the permutation's blocks arranged for the LDS gather
