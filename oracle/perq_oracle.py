@@ -47,7 +47,7 @@ __all__ = [
     "paley_hadamard", "hadamard_factors", "hadamard_matrix", "nonpo2_rotation_counted",
     "quant_int4_sym_token", "quant_mxfp4", "pack_nibbles", "E2M1_GRID",
     "quant_int4_asym_token", "dequant_int4_asym", "quant_fp4_token", "dequant_fp4_token",
-    "merge_into_weights", "w4a4_matmul", "w4a4_mxfp4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics", "splitmix64", "perm_random",
+    "merge_into_weights", "w4a4_matmul", "w4a4_mxfp4_matmul", "colabs_max", "perm_sorted_desc", "perm_zigzag", "block_diagnostics", "quant_error", "splitmix64", "perm_random",
     "dequant_int4", "dequant_mxfp4", "colabs_mean", "massdiff_greedy",
     "block_masses", "brute_force_min_max_block_mass", "fwht_f64", "perq_apply",
 ]
@@ -587,6 +587,28 @@ def block_diagnostics(x_bits: np.ndarray, perm, b: int) -> np.ndarray:
     l1b = np.abs(Xp).reshape(T, d // b, b).sum(axis=2).max(axis=1)
     y = block_hadamard(Xp, b)
     return np.stack([np.abs(X).max(axis=1), np.abs(X).sum(axis=1), l1b, np.abs(y).max(axis=1)], axis=1)
+
+
+def quant_error(Y: np.ndarray, fmt: str) -> np.ndarray:
+    """float64 [T, 3] per token: ||Y - Q(Y)||_2, ||Y||_2, ||Y||_inf for the rotated row Y = XP R~ and
+    the quantizer `fmt` ("int4", "mxfp4", "int4_asym", "fp4_token"), Q(Y) being the value the codes
+    stand for.  Section 3: with the symmetric q-bit step s = ||Y||_inf / (2^(q-1) - 1) every element
+    is off by at most s/2, so ||Y - Q(Y)||_2 <= sqrt(d) / (2^q - 2) ||Y||_inf (q = 4: sqrt(d)/14)."""
+    if fmt == "int4":
+        c, s = quant_int4_sym_token(Y)
+        Q = dequant_int4(c, s)
+    elif fmt == "mxfp4":
+        c, E = quant_mxfp4(Y)
+        Q = dequant_mxfp4(c, E)
+    elif fmt == "int4_asym":
+        c, s, z = quant_int4_asym_token(Y)
+        Q = dequant_int4_asym(c, s, z)
+    elif fmt == "fp4_token":
+        c, s = quant_fp4_token(Y)
+        Q = dequant_fp4_token(c, s)
+    else:
+        raise ValueError("fmt must be 'int4', 'mxfp4', 'int4_asym' or 'fp4_token'")
+    return np.stack([np.sqrt(((Y - Q) ** 2).sum(axis=1)), np.sqrt((Y ** 2).sum(axis=1)), np.abs(Y).max(axis=1)], axis=1)
 
 
 # ----------------------------------------------------------------------------------------

@@ -420,3 +420,38 @@ def test_mxfp4_product_of_hand_decoded_operands():
                           e2m1(int(cw[0, i])) * 2.0 ** (int(Ew[0, i // 32]) - 127)
     got = orc.w4a4_mxfp4_matmul(ca.astype(np.uint8), Ea.astype(np.uint8), cw.astype(np.uint8), Ew.astype(np.uint8))
     assert np.array_equal(got, want)
+
+
+# ---- per-token quantization error and the worst-case bound of Section 3 ----------------------------
+def test_quant_error_hand_case_bound_and_tightness():
+    # hand case, symmetric INT4: maximum 7 -> step 1; 0.25 -> 0, 2.6 -> 3, -1.5 -> -2 (tie to even), 7 -> 7
+    Y = np.array([[0.25, 2.6, -1.5, 7.0]])
+    e = orc.quant_error(Y, "int4")
+    assert np.allclose(e[0], [math.sqrt(0.25 ** 2 + 0.4 ** 2 + 0.5 ** 2), math.sqrt((Y ** 2).sum()), 7.0], rtol=1e-14)
+    # Section 3: ||Y - Q(Y)||_2 <= sqrt(d) / (2^q - 2) ||Y||_inf, q = 4, on heavy-tailed rows
+    R = _rng(31).standard_t(3, size=(200, 96))
+    e = orc.quant_error(R, "int4")
+    assert np.all(e[:, 0] <= math.sqrt(96) / 14.0 * e[:, 2] * (1 + 1e-12))
+    assert np.allclose(e[:, 1], np.linalg.norm(R, axis=1)) and np.array_equal(e[:, 2], np.abs(R).max(axis=1))
+    # the bound is attained: every element half a step from its code (one element carries the maximum,
+    # itself a tie: 7.5 steps would leave the alphabet, so it sits at 6.5 with another element at 7)
+    d = 64
+    T = np.full((1, d), 2.5); T[0, 0] = 7.0; T[0, 1::2] = -3.5
+    e = orc.quant_error(T, "int4")[0]
+    assert math.isclose(e[0], math.sqrt(d - 1) * 0.5, rel_tol=1e-14)           # all but the maximum are off by s/2
+    assert e[0] <= math.sqrt(d) / 14.0 * 7.0 and e[0] >= 0.99 * math.sqrt(d) / 14.0 * 7.0
+    # scale equivariance and the other quantizers: the error is that of the dequantized codes
+    for fmt in ("int4", "mxfp4", "int4_asym", "fp4_token"):
+        e1, e2 = orc.quant_error(R, fmt), orc.quant_error(R * 8.0, fmt)
+        assert np.allclose(e2, 8.0 * e1, rtol=1e-13)
+    c, E = orc.quant_mxfp4(R[:, :64])
+    want = np.linalg.norm(R[:, :64] - orc.dequant_mxfp4(c, E), axis=1)
+    assert np.allclose(orc.quant_error(R[:, :64], "mxfp4")[:, 0], want, rtol=1e-14)
+    # asymmetric INT4 has 16 levels over the range: half a step of (max - min)/15 per element
+    ea = orc.quant_error(R, "int4_asym")
+    rng_ = R.max(axis=1) - R.min(axis=1)
+    assert np.all(ea[:, 0] <= math.sqrt(96) * rng_ / 30.0 * (1 + 1e-9))
+    # a row that is exactly representable has no error
+    G = np.array([[7.0, -3.0, 0.0, 1.0, 2.0, -7.0, 5.0, 4.0]])
+    assert orc.quant_error(G, "int4")[0, 0] == 0.0
+
