@@ -249,6 +249,21 @@ perq_status_t perq_block_diagnostics(const uint16_t* x_bf16, int64_t T, int32_t 
                                      const int32_t* perm, int32_t b, float* out, void* hip_stream);
 
 /*
+ * Per-token quantization error of an output of the fused path (Section 3: the worst-case l2 error of
+ * a q-bit quantizer with step ||y||_inf / (2^(q-1) - 1) is sqrt(d) / (2^q - 2) ||y||_inf, the reason
+ * outliers are suppressed at all):
+ *   out[t] = ( ||y_t - Q(y_t)||_2,  ||y_t||_2,  ||y_t||_inf )                          float [T][3]
+ *   y       device, float [T, d], the output of perq_permute_rotate_f32, 8-byte aligned
+ *   codes   device, uint8 [T, d/2], and
+ *   scales  device, as perq_permute_rotate_quant wrote them for the same input, perm, b and fmt
+ * Q(y) is the value the codes stand for: step * code (INT4), step * (code + zero point) (asymmetric
+ * INT4), step * e2m1 value (FP4 per token), 2^(E-127) * e2m1 value (MXFP4).  d % 32 == 0.  fp32 sums in
+ * a fixed order.  T == 0 does nothing.
+ */
+perq_status_t perq_quant_error(const float* y, int64_t T, int32_t d, const uint8_t* codes,
+                               const void* scales, perq_fmt_t fmt, float* out, void* hip_stream);
+
+/*
  * Reference consumer of the codes (Remark "Merging Permutations", Section 4): with P and the block
  * rotation merged into the weights, W~ = R~^T P^T W, the product of the two quantized operands
  * stands for X W.  Both operands are PERQ_FMT_INT4_SYM_TOKEN outputs of

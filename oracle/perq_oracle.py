@@ -416,18 +416,19 @@ def dequant_int4_asym(codes: np.ndarray, s: np.ndarray, z: np.ndarray) -> np.nda
 # ----------------------------------------------------------------------------------------
 # Q: FP4 (e2m1) with one real-valued scale per token   (Appendix B, (MX)FP4 paragraph)
 # ----------------------------------------------------------------------------------------
-def quant_fp4_token(Y: np.ndarray):
+def quant_fp4_token(Y: np.ndarray, c: float = 6.0):
     """Returns (codes uint8 [T,d], 4-bit sign|exp|mant; s float64 [T]).
 
     Appendix B: FP4 activations take one scale per token, s = ||Y_t||_inf / c, z = 0, and the
     elements are rounded (nearest, ties to the even code) onto the e2m1 grid.
     Reading of c: the appendix prints c = 2^(q-1) - 1 = 7, the integer quantizer's constant,
-    which is not an e2m1 value; with it the row maximum would land on 7 and saturate to 6.
-    The largest magnitude of the alphabet, c = 6, is taken, so the row maximum maps onto the
-    largest code.  An all-zero row has s = 0 and all codes 0; zero is always emitted as +0.
+    which is not an e2m1 value; with it the row maximum lands on 7 and saturates to 6, as does
+    everything above 6.5.  The default takes the largest magnitude of the alphabet, c = 6, so the
+    row maximum maps onto the largest code; c = 7 is the formula as printed (format "fp4_token7").
+    An all-zero row has s = 0 and all codes 0; zero is always emitted as +0.
     """
     amax = np.abs(Y).max(axis=1)
-    s = amax / 6.0
+    s = amax / c
     safe = np.where(s > 0.0, s, 1.0)
     V = Y / safe[:, None]
     mag = _round_to_e2m1_codes(np.abs(V))
@@ -603,11 +604,11 @@ def quant_error(Y: np.ndarray, fmt: str) -> np.ndarray:
     elif fmt == "int4_asym":
         c, s, z = quant_int4_asym_token(Y)
         Q = dequant_int4_asym(c, s, z)
-    elif fmt == "fp4_token":
-        c, s = quant_fp4_token(Y)
+    elif fmt in ("fp4_token", "fp4_token7"):
+        c, s = quant_fp4_token(Y, 7.0 if fmt == "fp4_token7" else 6.0)
         Q = dequant_fp4_token(c, s)
     else:
-        raise ValueError("fmt must be 'int4', 'mxfp4', 'int4_asym' or 'fp4_token'")
+        raise ValueError("fmt must be 'int4', 'mxfp4', 'int4_asym', 'fp4_token' or 'fp4_token7'")
     return np.stack([np.sqrt(((Y - Q) ** 2).sum(axis=1)), np.sqrt((Y ** 2).sum(axis=1)), np.abs(Y).max(axis=1)], axis=1)
 
 
@@ -643,7 +644,7 @@ def perq_apply(x_bits: np.ndarray, perm, b: int, fmt: str, rotate=block_hadamard
     """bf16 bits [T,d] -> dict(y, codes, packed, scales[, s64]) following P, R~, Q in order.
 
     fmt is "int4" (scales: float32 [T]), "mxfp4" (scales: uint8 [T, d/32]), "int4_asym"
-    (scales: float32 [T, 2] = step, zero point) or "fp4_token" (scales: float32 [T]).
+    (scales: float32 [T, 2] = step, zero point), "fp4_token" or "fp4_token7" (scales: float32 [T]).
     """
     X = bf16_bits_to_f64(x_bits)
     Y = rotate(permute_channels(X, perm), b)
@@ -658,8 +659,8 @@ def perq_apply(x_bits: np.ndarray, perm, b: int, fmt: str, rotate=block_hadamard
         codes, s, z = quant_int4_asym_token(Y)
         return {"y": Y, "codes": codes, "packed": pack_nibbles(codes),
                 "scales": np.stack([s, z], axis=1).astype(np.float32), "s64": s, "z": z}
-    if fmt == "fp4_token":
-        codes, s = quant_fp4_token(Y)
+    if fmt in ("fp4_token", "fp4_token7"):
+        codes, s = quant_fp4_token(Y, 7.0 if fmt == "fp4_token7" else 6.0)
         return {"y": Y, "codes": codes, "packed": pack_nibbles(codes),
                 "scales": s.astype(np.float32), "s64": s}
-    raise ValueError("fmt must be 'int4', 'mxfp4', 'int4_asym' or 'fp4_token'")
+    raise ValueError("fmt must be 'int4', 'mxfp4', 'int4_asym', 'fp4_token' or 'fp4_token7'")

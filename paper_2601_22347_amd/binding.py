@@ -27,7 +27,7 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
            "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref", "perq_perm_arrange",
            "perq_perm_gather_cost", "perq_schedule_set", "perq_reset_schedule", "perq_schedule_selftest",
-           "perq_colabs_mean_static"]
+           "perq_colabs_mean_static", "perq_quant_error"]
 
 _lib = None
 
@@ -89,6 +89,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_block_diagnostics.restype = ctypes.c_int
     lib.perq_colabs_mean_static.argtypes = [vp, i64, i32, i64, vp, vp]
     lib.perq_colabs_mean_static.restype = ctypes.c_int
+    lib.perq_quant_error.argtypes = [vp, i64, i32, vp, vp, ctypes.c_int, vp, vp]
+    lib.perq_quant_error.restype = ctypes.c_int
     lib.perq_schedule_set.argtypes = [vp]
     lib.perq_schedule_set.restype = ctypes.c_int32
     lib.perq_reset_schedule.argtypes = [vp]
@@ -253,6 +255,19 @@ def perq_block_diagnostics(x, perm, b: int, out=None, stream=None):
         out = torch.empty((T, 4), dtype=torch.float32, device=x.device)
     st = load().perq_block_diagnostics(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), int(b), _dev_ptr(out), _stream_ptr(stream))
     _check(st, "perq_block_diagnostics")
+    return out
+
+
+def perq_quant_error(y, codes, scales, fmt: str, out=None, stream=None):
+    """y: CUDA float32 [T, d]; codes, scales: outputs of perq_permute_rotate_quant for the same input ->
+    CUDA float32 [T, 3] = (|y - Q(y)|_2, |y|_2, |y|_inf)."""
+    import torch
+    T, d = y.shape
+    if out is None:
+        out = torch.empty((T, 3), dtype=torch.float32, device=y.device)
+    st = load().perq_quant_error(_dev_ptr(y), T, d, _dev_ptr(codes), _dev_ptr(scales), FMT[fmt], _dev_ptr(out),
+                                 _stream_ptr(stream))
+    _check(st, "perq_quant_error")
     return out
 
 

@@ -11,7 +11,7 @@ CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libperq.so")
 
 SOURCES = ["perq_host.cpp", "perq_colabs.hip", "perq_butterfly.hip", "perq_mfma.hip", "perq_api.hip",
-           "perq_gemm.hip", "perq_npo2.hip", "perq_npo2_12.hip", "perq_npo2_76.hip", "perq_npo2_32.hip"]
+           "perq_gemm.hip", "perq_qerr.hip", "perq_npo2.hip", "perq_npo2_12.hip", "perq_npo2_76.hip", "perq_npo2_32.hip"]
 
 # -packed-fp32-ops: keep the compiler from fusing fp32 pairs into packed VALU instructions.
 HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-ffp-contract=off",

@@ -1,4 +1,5 @@
 """HIP library vs CPU oracle, element by element, through the C ABI (needs an MI355X)."""
+import math
 import os
 import sys
 
@@ -515,6 +516,33 @@ def test_calibrated_permutations_ranked_by_the_bound():
     assert bound["massdiff"] < bound["identity"] and bound["massdiff"] <= bound["zigzag"] * 1.02
     assert bound["absmax"] > bound["massdiff"]            # sorting concentrates the heavy channels in one block
     assert bound["random"] >= bound["massdiff"]           # a shuffle spreads them by chance only
+
+
+# ---- per-token quantization error (Section 3) ---------------------------------------------------------
+@pytest.mark.parametrize("d,b", [(256, 16), (2048, 64), (4096, 128), (4096, 4096), (3072, 768)])
+def test_quant_error_against_oracle_and_worst_case_bound(d, b):
+    torch = _torch()
+    rng = np.random.default_rng(d * 3 + b)
+    T = 70
+    x = rng.standard_t(3, size=(T, d))
+    x[:, rng.choice(d, size=max(1, d // 100), replace=False)] *= 40.0
+    x[T - 1] = 0.0                                                    # an all-zero token: no error, no norm
+    x_bits = synth.f64_to_bf16_bits(x)
+    perm = rng.permutation(d).astype(np.int32)
+    xd = binding.bits_to_device(x_bits)
+    perm_t = torch.from_numpy(perm).cuda()
+    y = binding.perq_permute_rotate_f32(xd, perm_t, b)
+    Y = orc.block_hadamard(orc.permute_channels(orc.bf16_bits_to_f64(x_bits), perm), b)
+    for fmt in ("int4", "mxfp4", "int4_asym", "fp4_token"):
+        print(f"[case] quant error d={d} b={b} fmt={fmt}", flush=True)
+        codes, scales = binding.perq_permute_rotate_quant(xd, perm_t, b, fmt)
+        got = binding.perq_quant_error(y, codes, scales, fmt).cpu().numpy().astype(np.float64)
+        want = orc.quant_error(Y, fmt)
+        assert np.all(np.abs(got - want) <= 1e-4 * want + 1e-30), (fmt, np.abs(got - want).max())
+        assert np.all(got[T - 1] == 0.0)
+        if fmt == "int4":
+            # Section 3 on the device's own numbers: ||y - Q(y)||_2 <= sqrt(d) / (2^4 - 2) ||y||_inf
+            assert np.all(got[:, 0] <= math.sqrt(d) / 14.0 * got[:, 2] * (1 + 1e-5))
 
 
 # ---- the ticket counters under concurrency and graph replay ------------------------------------------

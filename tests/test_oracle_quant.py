@@ -455,3 +455,23 @@ def test_quant_error_hand_case_bound_and_tightness():
     G = np.array([[7.0, -3.0, 0.0, 1.0, 2.0, -7.0, 5.0, 4.0]])
     assert orc.quant_error(G, "int4")[0, 0] == 0.0
 
+
+
+
+def test_fp4_token_with_the_printed_constant_saturates_the_top_of_the_row():
+    """Appendix B prints s = ||Y||_inf / (2^(q-1) - 1) for FP4 as well: the row maximum then sits at 7
+    steps, past the largest e2m1 magnitude, and saturates together with everything above 6.5."""
+    Y = np.array([[7.0, -6.6, 6.4, 5.0, 0.2, -0.26, 3.5, 2.5]])
+    c, s = orc.quant_fp4_token(Y, 7.0)
+    assert s[0] == 1.0
+    # 7 -> 6 (saturated), -6.6 -> -6, 6.4 -> 6, 5 -> 4 (tie to even), 0.2 -> 0, -0.26 -> -0.5, 3.5 -> 4, 2.5 -> 2
+    assert [float(orc.dequant_fp4_token(c, s)[0, i]) for i in range(8)] == [6.0, -6.0, 6.0, 4.0, 0.0, -0.5, 4.0, 2.0]
+    R = _rng(33).standard_t(3, size=(50, 64))
+    c7, s7 = orc.quant_fp4_token(R, 7.0)
+    assert np.allclose(s7 * 7.0, np.abs(R).max(axis=1), rtol=1e-15)
+    arg = np.abs(R).argmax(axis=1)
+    assert np.all((c7[np.arange(50), arg] & 7) == 7)                   # the maximum saturates to +-6
+    dq = orc.dequant_fp4_token(c7, s7)
+    assert np.all(np.abs(R - dq) <= s7[:, None] * (1 + 1e-12))           # at most one step (the saturated top)
+    e7 = orc.quant_error(R, "fp4_token7")
+    assert np.allclose(e7[:, 0], np.linalg.norm(R - dq, axis=1), rtol=1e-14)
