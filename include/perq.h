@@ -62,7 +62,10 @@ typedef enum {
     PERQ_FMT_INT4_ASYM_TOKEN = 2,
     /* Appendix B, (MX)FP4 paragraph: e2m1 nibbles with one real scale per token,
      * s = max|y| / 6 (6 = largest e2m1 magnitude); scales: float [T]. */
-    PERQ_FMT_FP4_TOKEN = 3
+    PERQ_FMT_FP4_TOKEN = 3,
+    /* The same with the step as that paragraph prints it, s = max|y| / (2^(q-1) - 1) = max|y| / 7:
+     * values above 6.5 steps, the row maximum among them, saturate to the largest code. */
+    PERQ_FMT_FP4_TOKEN_AMAX7 = 4
 } perq_fmt_t;
 
 /* Which rotation kernel runs.  AUTO picks the fastest one that covers the shape (block sizes that
@@ -213,7 +216,7 @@ perq_status_t perq_perm_gather_cost(const int32_t* perm, int32_t d, int32_t b, i
  *   scales   INT4:  device float [T], s_t = ||y_t||_inf / 7 (0 for an all-zero row)
  *            MXFP4: device uint8 [T, d/32], biased exponent E, scale = 2^(E-127),
  *                   E - 127 = floor(log2 ||group||_inf) - 2, clamped to [0,254], 0 for a zero group
- *            INT4_ASYM_TOKEN: device float [T][2] = (step, zero point); FP4_TOKEN: device float [T]
+ *            INT4_ASYM_TOKEN: device float [T][2] = (step, zero point); FP4_TOKEN(_AMAX7): device float [T]
  *                   (see perq_fmt_t)
  *   d % 32 == 0 is required for both formats; T == 0 is OK and does nothing.
  *

@@ -16,9 +16,10 @@ LIB_PATH = os.path.join(PKG, "libperq.so")
 
 PERQ_OK, PERQ_ERR_INVALID_ARG, PERQ_ERR_UNSUPPORTED, PERQ_ERR_LAUNCH, PERQ_ERR_INTERNAL = 0, 1, 2, 3, 4
 PERQ_FMT_INT4_SYM_TOKEN, PERQ_FMT_MXFP4, PERQ_FMT_INT4_ASYM_TOKEN, PERQ_FMT_FP4_TOKEN = 0, 1, 2, 3
+PERQ_FMT_FP4_TOKEN_AMAX7 = 4
 PERQ_ALGO_AUTO, PERQ_ALGO_BUTTERFLY, PERQ_ALGO_MFMA = 0, 1, 2
 FMT = {"int4": PERQ_FMT_INT4_SYM_TOKEN, "mxfp4": PERQ_FMT_MXFP4, "int4_asym": PERQ_FMT_INT4_ASYM_TOKEN,
-       "fp4_token": PERQ_FMT_FP4_TOKEN}
+       "fp4_token": PERQ_FMT_FP4_TOKEN, "fp4_token7": PERQ_FMT_FP4_TOKEN_AMAX7}
 ALGO = {"auto": PERQ_ALGO_AUTO, "butterfly": PERQ_ALGO_BUTTERFLY, "mfma": PERQ_ALGO_MFMA}
 
 EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colabs_mean",
@@ -274,7 +275,7 @@ def perq_quant_error(y, codes, scales, fmt: str, out=None, stream=None):
 def alloc_outputs(T: int, d: int, fmt: str, device):
     import torch
     codes = torch.empty((T, d // 2), dtype=torch.uint8, device=device)
-    if FMT[fmt] in (PERQ_FMT_INT4_SYM_TOKEN, PERQ_FMT_FP4_TOKEN):
+    if FMT[fmt] in (PERQ_FMT_INT4_SYM_TOKEN, PERQ_FMT_FP4_TOKEN, PERQ_FMT_FP4_TOKEN_AMAX7):
         scales = torch.empty(T, dtype=torch.float32, device=device)
     elif FMT[fmt] == PERQ_FMT_INT4_ASYM_TOKEN:
         scales = torch.empty((T, 2), dtype=torch.float32, device=device)      # (step, zero point)

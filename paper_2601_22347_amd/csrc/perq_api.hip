@@ -101,7 +101,8 @@ perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, 
     p->half_log2b = log2b / 2;
     p->inv_7sqrt_b = 1.0 / (7.0 * std::sqrt((double)b));
     p->inv_15sqrt_b = 1.0 / (15.0 * std::sqrt((double)b));
-    p->inv_6sqrt_b = 1.0 / (6.0 * std::sqrt((double)b));
+    p->fp4_qmax = 6.0f;
+    p->inv_fp4sqrt_b = 1.0 / (6.0 * std::sqrt((double)b));
     return PERQ_OK;
 }
 
@@ -147,6 +148,7 @@ extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, 
         case PERQ_FMT_MXFP4: out_kind = perq::OUT_MXFP4; break;
         case PERQ_FMT_INT4_ASYM_TOKEN: out_kind = perq::OUT_INT4_ASYM; break;
         case PERQ_FMT_FP4_TOKEN: out_kind = perq::OUT_FP4_TOKEN; break;
+        case PERQ_FMT_FP4_TOKEN_AMAX7: out_kind = perq::OUT_FP4_TOKEN; break;
         default: return PERQ_ERR_INVALID_ARG;
     }
     if (algo != PERQ_ALGO_AUTO && algo != PERQ_ALGO_BUTTERFLY && algo != PERQ_ALGO_MFMA)
@@ -159,6 +161,10 @@ extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, 
     if ((reinterpret_cast<uintptr_t>(scales) & (scale_align - 1u)) != 0) return PERQ_ERR_UNSUPPORTED;
     p.codes = codes;
     p.scales = scales;
+    if (fmt == PERQ_FMT_FP4_TOKEN_AMAX7) {
+        p.fp4_qmax = 7.0f;
+        p.inv_fp4sqrt_b = 1.0 / (7.0 * std::sqrt((double)b));
+    }
     return perq::dispatch(p, out_kind, algo, static_cast<hipStream_t>(hip_stream));
 }
 

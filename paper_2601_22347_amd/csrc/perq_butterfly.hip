@@ -285,12 +285,12 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
             } else if constexpr (OUT == OUT_FP4_TOKEN) {
                 float mx = m[0];
                 if (tiny_row(mx)) { lift_values(v); mx *= kTinyRowLift; }
-                const float inv = mx > 0.0f ? 6.0f / mx : 0.0f;
+                const float inv = mx > 0.0f ? p.fp4_qmax / mx : 0.0f;
                 if (live) {
                     const uint4 c = make_uint4(fp4_pack8(v, inv), fp4_pack8(v + 8, inv),
                                                fp4_pack8(v + 16, inv), fp4_pack8(v + 24, inv));
                     store_stream16(crow, c);
-                    if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_6sqrt_b);
+                    if (t == 0) static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_fp4sqrt_b);
                 }
             } else {
                 float lo = -m[1], hi = m[0];

@@ -32,7 +32,8 @@ struct ApplyParams {
     int32_t half_log2b;     // floor(log2b / 2)
     double inv_7sqrt_b;     // 1 / (7 sqrt(b)) in double
     double inv_15sqrt_b;    // 1 / (15 sqrt(b))
-    double inv_6sqrt_b;     // 1 / (6 sqrt(b))
+    double inv_fp4sqrt_b;   // 1 / (c sqrt(b)), c = fp4_qmax
+    float fp4_qmax;         // per-token FP4: the row maximum maps to this many steps (6, or 7 as printed)
 };
 
 // Streaming (non-temporal) 16-byte global accesses: every input byte is read once and every

@@ -748,7 +748,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     row_max = m[0];
                     float mx = m[0];
                     if (tiny_row(mx)) { lift_values(v); mx *= kTinyRowLift; }
-                    const float inv = mx > 0.0f ? 6.0f / mx : 0.0f;
+                    const float inv = mx > 0.0f ? p.fp4_qmax / mx : 0.0f;
 #pragma unroll
                     for (int q = 0; q < kQ; ++q) {
                         pk[q][0] = fp4_pack8(v + q * 16, inv);
@@ -833,7 +833,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                                 make_float2((float)((double)row_max * p.inv_15sqrt_b), (float)row_zero);
                         else
                             static_cast<float*>(p.scales)[real_row] =
-                                (float)((double)row_max * (OUT == OUT_INT4 ? p.inv_7sqrt_b : p.inv_6sqrt_b));
+                                (float)((double)row_max * (OUT == OUT_INT4 ? p.inv_7sqrt_b : p.inv_fp4sqrt_b));
                     }
                 }
             }

@@ -439,7 +439,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                 lo *= kTinyRowLift;
             }
             if constexpr (OUT == OUT_INT4) inv = hi > 0.0f ? 7.0f / hi : 0.0f;
-            if constexpr (OUT == OUT_FP4_TOKEN) inv = hi > 0.0f ? 6.0f / hi : 0.0f;
+            if constexpr (OUT == OUT_FP4_TOKEN) inv = hi > 0.0f ? p.fp4_qmax / hi : 0.0f;
             if constexpr (OUT == OUT_INT4_ASYM) qa = int4_asym_row(lo, hi);
         }
 #pragma unroll
@@ -500,7 +500,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
             if constexpr (OUT == OUT_INT4)
                 static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_7sqrt_b);
             if constexpr (OUT == OUT_FP4_TOKEN)
-                static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_6sqrt_b);
+                static_cast<float*>(p.scales)[row] = (float)((double)m[0] * p.inv_fp4sqrt_b);
             if constexpr (OUT == OUT_INT4_ASYM)
                 static_cast<float2*>(p.scales)[row] =
                     make_float2((float)((double)(m[0] + m[1]) * p.inv_15sqrt_b), (float)qa.z);

@@ -91,7 +91,7 @@ extern "C" perq_status_t perq_quant_error(const float* y, int64_t T, int32_t d, 
                                           const void* scales, perq_fmt_t fmt, float* out, void* hip_stream) {
     if (T < 0 || d <= 0 || d % 32 != 0) return PERQ_ERR_INVALID_ARG;
     if (fmt != PERQ_FMT_INT4_SYM_TOKEN && fmt != PERQ_FMT_MXFP4 && fmt != PERQ_FMT_INT4_ASYM_TOKEN &&
-        fmt != PERQ_FMT_FP4_TOKEN)
+        fmt != PERQ_FMT_FP4_TOKEN && fmt != PERQ_FMT_FP4_TOKEN_AMAX7)
         return PERQ_ERR_INVALID_ARG;
     if (T == 0) return PERQ_OK;
     if (y == nullptr || codes == nullptr || scales == nullptr || out == nullptr) return PERQ_ERR_INVALID_ARG;

@@ -217,9 +217,9 @@ def check_int4_asym(packed_gpu: np.ndarray, scales_gpu: np.ndarray, ref: dict, x
 
 
 def check_fp4_token(packed_gpu: np.ndarray, scales_gpu: np.ndarray, ref: dict, x_bits: np.ndarray,
-                    rep: ParityReport) -> None:
+                    rep: ParityReport, qmax: float = 6.0) -> None:
     """FP4 with one scale per token: scale within tolerance / 6, codes as for MXFP4 with the
-    quotient tolerance (1 + |v|/6) * 1e-5*||x||/s."""
+    quotient tolerance (1 + |v|/c) * 1e-5*||x||/s, c = 6 (7 for the step as Appendix B prints it)."""
     l2 = row_l2(x_bits)
     c_gpu = unpack_nibbles(packed_gpu)
     rep.neg_zero_seen += int((c_gpu == 8).sum())
@@ -227,7 +227,7 @@ def check_fp4_token(packed_gpu: np.ndarray, scales_gpu: np.ndarray, ref: dict, x
     c_orc = ref["codes"]
     rep.elements += c_orc.size
     s = ref["s64"]
-    bad_scale = np.abs(scales_gpu.astype(np.float64) - s) > REL_TOL * l2 / 6.0
+    bad_scale = np.abs(scales_gpu.astype(np.float64) - s) > REL_TOL * l2 / qmax
     rep.scale_fail += int(bad_scale.sum())
     if bad_scale.any():
         i = int(np.argmax(bad_scale))
@@ -243,7 +243,7 @@ def check_fp4_token(packed_gpu: np.ndarray, scales_gpu: np.ndarray, ref: dict, x
         same_sign = ((g & 8) == (o & 8)) | ((g & 7) == 0) | ((o & 7) == 0)
         adjacent = (np.abs((g & 7) - (o & 7)) == 1) & same_sign & (np.minimum(g & 7, o & 7) == k)
         inA = adjacent & (dist <= REL_TOL)
-        inB = adjacent & (dist <= (1.0 + v / 6.0) * REL_TOL * l2[rows] / safe[rows]) & ~inA
+        inB = adjacent & (dist <= (1.0 + v / qmax) * REL_TOL * l2[rows] / safe[rows]) & ~inA
         fail = ~(inA | inB)
         rep.code_mismatch_A += int(inA.sum())
         rep.code_mismatch_B += int(inB.sum())
@@ -266,7 +266,7 @@ def compare_apply(x_bits, perm, b, fmt, packed_gpu, scales_gpu, y_gpu=None, rota
     elif fmt == "int4_asym":
         check_int4_asym(packed_gpu, scales_gpu, ref, x_bits, rep)
     else:
-        check_fp4_token(packed_gpu, scales_gpu, ref, x_bits, rep)
+        check_fp4_token(packed_gpu, scales_gpu, ref, x_bits, rep, 7.0 if fmt == "fp4_token7" else 6.0)
     return rep
 
 

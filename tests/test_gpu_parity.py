@@ -288,7 +288,7 @@ TOKEN_FORMAT_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("fmt", ["int4_asym", "fp4_token"])
+@pytest.mark.parametrize("fmt", ["int4_asym", "fp4_token", "fp4_token7"])
 @pytest.mark.parametrize("algo", ALGOS)
 @pytest.mark.parametrize("T,d,bs", TOKEN_FORMAT_SHAPES)
 def test_token_formats_against_oracle(T, d, bs, algo, fmt):
@@ -304,7 +304,7 @@ def test_token_formats_against_oracle(T, d, bs, algo, fmt):
         assert_parity(x, perm, b, fmt, algo, rotate=rotate, label="token-format/perm")
 
 
-@pytest.mark.parametrize("fmt", ["int4_asym", "fp4_token"])
+@pytest.mark.parametrize("fmt", ["int4_asym", "fp4_token", "fp4_token7"])
 def test_token_formats_structured_rows(fmt):
     d, b = 1024, 64
     rows = [np.zeros(d), np.full(d, 0.75), np.full(d, -2.0)]
@@ -533,7 +533,7 @@ def test_quant_error_against_oracle_and_worst_case_bound(d, b):
     perm_t = torch.from_numpy(perm).cuda()
     y = binding.perq_permute_rotate_f32(xd, perm_t, b)
     Y = orc.block_hadamard(orc.permute_channels(orc.bf16_bits_to_f64(x_bits), perm), b)
-    for fmt in ("int4", "mxfp4", "int4_asym", "fp4_token"):
+    for fmt in ("int4", "mxfp4", "int4_asym", "fp4_token", "fp4_token7"):
         print(f"[case] quant error d={d} b={b} fmt={fmt}", flush=True)
         codes, scales = binding.perq_permute_rotate_quant(xd, perm_t, b, fmt)
         got = binding.perq_quant_error(y, codes, scales, fmt).cpu().numpy().astype(np.float64)
