@@ -78,13 +78,30 @@ def read_traffic(name: str, algo: str = "auto", identity: bool = False, arranged
     return value, {"file": rel, "kernel_line": kernel, "note": "committed rocprofv3 summary, not measured in this run"}
 
 
+def prepare_placement(perm_np, b, dev):
+    """The LDS placement perq_perm_prepare picks for this permutation (host, once per layer): device
+    table and what it does to the bank conflicts of the operand reads.  None where the shape's kernel
+    has no such gather."""
+    from paper_2601_22347_amd import binding
+    if perm_np.size <= 8192:
+        return None, None            # the library takes the plain path for rows this narrow
+    h0 = time.perf_counter()
+    try:
+        table, before, after, reads = binding.perq_perm_prepare(perm_np, b)
+    except binding.PerqError:
+        return None, None
+    ms = (time.perf_counter() - h0) * 1e3
+    return binding.placement_to_device(table, dev), {"lds_passes_per_read": [before / reads, after / reads],
+                                                     "prepare_host_ms": ms}
+
+
 # The configurations the bandwidth target (T >= 16384, d >= 4096) is quoted on: the headline and the
 # five others, every one timed by the default invocation.
 TARGET_SHAPES = ["llama8b_d4096_b128_int4_perm", "llama8b_d4096_b4096_int4_perm", "llama8b_d14336_b128_int4_perm",
                  "llama8b_d14336_b2048_int4_perm", "calib_apply_b32_mxfp4_perm", "calib_apply_b16_mxfp4_perm"]
 
 
-def time_target_shape(name, steps, warmup, pool_bytes, algo, check):
+def time_target_shape(name, steps, warmup, pool_bytes, algo, check, prepared=True):
     """One of the other target-size workloads: calibrate, time `steps` launches with HIP events over
     cycled buffer sets, compare sampled rows with the oracle.  Returns a dict for the report."""
     import torch
@@ -95,10 +112,13 @@ def time_target_shape(name, steps, warmup, pool_bytes, algo, check):
     dev = torch.device("cuda:0")
     x_bits = wl.apply_rows_parallel()
     perm_np = perm_t = None
+    place_t, place_info = None, None
     if use_perm:
         a_np = binding.perq_colabs_mean(binding.bits_to_device(wl.calib_rows())).cpu().numpy()
         perm_np = binding.perq_massdiff_perm(a_np, b)
         perm_t = torch.from_numpy(perm_np).to(dev)
+        if prepared and algo == "auto":
+            place_t, place_info = prepare_placement(perm_np, b, dev)
     per_set = T * d * 2 + T * d // 2
     nsets = max(2, int(np.ceil(pool_bytes / per_set)))
     x0 = binding.bits_to_device(x_bits, dev)
@@ -109,7 +129,7 @@ def time_target_shape(name, steps, warmup, pool_bytes, algo, check):
     def step(i):
         k = i % nsets
         binding.perq_permute_rotate_quant(xs[k], perm_t, b, fmt, codes=outs[k][0], scales=outs[k][1],
-                                          stream=stream, algo=algo)
+                                          stream=stream, algo=algo, placement=place_t)
     t_ramp = time.perf_counter()
     while time.perf_counter() - t_ramp < 0.15:
         for i in range(20):
@@ -126,7 +146,7 @@ def time_target_shape(name, steps, warmup, pool_bytes, algo, check):
     torch.cuda.synchronize()
     kern_ms = ev0.elapsed_time(ev1) / steps
     alg = algorithmic_bytes(T, d, fmt)
-    res = {"workload": name, "T": T, "d": d, "b": b, "fmt": fmt, "kernel_ms": kern_ms, "algorithmic_bytes": alg,
+    res = {"workload": name, "T": T, "d": d, "b": b, "fmt": fmt, "placement": place_info, "kernel_ms": kern_ms, "algorithmic_bytes": alg,
            "achieved_GBs": alg / (kern_ms * 1e-3) / 1e9, "frac": alg / (kern_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "tokens_per_s": T / (kern_ms * 1e-3)}
     if check:
@@ -155,6 +175,8 @@ def main() -> int:
     ap.add_argument("--identity", action="store_true", help="run the workload with P = I (no gather)")
     ap.add_argument("--arranged", action="store_true",
                     help="time the calibrated permutation in the order perq_perm_arrange gives its blocks")
+    ap.add_argument("--no-placement", action="store_true",
+                    help="call the fused path without the LDS placement of perq_perm_prepare")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-context", action="store_true",
@@ -187,6 +209,7 @@ def main() -> int:
     # ---- calibration: colabs mean on the device, greedy on the host (once, untimed region) ----
     calib = None
     perm_np = perm_t = None
+    place_t = None
     if use_perm:
         xc = binding.bits_to_device(wl.calib_rows())
         a_t = binding.perq_colabs_mean(xc)           # warm-up
@@ -208,6 +231,9 @@ def main() -> int:
         perm_t = torch.from_numpy(perm_np).to(dev)
         calib = {"colabs_mean_tokens": wl.calib_tokens, "colabs_mean_ms": e0.elapsed_time(e1) / 10,
                  "greedy_host_ms": greedy_ms}
+        if not args.no_placement and args.algo == "auto":
+            place_t, place_info = prepare_placement(perm_np, b, dev)
+            calib["placement"] = place_info
         del xc
 
     # ---- buffer pool larger than the last-level cache ----------------------------------------
@@ -221,7 +247,7 @@ def main() -> int:
     def step(i):
         k = i % nsets
         binding.perq_permute_rotate_quant(xs[k], perm_t, b, fmt, codes=outs[k][0], scales=outs[k][1],
-                                          stream=stream, algo=args.algo)
+                                          stream=stream, algo=args.algo, placement=place_t)
 
     # The device needs some tens of milliseconds of load before its clocks settle (the first
     # ~100 launches run 1.1-2.5x slower); run it up on the same work before the warm-up steps so
@@ -265,11 +291,22 @@ def main() -> int:
     context = None
     if not args.no_context:
         one_set_ms = timed(lambda i: binding.perq_permute_rotate_quant(xs[0], perm_t, b, fmt, codes=outs[0][0],
-                                                                       scales=outs[0][1], stream=stream, algo=args.algo),
+                                                                       scales=outs[0][1], stream=stream, algo=args.algo,
+                                                                       placement=place_t),
                            min(args.steps, 300))
+        if place_t is not None:
+            # the same launch without the prepared placement (fixed LDS layout): all buffer sets, in turns
+            def all_sets_pl(pl):
+                return timed(lambda i: binding.perq_permute_rotate_quant(
+                    xs[i % nsets], perm_t, b, fmt, codes=outs[i % nsets][0], scales=outs[i % nsets][1],
+                    stream=stream, algo=args.algo, placement=pl), min(args.steps, 300))
+            turns_pl = [(all_sets_pl(None), all_sets_pl(place_t)) for _ in range(3)]
+            placement_ab = {"fixed_layout_kernel_ms": float(np.mean([t[0] for t in turns_pl])),
+                            "prepared_kernel_ms": float(np.mean([t[1] for t in turns_pl]))}
         cp_src, cp_dst = xs[0].view(torch.uint8).reshape(-1), xs[1].view(torch.uint8).reshape(-1)
         copy_ms = timed(lambda i: cp_dst.copy_(cp_src), 50)
-        context = {"single_buffer_set_ms": one_set_ms,
+        context = {"placement_ab": placement_ab if place_t is not None else None,
+                   "single_buffer_set_ms": one_set_ms,
                    "single_buffer_set_note": "same call on one input/output set (%.0f MB; cache resident if well under "
                                              "256 MB)" % (per_set / 1e6),
                    "device_copy_GBs": 2 * cp_src.numel() / (copy_ms * 1e-3) / 1e9}
@@ -375,6 +412,7 @@ def main() -> int:
         "config": {"workload": args.workload, "T": T, "d": d, "b": b, "fmt": fmt,
                    "perm": ("greedy-calibrated, blocks arranged for the LDS gather, gather fused" if args.arranged
                             else "greedy-calibrated, gather fused") if use_perm else "identity",
+                   "lds_placement": "perq_perm_prepare" if place_t is not None else "fixed",
                    "algo": args.algo, "buffer_sets": nsets, "input_gen_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,

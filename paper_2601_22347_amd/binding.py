@@ -28,7 +28,8 @@ EXPORTS = ["perq_status_string", "perq_colabs_mean_workspace_bytes", "perq_colab
            "perq_colabs_absmax", "perq_perm_sorted", "perq_perm_zigzag", "perq_block_diagnostics",
            "perq_hadamard_base", "perq_perm_random", "perq_w4a4_mxfp4_gemm_ref", "perq_perm_arrange",
            "perq_perm_gather_cost", "perq_schedule_set", "perq_reset_schedule", "perq_schedule_selftest",
-           "perq_colabs_mean_static", "perq_quant_error"]
+           "perq_colabs_mean_static", "perq_quant_error", "perq_perm_prepared_bytes", "perq_perm_prepare",
+           "perq_perm_prepared_validate", "perq_permute_rotate_quant_prepared"]
 
 _lib = None
 
@@ -92,6 +93,14 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.perq_colabs_mean_static.restype = ctypes.c_int
     lib.perq_quant_error.argtypes = [vp, i64, i32, vp, vp, ctypes.c_int, vp, vp]
     lib.perq_quant_error.restype = ctypes.c_int
+    lib.perq_perm_prepared_bytes.argtypes = [i32]
+    lib.perq_perm_prepared_bytes.restype = sz
+    lib.perq_perm_prepare.argtypes = [vp, i32, i32, vp, vp, vp, vp]
+    lib.perq_perm_prepare.restype = ctypes.c_int
+    lib.perq_perm_prepared_validate.argtypes = [vp, vp, i32]
+    lib.perq_perm_prepared_validate.restype = ctypes.c_int
+    lib.perq_permute_rotate_quant_prepared.argtypes = [vp, i64, i32, i64, vp, vp, i32, ctypes.c_int, vp, vp, vp]
+    lib.perq_permute_rotate_quant_prepared.restype = ctypes.c_int
     lib.perq_schedule_set.argtypes = [vp]
     lib.perq_schedule_set.restype = ctypes.c_int32
     lib.perq_reset_schedule.argtypes = [vp]
@@ -192,6 +201,34 @@ def perq_perm_gather_cost(perm: np.ndarray, b: int):
     return passes.value, reads.value
 
 
+def perq_perm_prepare(perm: np.ndarray, b: int):
+    """(prepared uint8 [perq_perm_prepared_bytes(d)], passes_before, passes_after, reads): the permutation
+    in the form the fused call's LDS staging wants it."""
+    p = np.ascontiguousarray(perm, dtype=np.int32)
+    lib = load()
+    table = np.zeros(lib.perq_perm_prepared_bytes(p.size), dtype=np.uint8)
+    pb, pa, rd = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    st = lib.perq_perm_prepare(p.ctypes.data_as(ctypes.c_void_p), p.size, int(b), table.ctypes.data_as(ctypes.c_void_p),
+                               ctypes.byref(pb), ctypes.byref(pa), ctypes.byref(rd))
+    _check(st, "perq_perm_prepare")
+    return table, pb.value, pa.value, rd.value
+
+
+def prepared_parts(prepared: np.ndarray, d: int):
+    """(place of every position int32 [d], piece of the row in every slot uint16 [d/8]) of a prepared form."""
+    raw = np.ascontiguousarray(prepared, dtype=np.uint8)
+    return raw[:4 * d].view(np.int32), raw[4 * d:4 * d + d // 4].view(np.uint16)
+
+
+def perq_perm_prepared_validate(prepared: np.ndarray, perm: np.ndarray) -> bool:
+    p = np.ascontiguousarray(perm, dtype=np.int32)
+    t = np.ascontiguousarray(prepared, dtype=np.uint8)
+    if t.size != load().perq_perm_prepared_bytes(p.size):
+        return False
+    return load().perq_perm_prepared_validate(t.ctypes.data_as(ctypes.c_void_p), p.ctypes.data_as(ctypes.c_void_p),
+                                              p.size) == PERQ_OK
+
+
 def perq_perm_validate(perm: np.ndarray) -> bool:
     p = np.ascontiguousarray(perm, dtype=np.int32)
     return load().perq_perm_validate(p.ctypes.data_as(ctypes.c_void_p), p.shape[0]) == PERQ_OK
@@ -285,13 +322,19 @@ def alloc_outputs(T: int, d: int, fmt: str, device):
 
 
 def perq_permute_rotate_quant(x, perm, b: int, fmt: str, codes=None, scales=None, stream=None,
-                              algo: str = "auto"):
-    """x: CUDA bf16 [T, d]; perm: CUDA int32 [d] or None.  Returns (codes, scales) tensors."""
+                              algo: str = "auto", placement=None):
+    """x: CUDA bf16 [T, d]; perm: CUDA int32 [d] or None; placement: CUDA uint8 copy of what
+    perq_perm_prepare wrote for perm, or None.  Returns (codes, scales) tensors."""
     T, d, ldx = _check_x(x)
     if codes is None or scales is None:
         codes, scales = alloc_outputs(T, d, fmt, x.device)
     lib = load()
-    if algo == "auto":
+    if placement is not None:
+        if algo != "auto":
+            raise ValueError("a placement goes with algo='auto'")
+        st = lib.perq_permute_rotate_quant_prepared(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), _dev_ptr(placement), int(b),
+                                                    FMT[fmt], _dev_ptr(codes), _dev_ptr(scales), _stream_ptr(stream))
+    elif algo == "auto":
         st = lib.perq_permute_rotate_quant(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), int(b), FMT[fmt],
                                            _dev_ptr(codes), _dev_ptr(scales), _stream_ptr(stream))
     else:
@@ -345,6 +388,12 @@ def perq_w4a4_mxfp4_gemm_ref(a_codes, a_scales, w_codes, w_scales, out=None, str
                                          _stream_ptr(stream))
     _check(st, "perq_w4a4_mxfp4_gemm_ref")
     return out
+
+
+def placement_to_device(prepared: np.ndarray, device="cuda"):
+    """prepared form of a permutation (NumPy uint8) -> CUDA uint8 tensor."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(prepared, dtype=np.uint8)).to(device)
 
 
 def bits_to_device(bits: np.ndarray, device="cuda"):

@@ -90,6 +90,7 @@ perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, 
     p->T = T;
     p->ldx = ldx;
     p->perm = perm;
+    p->place = nullptr;
     p->codes = nullptr;
     p->scales = nullptr;
     p->y = nullptr;
@@ -137,42 +138,69 @@ perq_status_t dispatch(const ApplyParams& p, int out_kind, perq_algo_t algo, hip
 }  // namespace
 }  // namespace perq
 
-extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, int64_t T, int32_t d,
-                                                        int64_t ldx, const int32_t* perm, int32_t b,
-                                                        perq_fmt_t fmt, perq_algo_t algo, uint8_t* codes,
-                                                        void* scales, void* hip_stream) {
-    perq::ApplyParams p;
+namespace perq {
+namespace {
+perq_status_t quant_entry(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx, const int32_t* perm,
+                          const void* prepared, int32_t b, perq_fmt_t fmt, perq_algo_t algo, uint8_t* codes,
+                          void* scales, void* hip_stream) {
+    ApplyParams p;
     int out_kind;
     switch (fmt) {
-        case PERQ_FMT_INT4_SYM_TOKEN: out_kind = perq::OUT_INT4; break;
-        case PERQ_FMT_MXFP4: out_kind = perq::OUT_MXFP4; break;
-        case PERQ_FMT_INT4_ASYM_TOKEN: out_kind = perq::OUT_INT4_ASYM; break;
-        case PERQ_FMT_FP4_TOKEN: out_kind = perq::OUT_FP4_TOKEN; break;
-        case PERQ_FMT_FP4_TOKEN_AMAX7: out_kind = perq::OUT_FP4_TOKEN; break;
+        case PERQ_FMT_INT4_SYM_TOKEN: out_kind = OUT_INT4; break;
+        case PERQ_FMT_MXFP4: out_kind = OUT_MXFP4; break;
+        case PERQ_FMT_INT4_ASYM_TOKEN: out_kind = OUT_INT4_ASYM; break;
+        case PERQ_FMT_FP4_TOKEN: out_kind = OUT_FP4_TOKEN; break;
+        case PERQ_FMT_FP4_TOKEN_AMAX7: out_kind = OUT_FP4_TOKEN; break;
         default: return PERQ_ERR_INVALID_ARG;
     }
     if (algo != PERQ_ALGO_AUTO && algo != PERQ_ALGO_BUTTERFLY && algo != PERQ_ALGO_MFMA)
         return PERQ_ERR_INVALID_ARG;
-    const perq_status_t st = perq::check_apply(x_bf16, T, d, ldx, perm, b, &p);
+    const perq_status_t st = check_apply(x_bf16, T, d, ldx, perm, b, &p);
     if (st != PERQ_OK || p.T == 0) return st;
     if (codes == nullptr || scales == nullptr) return PERQ_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(codes) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     const uintptr_t scale_align = fmt == PERQ_FMT_MXFP4 ? 1u : (fmt == PERQ_FMT_INT4_ASYM_TOKEN ? 8u : 4u);
     if ((reinterpret_cast<uintptr_t>(scales) & (scale_align - 1u)) != 0) return PERQ_ERR_UNSUPPORTED;
+    if (prepared != nullptr && (reinterpret_cast<uintptr_t>(prepared) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     p.codes = codes;
     p.scales = scales;
+    // the placement belongs to the matrix-core kernel's staging of whole rows of d >= 4096 through perm
+    // The prepared form pays on rows of three tiles or more, where the operand reads keep the LDS
+    // busiest (d = 14336: 3 - 4 % less run time); the table lookup that has to come before a
+    // workgroup's first row loads costs rows of one or two tiles more than the reads gain (d = 4096,
+    // 8192: + 1 - 1.5 %), so those take the plain path.
+    if (prepared != nullptr && perm != nullptr && d > 8192 && d % 512 == 0 && is_pow2(b) && b <= 4096) {
+        // [int32 place of the channel of every position][uint16 granule of every slot]
+        p.perm = static_cast<const int32_t*>(prepared);
+        p.place = reinterpret_cast<const uint16_t*>(static_cast<const int32_t*>(prepared) + d);
+    }
     if (fmt == PERQ_FMT_FP4_TOKEN_AMAX7) {
         p.fp4_qmax = 7.0f;
         p.inv_fp4sqrt_b = 1.0 / (7.0 * std::sqrt((double)b));
     }
-    return perq::dispatch(p, out_kind, algo, static_cast<hipStream_t>(hip_stream));
+    return dispatch(p, out_kind, algo, static_cast<hipStream_t>(hip_stream));
+}
+}  // namespace
+}  // namespace perq
+
+extern "C" perq_status_t perq_permute_rotate_quant_algo(const uint16_t* x_bf16, int64_t T, int32_t d,
+                                                        int64_t ldx, const int32_t* perm, int32_t b,
+                                                        perq_fmt_t fmt, perq_algo_t algo, uint8_t* codes,
+                                                        void* scales, void* hip_stream) {
+    return perq::quant_entry(x_bf16, T, d, ldx, perm, nullptr, b, fmt, algo, codes, scales, hip_stream);
 }
 
 extern "C" perq_status_t perq_permute_rotate_quant(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,
                                                    const int32_t* perm, int32_t b, perq_fmt_t fmt,
                                                    uint8_t* codes, void* scales, void* hip_stream) {
-    return perq_permute_rotate_quant_algo(x_bf16, T, d, ldx, perm, b, fmt, PERQ_ALGO_AUTO, codes, scales,
-                                          hip_stream);
+    return perq::quant_entry(x_bf16, T, d, ldx, perm, nullptr, b, fmt, PERQ_ALGO_AUTO, codes, scales, hip_stream);
+}
+
+extern "C" perq_status_t perq_permute_rotate_quant_prepared(const uint16_t* x_bf16, int64_t T, int32_t d,
+                                                            int64_t ldx, const int32_t* perm,
+                                                            const void* prepared, int32_t b, perq_fmt_t fmt,
+                                                            uint8_t* codes, void* scales, void* hip_stream) {
+    return perq::quant_entry(x_bf16, T, d, ldx, perm, prepared, b, fmt, PERQ_ALGO_AUTO, codes, scales, hip_stream);
 }
 
 extern "C" perq_status_t perq_permute_rotate_f32(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t ldx,

@@ -7,6 +7,7 @@
 
 #include <algorithm>
 #include <array>
+#include <climits>
 #include <cmath>
 #include <cstdint>
 #include <numeric>
@@ -450,6 +451,200 @@ extern "C" perq_status_t perq_perm_arrange(const int32_t* perm, int32_t d, int32
     if (gather_passes(arranged.data(), d, s, nullptr) >= gather_passes(perm, d, s, nullptr))
         std::copy(perm, perm + d, arranged.begin());
     std::copy(arranged.begin(), arranged.end(), perm_out);
+    return PERQ_OK;
+}
+
+// ---- placement of a row's 16-byte granules in LDS for a given permutation ----------------------------
+// The kernel stages a row with direct-to-LDS loads of 16 bytes per lane, 64 consecutive slots per
+// instruction, and is free in which granule of the row a lane fetches.  Eight consecutive lanes fetch
+// the eight granules of one 128-byte line of the row, in any order: the loads stay as coalesced as
+// they are with the fixed layout.  The bank of a channel is 4 * (slot % 8) + (channel % 8) / 2, so the
+// order decides, per granule, which group of four banks its eight channels land in.  The fixed
+// swizzle of perq_layout.h spreads the identity and strided patterns; for an arbitrary permutation the
+// 32 lanes of a read meet at random (3.2 - 3.5 passes per read).  Here the order inside every line is
+// chosen for the permutation at hand.  Lanes whose channels share the pattern (channel % 8) / 2 can
+// only be told apart by the eight groups, so a read whose 32 channels hold more than eight of one
+// pattern keeps two passes.  The two 64-byte halves of a line stay halves (four neighbouring lanes fetch
+// one of them); about 2.3 passes per read are reached.
+namespace {
+
+struct PlacementProblem {
+    int32_t d;
+    int32_t n_granules;
+    std::vector<std::vector<std::pair<int32_t, uint8_t>>> member;   // per granule: (read, word % 4) of its words
+    int32_t n_reads;
+};
+
+PlacementProblem placement_problem(const int32_t* perm, int32_t d, const GatherShape& s) {
+    PlacementProblem pb;
+    pb.d = d;
+    pb.n_granules = d / 8;
+    pb.member.assign((size_t)pb.n_granules, {});
+    int32_t r = 0;
+    for_each_read(d, s, [&](const int32_t* pos, int n) {
+        int32_t words[32];
+        int nw = 0;
+        for (int i = 0; i < n; ++i) {
+            const int32_t w = perm[pos[i]] >> 1;
+            bool dup = false;
+            for (int k = 0; k < nw; ++k) dup = dup || words[k] == w;
+            if (!dup) words[nw++] = w;
+        }
+        for (int k = 0; k < nw; ++k) pb.member[(size_t)(words[k] >> 2)].emplace_back(r, (uint8_t)(words[k] & 3));
+        ++r;
+    });
+    pb.n_reads = r;
+    return pb;
+}
+
+// sum over the reads of the fullest bank, for group[granule] in 0..7
+int64_t placement_passes(const PlacementProblem& pb, const std::vector<uint8_t>& group) {
+    std::vector<std::array<uint8_t, 32>> load((size_t)pb.n_reads);
+    for (auto& l : load) l.fill(0);
+    for (int32_t g = 0; g < pb.n_granules; ++g)
+        for (const auto& m : pb.member[(size_t)g]) ++load[(size_t)m.first][4 * group[(size_t)g] + m.second];
+    int64_t total = 0;
+    for (const auto& l : load) total += *std::max_element(l.begin(), l.end());
+    return total;
+}
+
+}  // namespace
+
+extern "C" size_t perq_perm_prepared_bytes(int32_t d) {
+    if (d <= 0 || d % 8 != 0) return 0;
+    return (size_t)d * sizeof(int32_t) + (size_t)(d / 8) * sizeof(uint16_t);
+}
+
+extern "C" perq_status_t perq_perm_prepare(const int32_t* perm, int32_t d, int32_t b, void* prepared,
+                                           int64_t* passes_before, int64_t* passes_after, int64_t* reads) {
+    if (perm == nullptr || prepared == nullptr || d <= 0 || b <= 0) return PERQ_ERR_INVALID_ARG;
+    if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
+    const GatherShape s = gather_shape(d, b);
+    if (!s.ok) return PERQ_ERR_UNSUPPORTED;
+    const PlacementProblem pb = placement_problem(perm, d, s);
+    const int32_t G = pb.n_granules;                                // (d is a multiple of 512)
+    // what the fixed swizzle gives
+    std::vector<uint8_t> group((size_t)G);
+    for (int32_t g = 0; g < G; ++g) group[(size_t)g] = (uint8_t)(perq::layout::granule_slot((uint32_t)g) & 7u);
+    const int64_t before = placement_passes(pb, group);
+
+    // One 128-byte line of the row (8 granules) at a time: its granules take the 8 groups of four banks
+    // in some order, the order that costs least given the lines placed so far (an 8 x 8 assignment,
+    // solved exactly over subsets).  Cost of a granule in a group: for every read it takes part in,
+    // the words already in that bank, and a large penalty where it would raise the read's fullest bank.
+    std::vector<std::array<uint8_t, 32>> load((size_t)pb.n_reads);
+    for (auto& l : load) l.fill(0);
+    uint64_t rng = 0x9E3779B97F4A7C15ull;
+    auto next_rand = [&]() {
+        rng ^= rng << 13; rng ^= rng >> 7; rng ^= rng << 17;
+        return rng;
+    };
+    const int32_t n_lines = G / 8;
+    std::vector<int32_t> order((size_t)n_lines);
+    std::iota(order.begin(), order.end(), 0);
+    for (int32_t i = n_lines - 1; i > 0; --i) std::swap(order[(size_t)i], order[(size_t)(next_rand() % (uint64_t)(i + 1))]);
+    std::vector<uint8_t> chosen((size_t)G, 0xFF);
+    auto put = [&](int32_t g, int q, int sign) {
+        for (const auto& m : pb.member[(size_t)g]) load[(size_t)m.first][4 * q + m.second] = (uint8_t)(load[(size_t)m.first][4 * q + m.second] + sign);
+    };
+    auto place_line = [&](int32_t line) {
+        int32_t cost[8][8];
+        for (int i = 0; i < 8; ++i) {
+            const int32_t g = 8 * line + i;
+            for (int q = 0; q < 8; ++q) {
+                int32_t c = 0;
+                for (const auto& m : pb.member[(size_t)g]) {
+                    const auto& l = load[(size_t)m.first];
+                    const int here = l[4 * q + m.second];
+                    const int top = *std::max_element(l.begin(), l.end());
+                    c += here + (here + 1 > top ? 1000 : 0);
+                }
+                cost[i][q] = c;
+            }
+        }
+        // granule i = popcount(mask) - 1 takes a group in mask; the two halves of the line (64 bytes, what
+        // four neighbouring lanes fetch together) stay halves, in either order
+        int32_t best_total = INT32_MAX;
+        uint8_t best_q[8] = {0, 1, 2, 3, 4, 5, 6, 7};
+        for (int swap = 0; swap < 2; ++swap) {
+            int32_t best[256];
+            int8_t pick[256];
+            best[0] = 0;
+            for (int mask = 1; mask < 256; ++mask) {
+                const int i = __builtin_popcount(mask) - 1;
+                best[mask] = INT32_MAX;
+                pick[mask] = -1;
+                for (int q = 0; q < 8; ++q) {
+                    if (!((mask >> q) & 1) || ((q >> 2) != ((i >> 2) ^ swap))) continue;
+                    const int32_t prev = best[mask ^ (1 << q)];
+                    if (prev == INT32_MAX) continue;
+                    const int32_t c = prev + cost[i][q];
+                    if (c < best[mask]) { best[mask] = c; pick[mask] = (int8_t)q; }
+                }
+            }
+            if (best[255] < best_total) {
+                best_total = best[255];
+                int mask = 255;
+                for (int i = 7; i >= 0; --i) {
+                    const int q = pick[mask];
+                    best_q[i] = (uint8_t)q;
+                    mask ^= 1 << q;
+                }
+            }
+        }
+        for (int i = 0; i < 8; ++i) chosen[(size_t)(8 * line + i)] = best_q[i];
+        for (int i = 0; i < 8; ++i) put(8 * line + i, chosen[(size_t)(8 * line + i)], +1);
+    };
+    for (int32_t line : order) place_line(line);
+    int64_t now = 0;
+    for (const auto& l : load) now += *std::max_element(l.begin(), l.end());
+    for (int sweep = 0; sweep < 4; ++sweep) {
+        for (int32_t line : order) {
+            for (int i = 0; i < 8; ++i) put(8 * line + i, chosen[(size_t)(8 * line + i)], -1);
+            place_line(line);
+        }
+        int64_t then = 0;
+        for (const auto& l : load) then += *std::max_element(l.begin(), l.end());
+        if (then >= now) break;
+        now = then;
+    }
+    int64_t after = placement_passes(pb, chosen);
+    if (after >= before) {               // never worse than the fixed swizzle
+        chosen = group;
+        after = before;
+    }
+    // a granule stays in its line: slot = first slot of the line + its group
+    int32_t* place_of_position = static_cast<int32_t*>(prepared);
+    uint16_t* granule_of_slot = reinterpret_cast<uint16_t*>(place_of_position + d);
+    std::vector<int32_t> slot_of_granule((size_t)G);
+    for (int32_t g = 0; g < G; ++g) {
+        const int32_t slot = (g & ~7) | chosen[(size_t)g];
+        slot_of_granule[(size_t)g] = slot;
+        granule_of_slot[slot] = (uint16_t)g;
+    }
+    std::vector<int32_t> places((size_t)d);               // (perm may be the first part of `prepared`)
+    for (int32_t i = 0; i < d; ++i) places[(size_t)i] = slot_of_granule[(size_t)(perm[i] >> 3)] * 8 + (perm[i] & 7);
+    std::copy(places.begin(), places.end(), place_of_position);
+    if (passes_before != nullptr) *passes_before = before;
+    if (passes_after != nullptr) *passes_after = after;
+    if (reads != nullptr) *reads = pb.n_reads;
+    return PERQ_OK;
+}
+
+extern "C" perq_status_t perq_perm_prepared_validate(const void* prepared, const int32_t* perm, int32_t d) {
+    if (prepared == nullptr || perm == nullptr || d <= 0 || d % 512 != 0) return PERQ_ERR_INVALID_ARG;
+    if (perq_perm_validate(perm, d) != PERQ_OK) return PERQ_ERR_INVALID_ARG;
+    const int32_t G = d / 8;
+    const int32_t* place_of_position = static_cast<const int32_t*>(prepared);
+    const uint16_t* granule_of_slot = reinterpret_cast<const uint16_t*>(place_of_position + d);
+    std::vector<int32_t> slot_of_granule((size_t)G, -1);
+    for (int32_t slot = 0; slot < G; ++slot) {
+        const int32_t g = granule_of_slot[slot];
+        if (g >= G || g / 8 != slot / 8 || slot_of_granule[(size_t)g] >= 0) return PERQ_ERR_INVALID_ARG;
+        slot_of_granule[(size_t)g] = slot;
+    }
+    for (int32_t i = 0; i < d; ++i)
+        if (place_of_position[i] != slot_of_granule[(size_t)(perm[i] >> 3)] * 8 + (perm[i] & 7)) return PERQ_ERR_INVALID_ARG;
     return PERQ_OK;
 }
 

@@ -317,6 +317,18 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     for (int k = 0; k < 5; ++k) sgn[k] = (c >> k) & 1 ? -1.0f : 1.0f;
 
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
+    // Where a granule of the row sits in its staging buffer: the fixed swizzle, or the placement the
+    // caller prepared for this permutation (perq_perm_prepare).  In that case p.perm holds, per
+    // position, the channel's place in the staged row (slot * 8 + channel % 8) instead of the channel,
+    // and p.place the granule of the row that every slot takes (inside the slot's line of 8; entries
+    // are clipped to the row).
+    const uint16_t* const place = p.place;
+    auto slot_of = [&](uint32_t granule) -> uint32_t { return place == nullptr ? granule_slot(granule) : granule; };
+    auto granule_at = [&](uint32_t slot) -> uint32_t {
+        if (place == nullptr) return granule_slot(slot);
+        const uint32_t v = place[slot];
+        return v < gpr ? v : gpr - 1u;
+    };
 
     // One direct-to-LDS instruction moves 64 consecutive slots (1 KiB) of one row.  On rows of its
     // own, wave w fills row slot w; otherwise the instructions are dealt round-robin to the waves
@@ -344,7 +356,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             ok = rslot < (uint32_t)g.rows;
         }
         ok = ok && k < g.nload;
-        ld_lane_off[k] = granule_slot(in_row + (uint32_t)lane) * 16u + rslot * (uint32_t)(p.ldx * 2);
+        ld_lane_off[k] = (ok ? granule_at(in_row + (uint32_t)lane) : 0u) * 16u + rslot * (uint32_t)(p.ldx * 2);
         if (ok) (rslot == 0 ? mask_row0 : mask_row1) |= 1u << k;
     }
     const unsigned char* xbytes = reinterpret_cast<const unsigned char*>(p.x);
@@ -368,23 +380,20 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // in issue order, so once no more than the n operations issued after a group's loads remain,
     // that group has landed.  n must not exceed the true count; a smaller n only waits longer.
     auto wait_vm_le = [&](int n) {
-        switch (n) {
-            case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-            case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-            case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-            case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-            case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-            case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-            case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-            case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-            case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-            case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
-            case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-            case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
-            case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-            case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
-            default: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
+        // (vmcnt is a six-bit count, split over bits 3:0 and 15:14 of the operand)
+#define PERQ_VMCNT(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
+        switch (n < 0 ? 0 : (n > 63 ? 63 : n)) {
+            PERQ_VMCNT(0) PERQ_VMCNT(1) PERQ_VMCNT(2) PERQ_VMCNT(3) PERQ_VMCNT(4) PERQ_VMCNT(5) PERQ_VMCNT(6) PERQ_VMCNT(7)
+            PERQ_VMCNT(8) PERQ_VMCNT(9) PERQ_VMCNT(10) PERQ_VMCNT(11) PERQ_VMCNT(12) PERQ_VMCNT(13) PERQ_VMCNT(14) PERQ_VMCNT(15)
+            PERQ_VMCNT(16) PERQ_VMCNT(17) PERQ_VMCNT(18) PERQ_VMCNT(19) PERQ_VMCNT(20) PERQ_VMCNT(21) PERQ_VMCNT(22) PERQ_VMCNT(23)
+            PERQ_VMCNT(24) PERQ_VMCNT(25) PERQ_VMCNT(26) PERQ_VMCNT(27) PERQ_VMCNT(28) PERQ_VMCNT(29) PERQ_VMCNT(30) PERQ_VMCNT(31)
+            PERQ_VMCNT(32) PERQ_VMCNT(33) PERQ_VMCNT(34) PERQ_VMCNT(35) PERQ_VMCNT(36) PERQ_VMCNT(37) PERQ_VMCNT(38) PERQ_VMCNT(39)
+            PERQ_VMCNT(40) PERQ_VMCNT(41) PERQ_VMCNT(42) PERQ_VMCNT(43) PERQ_VMCNT(44) PERQ_VMCNT(45) PERQ_VMCNT(46) PERQ_VMCNT(47)
+            PERQ_VMCNT(48) PERQ_VMCNT(49) PERQ_VMCNT(50) PERQ_VMCNT(51) PERQ_VMCNT(52) PERQ_VMCNT(53) PERQ_VMCNT(54) PERQ_VMCNT(55)
+            PERQ_VMCNT(56) PERQ_VMCNT(57) PERQ_VMCNT(58) PERQ_VMCNT(59) PERQ_VMCNT(60) PERQ_VMCNT(61) PERQ_VMCNT(62)
+            default: __builtin_amdgcn_s_waitcnt(0x0F70 | 15 | (3 << 14)); break;
         }
+#undef PERQ_VMCNT
     };
     // Loads issued after those of the unit about to be consumed.  (The stores issued in between are
     // not counted: that only makes the wait stricter, and counting them measured no faster.)
@@ -893,8 +902,8 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
                 for (int e = 0; e < 8; e += 2) {
                     const uint32_t a0 = ch[8 * j + e], a1 = ch[8 * j + e + 1];
-                    const uint32_t o0 = (granule_slot(a0 >> 3) << 4) | ((a0 & 7u) << 1);
-                    const uint32_t o1 = (granule_slot(a1 >> 3) << 4) | ((a1 & 7u) << 1);
+                    const uint32_t o0 = (slot_of(a0 >> 3) << 4) | ((a0 & 7u) << 1);
+                    const uint32_t o1 = (slot_of(a1 >> 3) << 4) | ((a1 & 7u) << 1);
                     w[e >> 1] = o0 | (o1 << 16);
                 }
                 *reinterpret_cast<uint4*>(lds + kBufStride + (2u * (uint32_t)wave + j) * 1024u + 16u * (uint32_t)lane) =
@@ -973,7 +982,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     const uint32_t ch[4] = {fb + pe[jj].x, fb + pe[jj].y, fb + pe[jj].z, fb + pe[jj].w};
                     uint32_t o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1);
+                    for (int e = 0; e < 4; ++e) o[e] = (slot_of(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1);
                     *reinterpret_cast<uint2*>(tab + 2u * t) = make_uint2(o[0] | (o[1] << 16), o[2] | (o[3] << 16));
                 }
             }
@@ -1042,7 +1051,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     src[f * 8 + e] =
-                        qvalid[f >> 1] ? (uint32_t)rr * g.row_bytes + ((granule_slot(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1))
+                        qvalid[f >> 1] ? (uint32_t)rr * g.row_bytes + ((slot_of(ch[e] >> 3) << 4) | ((ch[e] & 7u) << 1))
                                        : kZeroSlot;
             }
         }
@@ -1069,7 +1078,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             for (int e = 0; e < 8; ++e) {
                 const bool ok = (int)hk_pos(sigma_i, 16u * f + 8u * h + e) < tile_len;
                 const uint32_t cc = ch[f * 8 + e];
-                src[f * 8 + e] = ok ? (uint32_t)rr * g.row_bytes + ((granule_slot(cc >> 3) << 4) | ((cc & 7u) << 1)) : kZeroSlot;
+                src[f * 8 + e] = ok ? (uint32_t)rr * g.row_bytes + ((slot_of(cc >> 3) << 4) | ((cc & 7u) << 1)) : kZeroSlot;
             }
         }
     }

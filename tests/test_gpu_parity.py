@@ -518,6 +518,54 @@ def test_calibrated_permutations_ranked_by_the_bound():
     assert bound["random"] >= bound["massdiff"]           # a shuffle spreads them by chance only
 
 
+# ---- the fused call with a placement prepared for the permutation -------------------------------------
+@pytest.mark.parametrize("T,d,b,fmt", [(300, 4096, 128, "int4"), (4200, 4096, 128, "int4"), (300, 4096, 4096, "int4"),
+                                       (2100, 8192, 32, "mxfp4"), (1030, 14336, 128, "int4"), (1030, 14336, 2048, "int4_asym"),
+                                       (270, 14336, 512, "fp4_token"), (530, 20480, 1024, "int4"), (600, 12288, 64, "mxfp4")])
+def test_prepared_placement_gives_the_plain_call_bit_for_bit(T, d, b, fmt):
+    """Where the row's pieces sit in LDS is between the staging loads and the operand reads of one
+    launch: the table of perq_perm_prepare, and any other valid table, must not change a bit."""
+    torch = _torch()
+    rng = np.random.default_rng(T + d + b)
+    x_bits = synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d)) * np.exp(rng.uniform(-2, 2, size=(T, 1))))
+    perm = rng.permutation(d).astype(np.int32)
+    x = binding.bits_to_device(x_bits)
+    perm_t = torch.from_numpy(perm).cuda()
+    print(f"[case] prepared placement T={T} d={d} b={b} fmt={fmt}", flush=True)
+    plain = binding.perq_permute_rotate_quant(x, perm_t, b, fmt)
+    table, before, after, reads = binding.perq_perm_prepare(perm, b)
+    assert after < before
+    got = binding.perq_permute_rotate_quant(x, perm_t, b, fmt, placement=binding.placement_to_device(table))
+    torch.cuda.synchronize()
+    assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1])
+    # a random valid form: the 8 pieces of every 128-byte line shuffled
+    G = d // 8
+    slot_of = np.concatenate([8 * w + rng.permutation(8) for w in range(G // 8)]).astype(np.int64)
+    granule_of = np.empty(G, dtype=np.uint16); granule_of[slot_of] = np.arange(G, dtype=np.uint16)
+    place = (slot_of[perm >> 3] * 8 + (perm & 7)).astype(np.int32)
+    rnd = np.concatenate([place.view(np.uint8), granule_of.view(np.uint8)])
+    assert binding.perq_perm_prepared_validate(rnd, perm)
+    got = binding.perq_permute_rotate_quant(x, perm_t, b, fmt, placement=binding.placement_to_device(rnd))
+    torch.cuda.synchronize()
+    assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1])
+    # and against the oracle
+    rep = parity.compare_apply(x_bits[:128], perm, b, fmt, got[0][:128].cpu().numpy(), got[1][:128].cpu().numpy())
+    assert rep.ok(), (rep.summary(), rep.notes[:5])
+
+
+def test_prepared_placement_is_ignored_where_no_such_gather_runs():
+    torch = _torch()
+    rng = np.random.default_rng(77)
+    for T, d, b in ((50, 2048, 128), (40, 8192, 8192), (30, 3072, 768)):
+        x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_normal((T, d))))
+        perm_t = torch.from_numpy(rng.permutation(d).astype(np.int32)).cuda()
+        junk = torch.full((4 * d + d // 4,), 0x7F, dtype=torch.uint8, device="cuda")
+        plain = binding.perq_permute_rotate_quant(x, perm_t, b, "int4")
+        got = binding.perq_permute_rotate_quant(x, perm_t, b, "int4", placement=junk)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1])
+
+
 # ---- per-token quantization error (Section 3) ---------------------------------------------------------
 @pytest.mark.parametrize("d,b", [(256, 16), (2048, 64), (4096, 128), (4096, 4096), (3072, 768)])
 def test_quant_error_against_oracle_and_worst_case_bound(d, b):

@@ -276,3 +276,65 @@ def test_schedule_model_rejects_shapes_off_the_queues():
     assert binding.perq_schedule_selftest(0, 512, 4, 0, 1) == INV
     assert binding.perq_schedule_selftest(8192, 512, 0, 0, 1) == INV
     assert binding.status_string(4) == "PERQ_ERR_INTERNAL"
+
+
+# ---- placement of a row's pieces in LDS for a permutation (perq_perm_prepare) ---------------------------
+@pytest.mark.parametrize("d,b", [(4096, 128), (4096, 4096), (8192, 32), (14336, 128), (14336, 2048), (20480, 1024)])
+def test_prepared_placement_is_a_line_bijection_and_never_worse(d, b):
+    rng = np.random.default_rng(d + b)
+    perm = rng.permutation(d).astype(np.int32)
+    table, before, after, reads = binding.perq_perm_prepare(perm, b)
+    assert table.dtype == np.uint8 and table.size == 4 * d + d // 4
+    G = d // 8
+    place, granule_of = binding.prepared_parts(table, d)
+    granule_of = granule_of.astype(np.int64)
+    assert np.array_equal(np.sort(granule_of), np.arange(G))                   # every slot takes one piece
+    assert np.array_equal(granule_of // 8, np.arange(G) // 8)                  # inside the 128-byte lines of the row
+    slot_of = np.empty(G, dtype=np.int64); slot_of[granule_of] = np.arange(G)
+    # a position's place: the slot of its channel's piece, and the channel's place inside the piece
+    assert np.array_equal(place, slot_of[perm >> 3] * 8 + (perm & 7))
+    assert binding.perq_perm_prepared_validate(table, perm)
+    # the count for the fixed layout is the one perq_perm_gather_cost reports; the table lowers it
+    assert (before, reads) == binding.perq_perm_gather_cost(perm, b)
+    assert after <= before and after < 0.8 * before                            # 3.2 - 3.5 -> about 2.3 passes per read
+    assert after >= reads
+    # recount with plain NumPy what the table gives: per read the largest number of distinct words per bank
+    # (bank = 4 * (slot % 8) + (channel % 8) // 2), for the low-K reads of the first tile
+    if b < 1024:
+        total = 0
+        for f in range(8):
+            for e in range(8):
+                for h in range(2):
+                    pos = np.array([(l * 4 + (f >> 1)) * 32 + 16 * (f & 1) + 8 * h + e for l in range(32)])
+                    words = np.unique(perm[pos] >> 1)
+                    bank = 4 * (slot_of[words >> 2] % 8) + (words & 3)
+                    total += np.bincount(bank, minlength=32).max()
+        # the first tile's 128 reads: the whole count for a row of one tile, a part of it otherwise
+        assert 128 <= total and (total == after if d == 4096 else total < after)
+    again = binding.perq_perm_prepare(perm, b)
+    assert np.array_equal(again[0], table) and again[1:] == (before, after, reads)     # deterministic
+    # a form that belongs to another permutation, or a broken one, is told apart
+    other = perm.copy(); other[[0, 9]] = other[[9, 0]]
+    assert not binding.perq_perm_prepared_validate(table, other)
+    bad = table.copy(); bad[4 * d], bad[4 * d + 2] = bad[4 * d + 2], bad[4 * d]
+    assert not binding.perq_perm_prepared_validate(bad, perm)
+
+
+def test_prepare_on_regular_and_unsupported_shapes(lib):
+    # the identity is served without conflicts by the fixed layout: nothing to gain, nothing lost
+    ident = np.arange(4096, dtype=np.int32)
+    table, before, after, reads = binding.perq_perm_prepare(ident, 128)
+    assert after <= before and binding.perq_perm_prepared_validate(table, ident)
+    perm = np.arange(2048, dtype=np.int32)
+    buf = np.zeros(2048 * 5, dtype=np.uint8)
+    pp, pt = perm.ctypes.data_as(ctypes.c_void_p), buf.ctypes.data_as(ctypes.c_void_p)
+    assert lib.perq_perm_prepare(pp, 2048, 128, pt, None, None, None) == binding.PERQ_ERR_UNSUPPORTED     # d < 4096
+    assert lib.perq_perm_prepare(None, 4096, 128, pt, None, None, None) == binding.PERQ_ERR_INVALID_ARG
+    assert lib.perq_perm_prepare(pp, 2048, 128, None, None, None, None) == binding.PERQ_ERR_INVALID_ARG
+    perm[3] = 4
+    assert lib.perq_perm_prepare(pp, 2048, 128, pt, None, None, None) == binding.PERQ_ERR_INVALID_ARG      # not a bijection
+    assert lib.perq_perm_prepared_bytes(14336) == 14336 * 4 + 14336 // 4 and lib.perq_perm_prepared_bytes(7) == 0
+    fake = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10004)
+    assert lib.perq_permute_rotate_quant_prepared(fake, 4, 4096, 4096, fake, odd, 128, 0, fake, fake, None) == binding.PERQ_ERR_UNSUPPORTED
+    assert lib.perq_permute_rotate_quant_prepared(fake, 4, 4096, 4096, fake, fake, 100, 0, fake, fake, None) == binding.PERQ_ERR_INVALID_ARG
