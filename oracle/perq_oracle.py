@@ -349,9 +349,9 @@ def quant_mxfp4(Y: np.ndarray, E_given: np.ndarray | None = None):
       E is clamped to [0, 254]; an all-zero group has E = 0.
       element code = round-to-nearest-even of y / 2^(E-127) on the e2m1 grid, saturating at 6;
       zero is always emitted as +0.
-    Reading: the appendix's printed scale formula is inconsistent with its own sentence
-    "rounded down to a power of 2" and with the OCP format it says it follows; the sentence
-    and the format are taken.
+    Reading: the appendix's printed scale formula is inconsistent with its own sentence before
+    it (the group maximum goes down to the next power of two) and with the OCP format it says it
+    follows; the sentence and the format are taken.
 
     `E_given` (uint8 [T, d/32]) replaces the computed exponents; the parity tests use it to
     check the codes of a group whose maximum sits on a power-of-two boundary.
