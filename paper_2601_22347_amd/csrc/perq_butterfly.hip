@@ -249,12 +249,12 @@ butterfly_kernel(ApplyParams p, BflyGeom g) {
             }
 #pragma unroll
             for (int j = 0; j < kRed; ++j) {
-                if (g.nt > 1) m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
-                if (g.nt > 2) m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
-                if (g.nt > 4) m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
-                if (g.nt > 8) m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
-                if (g.nt > 16) m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
-                if (g.nt > 32) m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+                if (g.nt > 1) m[j] = lane_max<1>(m[j]);
+                if (g.nt > 2) m[j] = lane_max<2>(m[j]);
+                if (g.nt > 4) m[j] = lane_max<4>(m[j]);
+                if (g.nt > 8) m[j] = lane_max<8>(m[j]);
+                if (g.nt > 16) m[j] = lane_max<16>(m[j]);
+                if (g.nt > 32) m[j] = lane_max<32>(m[j]);
             }
             if (g.waves_per_row > 1) {
                 float* red = reinterpret_cast<float*>(lds + g.red_off);

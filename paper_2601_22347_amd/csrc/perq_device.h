@@ -78,6 +78,28 @@ __device__ __forceinline__ float lane_xor(float v) {
     }
 }
 
+// max(v, value of lane l ^ M) as one step of a reduction that runs M = 1, 2, 4, ... upwards: for
+// M = 4 the lanes l ^ 1, l ^ 2 must already hold the same v (the mirror inside 8 lanes then reaches
+// the other quad).  Vector-ALU data movement only: a trip through the LDS crossbar would also wait
+// for every LDS read the wave has in flight.
+template <int M>
+__device__ __forceinline__ float lane_max(float v) {
+    if constexpr (M == 4) {
+        const int iv = __float_as_int(v);
+        return fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(iv, iv, 0x141, 0xF, 0xF, false)));   // row_half_mirror
+    } else if constexpr (M == 16) {
+        const uint32_t u = __float_as_uint(v);
+        auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);      // [r0 r0 r2 r2], [r1 r1 r3 r3]
+        return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    } else if constexpr (M == 32) {
+        const uint32_t u = __float_as_uint(v);
+        auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);      // [lo lo], [hi hi]
+        return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    } else {
+        return fmaxf(v, lane_xor<M>(v));
+    }
+}
+
 // One radix-2 butterfly stage across lanes for N registers: v <- (lane & M) ? p - v : p + v,
 // p = value of lane ^ M.  `sgn` is -1 in lanes with bit M set, +1 elsewhere.
 template <int M, int N>

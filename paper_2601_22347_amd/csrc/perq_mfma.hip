@@ -367,11 +367,13 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         const int64_t row0 = wave_local ? (int64_t)unit : (int64_t)unit * g.rows;
         const unsigned char* rp = xbytes + row0 * ldx_bytes;
         const uint32_t m = row0 + 1 < p.T ? (mask_row0 | mask_row1) : mask_row0;
+        auto load = [&](int k) {
+            __builtin_amdgcn_global_load_lds(rp + ld_lane_off[k], lds + buf_off + lds_base0 + (uint32_t)k * lds_stride,
+                                             16, 0, 2 /* nt */);
+        };
 #pragma unroll
         for (int k = 0; k < kMaxLoad; ++k) {
-            if ((m >> k) & 1u)
-                __builtin_amdgcn_global_load_lds(rp + ld_lane_off[k], lds + buf_off + lds_base0 + (uint32_t)k * lds_stride,
-                                                 16, 0, 2 /* nt */);
+            if ((m >> k) & 1u) load(k);
         }
         return __builtin_popcount(m);
     };
@@ -418,6 +420,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // units_q + workers_q tickets per launch; whoever draws the last one puts the counter back to
     // zero for the next launch.
     const bool dyn = g.dynamic != 0;
+    const bool whole_wave_row = g.row_c_bits == 5 && !g.row_per_half;     // no folded rows in a wave
     const uint32_t unit_rows = wave_local ? 1u : (uint32_t)g.rows;
     const uint32_t n_workers = wave_local ? gridDim.x * NWAVES : gridDim.x;
     const uint32_t worker = wave_local ? blockIdx.x * NWAVES + (uint32_t)wave : blockIdx.x;
@@ -677,7 +680,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) m = fmaxf(m, fabsf(v[q * 16 + r]));
                     // the other half of the 32-group: the other half-wave, or the neighbouring lane
-                    m = fmaxf(m, kHighK ? lane_xor<1>(m) : lane_xor<32>(m));
+                    m = kHighK ? lane_max<1>(m) : lane_max<32>(m);
                     const int E = mx_shared_exponent(m, p.half_log2b);
                     const float scale = __uint_as_float((uint32_t)(E + p.half_log2b) << 23);
                     pk[q][0] = mxfp4_pack8(v + q * 16, scale);
@@ -720,12 +723,19 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 // (folded rows, low-K modes only: a real row is 4, 8 or 16 neighbouring values of c and
                 //  both half-waves, so the exchange stops at the row's edge)
                 for (int j = 0; j < kRed; ++j) {
-                    m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
-                    m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
-                    if (g.row_c_bits > 2) m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
-                    if (g.row_c_bits > 3) m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
-                    if (g.row_c_bits > 4) m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
-                    if (!g.row_per_half) m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+                    m[j] = lane_max<1>(m[j]);
+                    m[j] = lane_max<2>(m[j]);
+                    if (whole_wave_row) {
+                        m[j] = lane_max<4>(m[j]);
+                        m[j] = lane_max<8>(m[j]);
+                        m[j] = lane_max<16>(m[j]);
+                        m[j] = lane_max<32>(m[j]);
+                    } else {
+                        if (g.row_c_bits > 2) m[j] = lane_max<4>(m[j]);
+                        if (g.row_c_bits > 3) m[j] = lane_max<8>(m[j]);
+                        if (g.row_c_bits > 4) m[j] = lane_max<16>(m[j]);
+                        if (!g.row_per_half) m[j] = lane_max<32>(m[j]);
+                    }
                 }
                 if (!wave_local) {
                     // extremes across the row's waves; scratch alternates with the group parity so

@@ -399,12 +399,12 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
             }
 #pragma unroll
             for (int j = 0; j < kRed; ++j) {
-                m[j] = fmaxf(m[j], lane_xor<1>(m[j]));
-                m[j] = fmaxf(m[j], lane_xor<2>(m[j]));
-                m[j] = fmaxf(m[j], lane_xor<4>(m[j]));
-                m[j] = fmaxf(m[j], lane_xor<8>(m[j]));
-                m[j] = fmaxf(m[j], lane_xor<16>(m[j]));
-                m[j] = fmaxf(m[j], lane_xor<32>(m[j]));
+                m[j] = lane_max<1>(m[j]);
+                m[j] = lane_max<2>(m[j]);
+                m[j] = lane_max<4>(m[j]);
+                m[j] = lane_max<8>(m[j]);
+                m[j] = lane_max<16>(m[j]);
+                m[j] = lane_max<32>(m[j]);
             }
             if (lane == 0) {
 #pragma unroll
@@ -468,8 +468,8 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                                 val[e] *= g.norm256;
                                 gm = fmaxf(gm, fabsf(val[e]));
                             }
-                            gm = fmaxf(gm, lane_xor<1>(gm));
-                            if constexpr (kRun == 8) gm = fmaxf(gm, lane_xor<2>(gm));
+                            gm = lane_max<1>(gm);
+                            if constexpr (kRun == 8) gm = lane_max<2>(gm);
                             const int E = mx_shared_exponent(gm, 8);
                             const float scale = __uint_as_float((uint32_t)(E + 8) << 23);
 #pragma unroll
