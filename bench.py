@@ -79,19 +79,19 @@ def read_traffic(name: str, algo: str = "auto", identity: bool = False, arranged
 
 
 def prepare_placement(perm_np, b, dev):
-    """The LDS placement perq_perm_prepare picks for this permutation (host, once per layer): device
-    table and what it does to the bank conflicts of the operand reads.  None where the shape's kernel
-    has no such gather."""
+    """The form perq_perm_prepare writes for this permutation (host, once per layer: the operand offsets
+    in the kernel's lane order and, for wide rows, the LDS placement): device copy, and what the
+    placement does to the bank conflicts of the operand reads.  None where the shape's kernel has no
+    such gather."""
     from paper_2601_22347_amd import binding
-    if perm_np.size <= 8192:
-        return None, None            # the library takes the plain path for rows this narrow
     h0 = time.perf_counter()
     try:
         table, before, after, reads = binding.perq_perm_prepare(perm_np, b)
     except binding.PerqError:
         return None, None
     ms = (time.perf_counter() - h0) * 1e3
-    return binding.placement_to_device(table, dev), {"lds_passes_per_read": [before / reads, after / reads],
+    placed = perm_np.size > 8192        # narrower rows keep the fixed layout
+    return binding.placement_to_device(table, dev), {"lds_passes_per_read": [before / reads, (after if placed else before) / reads],
                                                      "prepare_host_ms": ms}
 
 
@@ -176,7 +176,7 @@ def main() -> int:
     ap.add_argument("--arranged", action="store_true",
                     help="time the calibrated permutation in the order perq_perm_arrange gives its blocks")
     ap.add_argument("--no-placement", action="store_true",
-                    help="call the fused path without the LDS placement of perq_perm_prepare")
+                    help="call the fused path without the prepared form of perq_perm_prepare")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-context", action="store_true",
@@ -295,13 +295,14 @@ def main() -> int:
                                                                        placement=place_t),
                            min(args.steps, 300))
         if place_t is not None:
-            # the same launch without the prepared placement (fixed LDS layout): all buffer sets, in turns
+            # the same launch with the plain call (perm turned into addresses by every launch, fixed LDS
+            # layout): all buffer sets, in turns
             def all_sets_pl(pl):
                 return timed(lambda i: binding.perq_permute_rotate_quant(
                     xs[i % nsets], perm_t, b, fmt, codes=outs[i % nsets][0], scales=outs[i % nsets][1],
                     stream=stream, algo=args.algo, placement=pl), min(args.steps, 300))
             turns_pl = [(all_sets_pl(None), all_sets_pl(place_t)) for _ in range(3)]
-            placement_ab = {"fixed_layout_kernel_ms": float(np.mean([t[0] for t in turns_pl])),
+            placement_ab = {"plain_call_kernel_ms": float(np.mean([t[0] for t in turns_pl])),
                             "prepared_kernel_ms": float(np.mean([t[1] for t in turns_pl]))}
         cp_src, cp_dst = xs[0].view(torch.uint8).reshape(-1), xs[1].view(torch.uint8).reshape(-1)
         copy_ms = timed(lambda i: cp_dst.copy_(cp_src), 50)
@@ -412,7 +413,7 @@ def main() -> int:
         "config": {"workload": args.workload, "T": T, "d": d, "b": b, "fmt": fmt,
                    "perm": ("greedy-calibrated, blocks arranged for the LDS gather, gather fused" if args.arranged
                             else "greedy-calibrated, gather fused") if use_perm else "identity",
-                   "lds_placement": "perq_perm_prepare" if place_t is not None else "fixed",
+                   "prepared_form": "perq_perm_prepare" if place_t is not None else "none",
                    "algo": args.algo, "buffer_sets": nsets, "input_gen_s": round(gen_s, 1)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_source,

@@ -227,44 +227,55 @@ perq_status_t perq_permute_rotate_quant(const uint16_t* x_bf16, int64_t T, int32
                                         uint8_t* codes, void* scales, void* hip_stream);
 
 /*
- * A placement of the row's 16-byte pieces in the kernel's staging memory, chosen for one permutation
- * (host), and the fused call that uses it.  With a permutation the main kernel fetches every operand
- * element with a 2-byte LDS read; where a row's pieces lie in LDS decides how many of the 32 lanes of
- * a read meet in one bank.  The kernel's fixed layout serves P = I and regular patterns; on an
- * arbitrary permutation a read takes 3.2 - 3.5 passes.  perq_perm_prepare picks, for the permutation
- * at hand, the group of four banks every piece of eight channels lands in (the loads that stage the
- * row stay as coalesced as they are: pieces move only inside their 128-byte line of the row), which
- * brings a read to about 2.3 passes.  P itself is untouched and so is every output bit: the placement is a matter
- * between the staging loads and the operand reads of one launch (the prepared form also saves the
- * launch the conversion of channel numbers into LDS addresses).  Once per layer; 6 ms for
- * d = 4096, 25 ms for d = 14336 on one host core.
+ * A permutation prepared for the main kernel (host, once per layer), and the fused call that uses it.
+ * Two things are worked out ahead of the launches; P itself is untouched and so is every output bit.
+ *   Operand offsets.  With a permutation the kernel fetches every operand element with a 2-byte LDS
+ * read at an address that depends on perm, the lane and the kernel's operand layout.  The plain call
+ * turns perm into these addresses at the start of every launch (about 5 us of a short launch); the
+ * prepared form holds them as 16-bit offsets in the order the lanes need them, for both of the
+ * kernel's operand layouts (b <= 512 and b >= 1024), so a lane fetches its 64 offsets with eight
+ * 16-byte loads issued ahead of its first row loads.
+ *   Placement (rows wider than 8192).  Where a row's 16-byte pieces lie in LDS decides how many of the
+ * 32 lanes of a read meet in one bank.  The kernel's fixed layout serves P = I and regular patterns; on
+ * an arbitrary permutation a read takes 3.2 - 3.5 passes.  perq_perm_prepare picks, for the permutation
+ * at hand, the group of four banks every piece of eight channels lands in (the loads that stage the row
+ * stay as coalesced as they are: pieces move only inside their 128-byte line of the row), which brings
+ * a read to about 2.3 passes.  Rows of one or two tiles keep the fixed layout: the lookup that would
+ * have to come before a workgroup's first row loads costs them more than the reads gain.
+ * Once per layer; 6 ms for d = 4096, 25 ms for d = 14336 on one host core.
  *   perq_perm_prepared_bytes   size of the prepared form for rows of d channels: d int32 (per position,
- *                              the place of its channel in the staged row: slot * 8 + channel % 8)
- *                              followed by d / 8 uint16 (the piece of the row in every slot); 0 if d
- *                              is not a positive multiple of 8
+ *                              the place of its channel in the staged row: slot * 8 + channel % 8),
+ *                              d / 8 uint16 (the piece of the row in every slot), then two tables
+ *                              (b <= 512, b >= 1024) of ceil(d / 4096) * 4096 uint16 each: per tile of
+ *                              4096 positions, operand fragment (8), lane (64) and element (8) the byte
+ *                              offset of that operand in the staged row (fixed layout for d <= 8192,
+ *                              else the placement; 0xFFFF past the end of the row); 0 if d is not a
+ *                              positive multiple of 8
  *   perq_perm_prepare          perm: host, int32 [d], a bijection; b: the block size the fused call
- *                              will be made with (only whether b >= 1024 matters: the two families of
- *                              read patterns); prepared: host, out, perq_perm_prepared_bytes(d);
+ *                              will be made with (the placement is chosen for the read pattern of
+ *                              b <= 512 or of b >= 1024; the output is correct with either);
+ *                              prepared: host, out, perq_perm_prepared_bytes(d);
  *                              passes_before / passes_after / reads (each may be NULL): the sum over
  *                              the read instructions of a row of the largest number of lanes per
- *                              bank, with the fixed layout and with the prepared one, and their
+ *                              bank, with the fixed layout and with the chosen placement, and their
  *                              number.  Never worse than the fixed layout.  UNSUPPORTED for shapes
  *                              whose kernel has no such gather (d < 4096, d % 512 != 0, b > 4096 or
  *                              not a power of two).
  *   perq_perm_prepared_validate  OK iff `prepared` (host) is what some placement gives for `perm`: every
  *                              piece inside its line of 8, every slot taken once, every position's
- *                              place that of its channel
+ *                              place that of its channel, every operand offset the one that follows
  *   perq_permute_rotate_quant_prepared   perq_permute_rotate_quant with the prepared form (device,
- *                              16-byte aligned, a copy of what perq_perm_prepare wrote for this perm and
- *                              d; or NULL: the plain call).  perm is still passed: calls that would not
- *                              run on the main kernel with a permutation, and rows of d <= 8192 (where
- *                              the lookup before a workgroup's first loads costs more than the reads
- *                              gain), use it and ignore `prepared`.
- *                              `prepared` is not checked on the device; its entries are used like those
- *                              of perm (every access stays inside the row if they are below d, and
- *                              slot entries past the row are clipped), but a form that does not
- *                              belong to perm gives undefined output values.  Any valid form gives the
- *                              outputs of the plain call, bit for bit.
+ *                              16-byte aligned, a copy of all perq_perm_prepared_bytes(d) bytes that
+ *                              perq_perm_prepare wrote for this perm and d; or NULL: the plain call).
+ *                              perm is still passed: calls that do not run on the main kernel with a
+ *                              permutation use it and ignore `prepared`.
+ *                              `prepared` is not checked on the device.  Its entries address LDS only
+ *                              (an offset past the staged rows reads zero or another row's data, never
+ *                              outside the workgroup's memory) and pieces of the row (clipped to the
+ *                              row), so a form that does not belong to perm gives undefined output
+ *                              values and nothing else; a buffer shorter than
+ *                              perq_perm_prepared_bytes(d) is read past its end.  Any valid form gives
+ *                              the outputs of the plain call, bit for bit.
  */
 size_t perq_perm_prepared_bytes(int32_t d);
 perq_status_t perq_perm_prepare(const int32_t* perm, int32_t d, int32_t b, void* prepared,

@@ -215,9 +215,13 @@ def perq_perm_prepare(perm: np.ndarray, b: int):
 
 
 def prepared_parts(prepared: np.ndarray, d: int):
-    """(place of every position int32 [d], piece of the row in every slot uint16 [d/8]) of a prepared form."""
+    """(place of every position int32 [d], piece of the row in every slot uint16 [d/8], operand offsets in
+    lane order uint16 [2][tiles][8][64][8]) of a prepared form."""
     raw = np.ascontiguousarray(prepared, dtype=np.uint8)
-    return raw[:4 * d].view(np.int32), raw[4 * d:4 * d + d // 4].view(np.uint16)
+    at = 4 * d + d // 4
+    tiles = (d + 4095) // 4096
+    return (raw[:4 * d].view(np.int32), raw[4 * d:at].view(np.uint16),
+            raw[at:at + 2 * tiles * 8192].view(np.uint16).reshape(2, tiles, 8, 64, 8))
 
 
 def perq_perm_prepared_validate(prepared: np.ndarray, perm: np.ndarray) -> bool:
@@ -332,6 +336,10 @@ def perq_permute_rotate_quant(x, perm, b: int, fmt: str, codes=None, scales=None
     if placement is not None:
         if algo != "auto":
             raise ValueError("a placement goes with algo='auto'")
+        import torch
+        if placement.dtype != torch.uint8 or not placement.is_contiguous() or \
+                placement.numel() != lib.perq_perm_prepared_bytes(d):
+            raise ValueError("placement: not the bytes perq_perm_prepare writes for rows of this width")
         st = lib.perq_permute_rotate_quant_prepared(_dev_ptr(x), T, d, ldx, _dev_ptr(perm), _dev_ptr(placement), int(b),
                                                     FMT[fmt], _dev_ptr(codes), _dev_ptr(scales), _stream_ptr(stream))
     elif algo == "auto":

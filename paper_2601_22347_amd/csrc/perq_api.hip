@@ -2,6 +2,7 @@
 #include "perq.h"
 #include "perq_base.h"
 #include "perq_launch.h"
+#include "perq_layout.h"
 
 #include <cmath>
 #include <map>
@@ -91,6 +92,7 @@ perq_status_t check_apply(const uint16_t* x, int64_t T, int32_t d, int64_t ldx, 
     p->ldx = ldx;
     p->perm = perm;
     p->place = nullptr;
+    p->lane_table = nullptr;
     p->codes = nullptr;
     p->scales = nullptr;
     p->y = nullptr;
@@ -164,15 +166,23 @@ perq_status_t quant_entry(const uint16_t* x_bf16, int64_t T, int32_t d, int64_t 
     if (prepared != nullptr && (reinterpret_cast<uintptr_t>(prepared) & 15u) != 0) return PERQ_ERR_UNSUPPORTED;
     p.codes = codes;
     p.scales = scales;
-    // the placement belongs to the matrix-core kernel's staging of whole rows of d >= 4096 through perm
-    // The prepared form pays on rows of three tiles or more, where the operand reads keep the LDS
-    // busiest (d = 14336: 3 - 4 % less run time); the table lookup that has to come before a
+    // The prepared form belongs to the matrix-core kernel's staging of whole rows of d >= 4096 through
+    // perm (the same shapes perq_perm_prepare accepts); every other shape takes perm as it is.
+    //   Its tables of operand offsets in lane order spare every launch the work of turning perm into
+    // LDS addresses.  Its placement pays on rows of three tiles or more, where the operand reads keep
+    // the LDS busiest (d = 14336: 3 - 4 % less run time); the lookup that has to come before a
     // workgroup's first row loads costs rows of one or two tiles more than the reads gain (d = 4096,
-    // 8192: + 1 - 1.5 %), so those take the plain path.
-    if (prepared != nullptr && perm != nullptr && d > 8192 && d % 512 == 0 && is_pow2(b) && b <= 4096) {
-        // [int32 place of the channel of every position][uint16 granule of every slot]
-        p.perm = static_cast<const int32_t*>(prepared);
-        p.place = reinterpret_cast<const uint16_t*>(static_cast<const int32_t*>(prepared) + d);
+    // 8192: + 1 - 1.5 %), so those stay in the fixed layout (layout::placement_applies, which the
+    // tables follow).
+    if (prepared != nullptr && perm != nullptr && algo == PERQ_ALGO_AUTO && d >= 4096 && d % 512 == 0 && is_pow2(b) &&
+        b >= 16 && b <= 4096 && mfma_supports(p)) {
+        // [int32 place of the channel of every position][uint16 granule of every slot][uint16 lane tables]
+        const int32_t* places = static_cast<const int32_t*>(prepared);
+        if (layout::placement_applies(d)) {
+            p.perm = places;
+            p.place = reinterpret_cast<const uint16_t*>(places + d);
+        }
+        p.lane_table = reinterpret_cast<const uint16_t*>(places + d) + d / 8;
     }
     if (fmt == PERQ_FMT_FP4_TOKEN_AMAX7) {
         p.fp4_qmax = 7.0f;

@@ -22,6 +22,7 @@ struct ApplyParams {
     int64_t ldx;
     const int32_t* perm;    // int32 [d] or nullptr
     const uint16_t* place;  // prepared placement: granule of the row in every LDS slot (then perm holds places), or nullptr
+    const uint16_t* lane_table;  // prepared operand offsets in the matrix-core kernel's lane order (two tables), or nullptr
     uint8_t* codes;         // [T, d/2]
     void* scales;           // float [T], uint8 [T, d/32] or float [T][2] (step, zero point)
     float* y;               // [T, d] (test entry), or [T, 4] (diagnostics)

@@ -510,9 +510,41 @@ int64_t placement_passes(const PlacementProblem& pb, const std::vector<uint8_t>&
 
 }  // namespace
 
+// The prepared form of a permutation: [int32 place of the channel of every position, d entries]
+// [uint16 granule of every slot, d / 8 entries] [uint16 operand offsets in the kernel's lane order, one
+// table for b <= 512 and one for b >= 1024, each tiles x 8 fragments x 64 lanes x 8 elements].
+namespace {
+size_t prepared_lane_tables_at(int32_t d) { return (size_t)d * sizeof(int32_t) + (size_t)(d / 8) * sizeof(uint16_t); }
+size_t lane_table_entries(int32_t d) { return (size_t)((d + 4095) / 4096) * 4096; }
+
+// Byte offset inside the staged row of the operand that read (f, e) of lane l fetches, for every tile,
+// fragment, lane and element: what the kernel otherwise works out from `perm` at the start of every
+// launch.  0xFFFF (no offset is odd) marks positions past the end of a ragged last tile.
+void fill_lane_tables(const int32_t* perm, int32_t d, const std::vector<int32_t>& slot_of_granule, uint16_t* tables) {
+    const bool placed = perq::layout::placement_applies(d);
+    const int tiles = (d + 4095) / 4096;
+    for (int mode = 0; mode < 2; ++mode) {
+        uint16_t* tab = tables + (size_t)mode * lane_table_entries(d);
+        for (int t = 0; t < tiles; ++t)
+            for (uint32_t f = 0; f < 8; ++f)
+                for (uint32_t lane = 0; lane < 64; ++lane)
+                    for (uint32_t e = 0; e < 8; ++e) {
+                        const int64_t pos = 4096 * (int64_t)t + perq::layout::gather_pos(mode == 1, lane & 31u, lane >> 5, f, e);
+                        uint16_t off = 0xFFFFu;
+                        if (pos < d) {
+                            const uint32_t a = (uint32_t)perm[pos];
+                            off = placed ? (uint16_t)(((uint32_t)slot_of_granule[a >> 3] << 4) | ((a & 7u) << 1))
+                                         : (uint16_t)perq::layout::channel_offset(a);
+                        }
+                        tab[(((size_t)t * 8 + f) * 64 + lane) * 8 + e] = off;
+                    }
+    }
+}
+}  // namespace
+
 extern "C" size_t perq_perm_prepared_bytes(int32_t d) {
     if (d <= 0 || d % 8 != 0) return 0;
-    return (size_t)d * sizeof(int32_t) + (size_t)(d / 8) * sizeof(uint16_t);
+    return prepared_lane_tables_at(d) + 2 * lane_table_entries(d) * sizeof(uint16_t);
 }
 
 extern "C" perq_status_t perq_perm_prepare(const int32_t* perm, int32_t d, int32_t b, void* prepared,
@@ -624,7 +656,10 @@ extern "C" perq_status_t perq_perm_prepare(const int32_t* perm, int32_t d, int32
     }
     std::vector<int32_t> places((size_t)d);               // (perm may be the first part of `prepared`)
     for (int32_t i = 0; i < d; ++i) places[(size_t)i] = slot_of_granule[(size_t)(perm[i] >> 3)] * 8 + (perm[i] & 7);
+    std::vector<uint16_t> tables(2 * lane_table_entries(d));
+    fill_lane_tables(perm, d, slot_of_granule, tables.data());
     std::copy(places.begin(), places.end(), place_of_position);
+    std::copy(tables.begin(), tables.end(), reinterpret_cast<uint16_t*>(static_cast<char*>(prepared) + prepared_lane_tables_at(d)));
     if (passes_before != nullptr) *passes_before = before;
     if (passes_after != nullptr) *passes_after = after;
     if (reads != nullptr) *reads = pb.n_reads;
@@ -645,6 +680,10 @@ extern "C" perq_status_t perq_perm_prepared_validate(const void* prepared, const
     }
     for (int32_t i = 0; i < d; ++i)
         if (place_of_position[i] != slot_of_granule[(size_t)(perm[i] >> 3)] * 8 + (perm[i] & 7)) return PERQ_ERR_INVALID_ARG;
+    std::vector<uint16_t> tables(2 * lane_table_entries(d));
+    fill_lane_tables(perm, d, slot_of_granule, tables.data());
+    const uint16_t* given = reinterpret_cast<const uint16_t*>(static_cast<const char*>(prepared) + prepared_lane_tables_at(d));
+    if (!std::equal(tables.begin(), tables.end(), given)) return PERQ_ERR_INVALID_ARG;
     return PERQ_OK;
 }
 

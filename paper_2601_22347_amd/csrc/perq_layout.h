@@ -36,5 +36,9 @@ __host__ __device__ inline __attribute__((always_inline)) uint32_t gather_pos(bo
                   : (l * 4u + (f >> 1)) * 32u + 16u * (f & 1u) + 8u * h + e;
 }
 
+// Rows this wide are staged in the placement a caller prepared for the permutation
+// (perq_perm_prepare); narrower ones keep granule_slot.
+__host__ __device__ inline __attribute__((always_inline)) bool placement_applies(int32_t d) { return d > 8192; }
+
 }  // namespace layout
 }  // namespace perq

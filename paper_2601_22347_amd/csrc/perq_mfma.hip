@@ -884,9 +884,10 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     // row loads: nothing queues behind those, and no ordinary LDS access meets a pending
     // direct-to-LDS load.
     constexpr bool shared_src = SHARED;
+    const bool use_table = PERM && p.lane_table != nullptr;      // operand addresses prepared by the caller, see below
     static_assert(!SHARED || (PERM && NWAVES == 4), "the shared table is for four waves with the same tile");
     if constexpr (SHARED) {
-        {
+        if (!use_table) {
             uint32_t ch[16];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -924,21 +925,66 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
 
     // Operand addresses through `perm`, general case with two staging buffers: see below.
     constexpr bool kLdsTable = PERM && !SHARED && kDouble;
+    // Operand addresses the caller prepared (perq_perm_prepare): the eight fragments of a lane are eight
+    // 16-byte reads of the tile's table.  They are issued ahead of the first row loads and waited for
+    // by count, so they arrive while the rows are on their way.  The reads and the wait are written as
+    // instructions: the compiler's own wait for a load it knows would cover every row load behind it.
+    auto src_from_table = [&](auto&& issue_rows) {
+        if constexpr (PERM) {
+            const uint32_t tiles = ((uint32_t)d + (uint32_t)kTile - 1u) / (uint32_t)kTile;
+            const bool have = tile_len > 0;                                     // (uniform in a wave)
+            const uint4* tb = reinterpret_cast<const uint4*>(p.lane_table) +
+                              ((kHighK ? tiles : 0u) + (have ? (uint32_t)tile_base / (uint32_t)kTile : 0u)) * 512u + (uint32_t)lane;
+            u32x4_t t[8];
+#pragma unroll
+            for (int f = 0; f < 8; ++f) asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(t[f]) : "v"(tb + f * 64) : "memory");
+            const int n_after = issue_rows();        // vector-memory operations issued behind the table reads (or fewer)
+            // (the count is waited for in a branch of its own; the statement after it is where the
+            //  compiler is told that the eight registers have their values, on one path for all counts)
+#define PERQ_TABLE_WAIT(N) case N: asm volatile("s_waitcnt vmcnt(" #N ")" ::: "memory"); break;
+            switch (n_after < 0 ? 0 : n_after) {
+                PERQ_TABLE_WAIT(1) PERQ_TABLE_WAIT(2) PERQ_TABLE_WAIT(3) PERQ_TABLE_WAIT(4) PERQ_TABLE_WAIT(5) PERQ_TABLE_WAIT(6)
+                PERQ_TABLE_WAIT(7) PERQ_TABLE_WAIT(8) PERQ_TABLE_WAIT(9) PERQ_TABLE_WAIT(10) PERQ_TABLE_WAIT(11) PERQ_TABLE_WAIT(12)
+                PERQ_TABLE_WAIT(13) PERQ_TABLE_WAIT(14) PERQ_TABLE_WAIT(15) PERQ_TABLE_WAIT(16)
+                default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+            }
+#undef PERQ_TABLE_WAIT
+            asm volatile("; table reads have landed"
+                         : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7])::"memory");
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < kQ; ++q) qvalid[q] = kHighK ? hk_run(q) < tile_len : (c * kQ + q) * 32 < tile_len;
+            const uint32_t base = (uint32_t)rr * g.row_bytes;
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const uint32_t w = t[f][e >> 1];
+                    const uint32_t off = (e & 1) ? w >> 16 : w & 0xFFFFu;
+                    src[f * 8 + e] = !have || off == 0xFFFFu ? kZeroSlot : base + off;     // (0xFFFF: past the row's end)
+                }
+            }
+        }
+    };
     if (tid < 4) {
         *reinterpret_cast<uint32_t*>(lds + kZeroSlot + 4 * tid) = 0u;
-        if constexpr (kDouble && !kLdsTable) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
+        if (kDouble && (!kLdsTable || use_table)) *reinterpret_cast<uint32_t*>(lds + kBufStride + kZeroSlot + 4 * tid) = 0u;
     }
     __syncthreads();
-    auto first_loads = [&]() {
-        if (u_cur < n_units) issue_loads(u_cur, 0u);
+    // (returns the number of row loads issued: the ticket's atomic, issued between them, is not counted)
+    auto first_loads = [&]() -> int {
+        const int n0 = u_cur < n_units ? issue_loads(u_cur, 0u) : 0;
         if (drawing) draw();
         if constexpr (kDouble) n_behind = u_nxt < n_units ? issue_loads(u_nxt, kBufStride) : 0;
+        return n0 + (kDouble ? n_behind : 0);
     };
-    if constexpr (!SHARED && !kLdsTable) first_loads();
+    if constexpr (!SHARED && !kLdsTable) {
+        if (!use_table) first_loads();
+    }
 
     // Shared case: collect the eight fragments of addresses the four waves have left in LDS.
     if constexpr (SHARED) {
-        {
+        if (!use_table) {
             const uint32_t base = (uint32_t)rr * g.row_bytes;
 #pragma unroll
             for (int q = 0; q < kQ; ++q) qvalid[q] = true;
@@ -955,12 +1001,17 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             __syncthreads();      // the table's place is about to be loaded over
         }
     }
-    if constexpr (SHARED) first_loads();
+    if constexpr (SHARED) {
+        if (use_table) src_from_table(first_loads);
+        else first_loads();
+    }
     // Otherwise every wave builds its own addresses (and reads `perm`) while the first row groups
     // are already on their way from HBM.  All sixteen 16-byte reads of `perm` are issued together
     // (absent sub-blocks re-read position 0 and are redirected to the zero slot).
     if constexpr (shared_src) {
         // done above
+    } else if (use_table) {
+        src_from_table(first_loads);
     } else if constexpr (kLdsTable) {
         // The first unit is requested, then the tile of `perm` is read in order (16-byte loads,
         // 1 KiB per instruction: read lane by lane along the operand layout the same entries cost

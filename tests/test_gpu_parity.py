@@ -8,6 +8,7 @@ import pytest
 
 sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 import parity  # noqa: E402
+import prepared_form  # noqa: E402
 from oracle import perq_oracle as orc  # noqa: E402
 from paper_2601_22347_amd import binding, synth  # noqa: E402
 
@@ -521,10 +522,15 @@ def test_calibrated_permutations_ranked_by_the_bound():
 # ---- the fused call with a placement prepared for the permutation -------------------------------------
 @pytest.mark.parametrize("T,d,b,fmt", [(300, 4096, 128, "int4"), (4200, 4096, 128, "int4"), (300, 4096, 4096, "int4"),
                                        (2100, 8192, 32, "mxfp4"), (1030, 14336, 128, "int4"), (1030, 14336, 2048, "int4_asym"),
-                                       (270, 14336, 512, "fp4_token"), (530, 20480, 1024, "int4"), (600, 12288, 64, "mxfp4")])
+                                       (270, 14336, 512, "fp4_token"), (530, 20480, 1024, "int4"), (600, 12288, 64, "mxfp4"),
+                                       (1, 4096, 16, "int4"), (3, 8192, 1024, "mxfp4"), (2050, 8192, 32, "int4"),
+                                       (5, 12288, 4096, "int4"), (77, 14336, 2048, "int4"), (130, 32768, 256, "int4"),
+                                       (9, 24576, 4096, "fp4_token"), (2, 16384, 64, "int4_asym")])
 def test_prepared_placement_gives_the_plain_call_bit_for_bit(T, d, b, fmt):
-    """Where the row's pieces sit in LDS is between the staging loads and the operand reads of one
-    launch: the table of perq_perm_prepare, and any other valid table, must not change a bit."""
+    """The prepared form only moves work out of the launch (operand offsets worked out once per
+    permutation) and, on wide rows, decides where the row's pieces sit in LDS between the staging loads
+    and the operand reads of one launch: the form of perq_perm_prepare, and any other valid one, must
+    not change a bit."""
     torch = _torch()
     rng = np.random.default_rng(T + d + b)
     x_bits = synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d)) * np.exp(rng.uniform(-2, 2, size=(T, 1))))
@@ -535,21 +541,20 @@ def test_prepared_placement_gives_the_plain_call_bit_for_bit(T, d, b, fmt):
     plain = binding.perq_permute_rotate_quant(x, perm_t, b, fmt)
     table, before, after, reads = binding.perq_perm_prepare(perm, b)
     assert after < before
+    rows = min(T, 128)
     got = binding.perq_permute_rotate_quant(x, perm_t, b, fmt, placement=binding.placement_to_device(table))
     torch.cuda.synchronize()
     assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1])
     # a random valid form: the 8 pieces of every 128-byte line shuffled
     G = d // 8
     slot_of = np.concatenate([8 * w + rng.permutation(8) for w in range(G // 8)]).astype(np.int64)
-    granule_of = np.empty(G, dtype=np.uint16); granule_of[slot_of] = np.arange(G, dtype=np.uint16)
-    place = (slot_of[perm >> 3] * 8 + (perm & 7)).astype(np.int32)
-    rnd = np.concatenate([place.view(np.uint8), granule_of.view(np.uint8)])
+    rnd = prepared_form.assemble(perm, slot_of)
     assert binding.perq_perm_prepared_validate(rnd, perm)
     got = binding.perq_permute_rotate_quant(x, perm_t, b, fmt, placement=binding.placement_to_device(rnd))
     torch.cuda.synchronize()
     assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1])
     # and against the oracle
-    rep = parity.compare_apply(x_bits[:128], perm, b, fmt, got[0][:128].cpu().numpy(), got[1][:128].cpu().numpy())
+    rep = parity.compare_apply(x_bits[:rows], perm, b, fmt, got[0][:rows].cpu().numpy(), got[1][:rows].cpu().numpy())
     assert rep.ok(), (rep.summary(), rep.notes[:5])
 
 
@@ -559,7 +564,7 @@ def test_prepared_placement_is_ignored_where_no_such_gather_runs():
     for T, d, b in ((50, 2048, 128), (40, 8192, 8192), (30, 3072, 768)):
         x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_normal((T, d))))
         perm_t = torch.from_numpy(rng.permutation(d).astype(np.int32)).cuda()
-        junk = torch.full((4 * d + d // 4,), 0x7F, dtype=torch.uint8, device="cuda")
+        junk = torch.full((binding.load().perq_perm_prepared_bytes(d),), 0x7F, dtype=torch.uint8, device="cuda")
         plain = binding.perq_permute_rotate_quant(x, perm_t, b, "int4")
         got = binding.perq_permute_rotate_quant(x, perm_t, b, "int4", placement=junk)
         torch.cuda.synchronize()

@@ -9,6 +9,7 @@ import pytest
 
 from oracle import perq_oracle as orc
 from paper_2601_22347_amd import binding, synth
+import prepared_form
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -284,9 +285,10 @@ def test_prepared_placement_is_a_line_bijection_and_never_worse(d, b):
     rng = np.random.default_rng(d + b)
     perm = rng.permutation(d).astype(np.int32)
     table, before, after, reads = binding.perq_perm_prepare(perm, b)
-    assert table.dtype == np.uint8 and table.size == 4 * d + d // 4
+    tiles = (d + 4095) // 4096
+    assert table.dtype == np.uint8 and table.size == 4 * d + d // 4 + 2 * tiles * 8192
     G = d // 8
-    place, granule_of = binding.prepared_parts(table, d)
+    place, granule_of, lanes = binding.prepared_parts(table, d)
     granule_of = granule_of.astype(np.int64)
     assert np.array_equal(np.sort(granule_of), np.arange(G))                   # every slot takes one piece
     assert np.array_equal(granule_of // 8, np.arange(G) // 8)                  # inside the 128-byte lines of the row
@@ -294,6 +296,14 @@ def test_prepared_placement_is_a_line_bijection_and_never_worse(d, b):
     # a position's place: the slot of its channel's piece, and the channel's place inside the piece
     assert np.array_equal(place, slot_of[perm >> 3] * 8 + (perm & 7))
     assert binding.perq_perm_prepared_validate(table, perm)
+    # the operand offsets in lane order, rebuilt from the description of the form: both modes, every tile,
+    # the ragged end marked; and the whole form byte for byte
+    assert np.array_equal(lanes, prepared_form.lane_tables(perm, slot_of))
+    assert np.array_equal(table, prepared_form.assemble(perm, slot_of))
+    in_row = lanes[lanes != 0xFFFF]
+    assert in_row.size == 2 * d and in_row.max() < 2 * d and not (in_row & 1).any()
+    for mode in range(2):           # every channel of the row is read exactly once per mode
+        assert np.array_equal(np.sort(lanes[mode][lanes[mode] != 0xFFFF].astype(np.int64)), 2 * np.arange(d))
     # the count for the fixed layout is the one perq_perm_gather_cost reports; the table lowers it
     assert (before, reads) == binding.perq_perm_gather_cost(perm, b)
     assert after <= before and after < 0.8 * before                            # 3.2 - 3.5 -> about 2.3 passes per read
@@ -318,6 +328,8 @@ def test_prepared_placement_is_a_line_bijection_and_never_worse(d, b):
     assert not binding.perq_perm_prepared_validate(table, other)
     bad = table.copy(); bad[4 * d], bad[4 * d + 2] = bad[4 * d + 2], bad[4 * d]
     assert not binding.perq_perm_prepared_validate(bad, perm)
+    bad = table.copy(); bad[-2] ^= 2                       # one operand offset of the last table
+    assert not binding.perq_perm_prepared_validate(bad, perm)
 
 
 def test_prepare_on_regular_and_unsupported_shapes(lib):
@@ -326,14 +338,14 @@ def test_prepare_on_regular_and_unsupported_shapes(lib):
     table, before, after, reads = binding.perq_perm_prepare(ident, 128)
     assert after <= before and binding.perq_perm_prepared_validate(table, ident)
     perm = np.arange(2048, dtype=np.int32)
-    buf = np.zeros(2048 * 5, dtype=np.uint8)
+    buf = np.zeros(2048 * 5 + 16384, dtype=np.uint8)
     pp, pt = perm.ctypes.data_as(ctypes.c_void_p), buf.ctypes.data_as(ctypes.c_void_p)
     assert lib.perq_perm_prepare(pp, 2048, 128, pt, None, None, None) == binding.PERQ_ERR_UNSUPPORTED     # d < 4096
     assert lib.perq_perm_prepare(None, 4096, 128, pt, None, None, None) == binding.PERQ_ERR_INVALID_ARG
     assert lib.perq_perm_prepare(pp, 2048, 128, None, None, None, None) == binding.PERQ_ERR_INVALID_ARG
     perm[3] = 4
     assert lib.perq_perm_prepare(pp, 2048, 128, pt, None, None, None) == binding.PERQ_ERR_INVALID_ARG      # not a bijection
-    assert lib.perq_perm_prepared_bytes(14336) == 14336 * 4 + 14336 // 4 and lib.perq_perm_prepared_bytes(7) == 0
+    assert lib.perq_perm_prepared_bytes(14336) == 14336 * 4 + 14336 // 4 + 2 * 4 * 8192 and lib.perq_perm_prepared_bytes(7) == 0
     fake = ctypes.c_void_p(0x10000)
     odd = ctypes.c_void_p(0x10004)
     assert lib.perq_permute_rotate_quant_prepared(fake, 4, 4096, 4096, fake, odd, 128, 0, fake, fake, None) == binding.PERQ_ERR_UNSUPPORTED
