@@ -50,6 +50,12 @@ __device__ __forceinline__ void store_stream16(void* p, uint4 v) {
     __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
 }
 
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_stream8(void* p, uint32_t a, uint32_t b) {
+    const u32x2_t t = {a, b};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x2_t*>(p));
+}
+
 // Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for every
 // outstanding global load and store of the wave, which would expose the latency of loads issued
 // ahead of their use once per barrier.

@@ -138,11 +138,6 @@ __device__ __forceinline__ void lds_store16(void* p, uint32_t a, uint32_t b, uin
     const u32x4_t v = {a, b, c, d};
     asm volatile("ds_write_b128 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
 }
-__device__ __forceinline__ void lds_store8(void* p, uint32_t a, uint32_t b) {
-    typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-    const u32x2_t v = {a, b};
-    asm volatile("ds_write_b64 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
-}
 __device__ __forceinline__ void lds_store4(void* p, float v) {
     asm volatile("ds_write_b32 %0, %1" ::"v"(lds_addr(p)), "v"(v) : "memory");
 }
@@ -795,12 +790,18 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                     }
                 }
             }
-            // The wave's 2 KiB of codes take one trip through LDS so that each store instruction
-            // writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of short pieces
-            // at a pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
+            // Low-K modes: the wave's 2 KiB of codes take one trip through LDS so that each store
+            // instruction writes 1 KiB of consecutive bytes (lane l -> 16 bytes at 16 l) instead of short
+            // pieces at a pitch.  16-byte slot s sits at s ^ ((s >> 3) & 7).
+            // High-K modes: a lane's 16 codes of an accumulator tile are 8 consecutive bytes and the 32
+            // lanes of a half-wave hold 256 consecutive bytes, whole cache lines, so the codes are stored
+            // from the registers (four 8-byte stores instead of two 16-byte ones, and no wait for a
+            // round trip through an LDS queue that the other waves' operand reads keep long;
+            // d = 14336, b = 2048: 222 -> 215 us).
             if constexpr (!kHighK && OUT != OUT_MXFP4) PERQ_GATHER_STEPS(8, 9);
-            unsigned char* ob = out_stage + (uint32_t)wave * 2048u;
+            uint4 o0, o1;
             if constexpr (!kHighK) {
+                unsigned char* ob = out_stage + (uint32_t)wave * 2048u;
                 // Give lane (c,0) the whole of its sub-blocks q = 0, 1 and lane (c,1) the whole of
                 // q = 2, 3: the half-wave swap exchanges (q, h=1) of the low lanes' tiles with (q+2, h=0).
                 uint32_t out[2][4];
@@ -816,22 +817,19 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 const uint32_t s0 = (uint32_t)sbq(2 * h), s1 = (uint32_t)sbq(2 * h + 1);
                 lds_store16(ob + ((s0 ^ ((s0 >> 3) & 7u)) << 4), out[0][0], out[0][1], out[0][2], out[0][3]);
                 lds_store16(ob + ((s1 ^ ((s1 >> 3) & 7u)) << 4), out[1][0], out[1][1], out[1][2], out[1][3]);
-            } else {
-                // 16 codes = 8 bytes per accumulator tile, at byte hk_run(q) / 2 of the wave's block
-#pragma unroll
-                for (int q = 0; q < kQ; ++q) {
-                    const uint32_t off = (uint32_t)hk_run(q) >> 1;
-                    const uint32_t sl = off >> 4;
-                    lds_store8(ob + (((sl ^ ((sl >> 3) & 7u)) << 4) | (off & 8u)), pk[q][0], pk[q][1]);
-                }
+                const uint32_t r0 = (uint32_t)lane, r1 = 64u + (uint32_t)lane;
+                lds_load16x2(ob + ((r0 ^ ((r0 >> 3) & 7u)) << 4), ob + ((r1 ^ ((r1 >> 3) & 7u)) << 4), o0, o1);
             }
-            const uint32_t r0 = (uint32_t)lane, r1 = 64u + (uint32_t)lane;
-            uint4 o0, o1;
-            lds_load16x2(ob + ((r0 ^ ((r0 >> 3) & 7u)) << 4), ob + ((r1 ^ ((r1 >> 3) & 7u)) << 4), o0, o1);
             if (row_live) {
-                uint8_t* crow = p.codes + row * (int64_t)(d >> 1) + (tile_base >> 1) + lane * 16;
-                if (lane * 32 < tile_len) store_stream16(crow, o0);
-                if (2048 + lane * 32 < tile_len) store_stream16(crow + 1024, o1);
+                uint8_t* ctile = p.codes + row * (int64_t)(d >> 1) + (tile_base >> 1);
+                if constexpr (!kHighK) {
+                    if (lane * 32 < tile_len) store_stream16(ctile + lane * 16, o0);
+                    if (2048 + lane * 32 < tile_len) store_stream16(ctile + lane * 16 + 1024, o1);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < kQ; ++q)
+                        if (qvalid[q]) store_stream8(ctile + ((uint32_t)hk_run(q) >> 1), pk[q][0], pk[q][1]);
+                }
                 if constexpr (OUT == OUT_MXFP4) {
                     uint8_t* srow = static_cast<uint8_t*>(p.scales) + row * (int64_t)(d >> 5) + (tile_base >> 5);
                     if constexpr (!kHighK) {
