@@ -256,69 +256,84 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         // Accumulator tile (al', nt): outputs whose a lies in row tile al', columns 32 nt ..: the sum
         // over al of H[al][al'] * (Z_al H_MB), H = H_4 when the block spans the whole chunk,
         // I_2 (x) H_2 when it spans half of it, I_4 below.
-        f32x16_t acc[kTiles];
+        // The products of one output tile at a time, and the in-register stages of a tile while the
+        // matrix unit works on the next one: a wave issues in order, so the stages' instructions are
+        // placed between the products (one product keeps the unit busy for about as long as eight
+        // vector instructions take).
+        float v[kVals];
+        // accumulator j of tile (al', nt) in lane (c, h): row m = 8 (j >> 2) + 4 h + (j & 3) of the
+        // product, a = kTileA al' + kA0 m (+ c >> 4 when kA0 = 2); row bit q is a-bit q + kSh
+        const bool stage2 = STG >= 0 || kp > kSh + 2;
+        auto tile_stages = [&](int t) {
+            float* w = v + 16 * t;
+            auto pair_stage = [&](int bit_in_index) {
 #pragma unroll
-        for (int t = 0; t < kTiles; ++t) acc[t] = f32x16_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+                for (int i = 0; i < 16; ++i) {
+                    if ((i & bit_in_index) == 0) {
+                        const float s = w[i], u = w[i | bit_in_index];
+                        w[i] = s + u;
+                        w[i | bit_in_index] = s - u;
+                    }
+                }
+            };
+            if (STG >= 0 || kp > kSh + 0) pair_stage(1);       // row bit 0
+            if (STG >= 0 || kp > kSh + 1) pair_stage(2);       // row bit 1
+            if (STG >= 0 || kp > kSh + 3) pair_stage(4);       // row bit 3
+            if (STG >= 0 || kp > kSh + 4) pair_stage(8);       // row bit 4
+            // Row bit 2 separates the half-waves.  One half-wave swap per register pair (i, i+1) hands
+            // the low lanes both halves of register i and the high lanes both halves of register i+1;
+            // sum and difference stay there.  Afterwards the half-wave tells row bit 0 and the slot in
+            // the pair row bit 2.  Without this stage the same swap only re-sorts the values, so that
+            // the addresses below hold either way.
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(w[i]), __float_as_uint(w[i + 1]), false, false);
+                const float lo = __uint_as_float(sw[0]), hi = __uint_as_float(sw[1]);
+                w[i] = stage2 ? lo + hi : lo;
+                w[i + 1] = stage2 ? lo - hi : hi;
+            }
+        };
+        // Accumulator tile (al', nt): outputs whose a lies in row tile al', columns 32 nt ..: the sum
+        // over al of H[al][al'] * (Z_al H_MB), H = H_4 when the block spans the whole chunk,
+        // I_2 (x) H_2 when it spans half of it, I_4 below.
         // keep: those of the two tile bits that lie above the block (they must agree between input and output)
-        auto products = [&](auto keep_const) {
+        auto phase1 = [&](auto keep_const) {
             constexpr int keep = decltype(keep_const)::value;
 #pragma unroll
-            for (int al = 0; al < kAL; ++al) {
+            for (int t = 0; t < kTiles; ++t) {
+                const int ao = t / kNT, nt = t % kNT;
+                f32x16_t acc = f32x16_t{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int ao = 0; ao < kAL; ++ao) {
+                for (int al = 0; al < kAL; ++al) {
                     if (((al ^ ao) & keep) == 0) {
                         const bool minus = (__builtin_popcount(al & ao & ~keep) & 1) != 0;
 #pragma unroll
-                        for (int nt = 0; nt < kNT; ++nt)
+                        for (int ks = 0; ks < kKS; ++ks) {
+                            if constexpr (kAL > 1)
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[al][ks], minus ? bneg[nt][ks] : bpos[nt][ks], acc, 0, 0, 0);
+                            else
+                                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[al][ks], bpos[nt][ks], acc, 0, 0, 0);
+                        }
+                    }
+                }
+                if (t > 0) tile_stages(t - 1);
 #pragma unroll
-                            for (int ks = 0; ks < kKS; ++ks) {
-                                if constexpr (kAL > 1)
-                                    acc[ao * kNT + nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                                        afrag[al][ks], minus ? bneg[nt][ks] : bpos[nt][ks], acc[ao * kNT + nt], 0, 0, 0);
-                                else
-                                    acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afrag[al][ks], bpos[nt][ks], acc[nt], 0, 0, 0);
-                            }
+                for (int j = 0; j < 16; ++j) v[t * 16 + j] = acc[j];
+                // one product, then a share of the stage's instructions, until the tile's products are out
+                constexpr int kProducts = kAL > 1 ? (keep == 0 ? kAL : (keep == 3 ? 1 : 2)) * kKS : kKS;
+                if (t > 0) {
+#pragma unroll
+                    for (int i = 0; i < kProducts; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                       // one matrix instruction
+                        __builtin_amdgcn_sched_group_barrier(0x002, 96 / kProducts, 0);          // vector instructions
                     }
                 }
             }
+            tile_stages(kTiles - 1);
         };
-        if (kAL == 1 || STG >= 0) products(std::integral_constant<int, 0>{});
-        else if (kp == kChunkBits - 1) products(std::integral_constant<int, 2>{});
-        else products(std::integral_constant<int, 3>{});
-        float v[kVals];
-#pragma unroll
-        for (int t = 0; t < kTiles; ++t)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) v[t * 16 + j] = acc[t][j];
-        // accumulator j of tile (al', nt) in lane (c, h): row m = 8 (j >> 2) + 4 h + (j & 3) of the
-        // product, a = kTileA al' + kA0 m (+ c >> 4 when kA0 = 2); row bit q is a-bit q + kSh
-        auto pair_stage = [&](int bit_in_index) {
-#pragma unroll
-            for (int i = 0; i < kVals; ++i) {
-                if ((i & bit_in_index) == 0) {
-                    const float s = v[i], t = v[i | bit_in_index];
-                    v[i] = s + t;
-                    v[i | bit_in_index] = s - t;
-                }
-            }
-        };
-        if (STG >= 0 || kp > kSh + 0) pair_stage(1);       // row bit 0
-        if (STG >= 0 || kp > kSh + 1) pair_stage(2);       // row bit 1
-        if (STG >= 0 || kp > kSh + 3) pair_stage(4);       // row bit 3
-        if (STG >= 0 || kp > kSh + 4) pair_stage(8);       // row bit 4
-        // Row bit 2 separates the half-waves.  One half-wave swap per register pair (i, i+1) hands
-        // the low lanes both halves of register i and the high lanes both halves of register i+1;
-        // sum and difference stay there.  Afterwards the half-wave tells row bit 0 and the slot in
-        // the pair row bit 2.  Without this stage the same swap only re-sorts the values, so that
-        // the addresses below hold either way.
-        const bool stage2 = STG >= 0 || kp > kSh + 2;
-#pragma unroll
-        for (int i = 0; i < kVals; i += 2) {
-            auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[i]), __float_as_uint(v[i + 1]), false, false);
-            const float lo = __uint_as_float(sw[0]), hi = __uint_as_float(sw[1]);
-            v[i] = stage2 ? lo + hi : lo;
-            v[i + 1] = stage2 ? lo - hi : hi;
-        }
+        if (kAL == 1 || STG >= 0) phase1(std::integral_constant<int, 0>{});
+        else if (kp == kChunkBits - 1) phase1(std::integral_constant<int, 2>{});
+        else phase1(std::integral_constant<int, 3>{});
         if constexpr (PERM) workgroup_barrier_lds();   // every wave has gathered its operands: the chunks may be overwritten
         {
             const int rl = c & kColMask;                // r' inside a column tile
@@ -528,24 +543,34 @@ int base_entry(int kind, int r, int c) {
     else return hadamard_base_entry(MB, kind, r, c);
 }
 
-template <int OUT, bool PERM, int MB, int NCH>
-hipError_t launch_stg(const ApplyParams& p, const Npo2Geom<MB>& g, dim3 grid, hipStream_t stream) {
-    const int stg = g.kp - npo2_chunk_bits<MB>();
-    const dim3 block(64 * npo2_waves(NCH));
-    if (stg < 0) {
-        hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, -1>), grid, block, 0, stream, p, g);
-    } else if (stg == 0) {
-        hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 0>), grid, block, 0, stream, p, g);
-    } else if (stg == 1 && NCH >= 2) {
-        if constexpr (NCH >= 2) hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 1>), grid, block, 0, stream, p, g);
-    } else if (stg == 2 && NCH >= 4) {
-        if constexpr (NCH >= 4) hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 2>), grid, block, 0, stream, p, g);
-    } else if (stg == 3 && NCH >= 8) {
-        if constexpr (NCH >= 8) hipLaunchKernelGGL((npo2_kernel<OUT, PERM, MB, NCH, 3>), grid, block, 0, stream, p, g);
-    } else {
-        return hipErrorInvalidValue;
-    }
+// A persistent grid: as many workgroups as stay resident (two per CU by the size of the fp32 exchange
+// area for the bases 28 and 32, three for the smaller chunks of 12 and 76 where the registers allow).
+template <class Kern, int MB>
+hipError_t launch_resident(Kern kern, int threads, const ApplyParams& p, const Npo2Geom<MB>& g, int64_t n_units, hipStream_t stream) {
+    int per_cu = 0;
+    const hipError_t e = resident_blocks(reinterpret_cast<const void*>(kern), threads, 0, &per_cu);
+    if (e != hipSuccess) return e;
+    const int64_t max_grid = (int64_t)per_cu * launch_info().num_cus;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_units < max_grid ? n_units : max_grid)), dim3(threads), 0, stream, p, g);
     return hipGetLastError();
+}
+
+template <int OUT, bool PERM, int MB, int NCH>
+hipError_t launch_stg(const ApplyParams& p, const Npo2Geom<MB>& g, int64_t n_units, hipStream_t stream) {
+    const int stg = g.kp - npo2_chunk_bits<MB>();
+    constexpr int threads = 64 * npo2_waves(NCH);
+    if (stg < 0) return launch_resident(npo2_kernel<OUT, PERM, MB, NCH, -1>, threads, p, g, n_units, stream);
+    if (stg == 0) return launch_resident(npo2_kernel<OUT, PERM, MB, NCH, 0>, threads, p, g, n_units, stream);
+    if constexpr (NCH >= 2) {
+        if (stg == 1) return launch_resident(npo2_kernel<OUT, PERM, MB, NCH, 1>, threads, p, g, n_units, stream);
+    }
+    if constexpr (NCH >= 4) {
+        if (stg == 2) return launch_resident(npo2_kernel<OUT, PERM, MB, NCH, 2>, threads, p, g, n_units, stream);
+    }
+    if constexpr (NCH >= 8) {
+        if (stg == 3) return launch_resident(npo2_kernel<OUT, PERM, MB, NCH, 3>, threads, p, g, n_units, stream);
+    }
+    return hipErrorInvalidValue;
 }
 
 // Rows of eight chunks (d = 28672, 32768) exist for the bases 28 and 32 only.
@@ -553,22 +578,22 @@ template <int MB>
 constexpr bool npo2_has_eight() { return MB == 28 || MB == 32; }
 
 template <int OUT, bool PERM, int MB>
-hipError_t launch_nch(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, dim3 grid, hipStream_t stream) {
+hipError_t launch_nch(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, int64_t n_units, hipStream_t stream) {
     switch (nch) {
-        case 1: return launch_stg<OUT, PERM, MB, 1>(p, g, grid, stream);
-        case 2: return launch_stg<OUT, PERM, MB, 2>(p, g, grid, stream);
-        case 4: return launch_stg<OUT, PERM, MB, 4>(p, g, grid, stream);
+        case 1: return launch_stg<OUT, PERM, MB, 1>(p, g, n_units, stream);
+        case 2: return launch_stg<OUT, PERM, MB, 2>(p, g, n_units, stream);
+        case 4: return launch_stg<OUT, PERM, MB, 4>(p, g, n_units, stream);
         case 8:
-            if constexpr (npo2_has_eight<MB>()) return launch_stg<OUT, PERM, MB, 8>(p, g, grid, stream);
+            if constexpr (npo2_has_eight<MB>()) return launch_stg<OUT, PERM, MB, 8>(p, g, n_units, stream);
             return hipErrorInvalidValue;
         default: return hipErrorInvalidValue;
     }
 }
 
 template <int OUT, int MB>
-hipError_t launch_perm(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, dim3 grid, hipStream_t stream) {
-    return p.perm != nullptr ? launch_nch<OUT, true, MB>(p, g, nch, grid, stream)
-                             : launch_nch<OUT, false, MB>(p, g, nch, grid, stream);
+hipError_t launch_perm(const ApplyParams& p, const Npo2Geom<MB>& g, int nch, int64_t n_units, hipStream_t stream) {
+    return p.perm != nullptr ? launch_nch<OUT, true, MB>(p, g, nch, n_units, stream)
+                             : launch_nch<OUT, false, MB>(p, g, nch, n_units, stream);
 }
 
 // The caller has checked npo2_supports(p) and that b / MB is a power of two.
@@ -596,14 +621,12 @@ hipError_t launch_npo2_base_impl(const ApplyParams& p, int out_kind, hipStream_t
     const int nch = p.d / npo2_chunk_pos<MB>();
     const int64_t rows_per_unit = npo2_waves(nch) / nch;
     const int64_t n_units = (p.T + rows_per_unit - 1) / rows_per_unit;
-    const int64_t max_grid = (nch == 8 ? 1 : 2) * (int64_t)launch_info().num_cus;
-    const dim3 grid((unsigned)(n_units < max_grid ? n_units : max_grid));
     switch (out_kind) {
-        case OUT_INT4: return launch_perm<OUT_INT4, MB>(p, g, nch, grid, stream);
-        case OUT_MXFP4: return launch_perm<OUT_MXFP4, MB>(p, g, nch, grid, stream);
-        case OUT_INT4_ASYM: return launch_perm<OUT_INT4_ASYM, MB>(p, g, nch, grid, stream);
-        case OUT_FP4_TOKEN: return launch_perm<OUT_FP4_TOKEN, MB>(p, g, nch, grid, stream);
-        case OUT_F32: return launch_perm<OUT_F32, MB>(p, g, nch, grid, stream);
+        case OUT_INT4: return launch_perm<OUT_INT4, MB>(p, g, nch, n_units, stream);
+        case OUT_MXFP4: return launch_perm<OUT_MXFP4, MB>(p, g, nch, n_units, stream);
+        case OUT_INT4_ASYM: return launch_perm<OUT_INT4_ASYM, MB>(p, g, nch, n_units, stream);
+        case OUT_FP4_TOKEN: return launch_perm<OUT_FP4_TOKEN, MB>(p, g, nch, n_units, stream);
+        case OUT_F32: return launch_perm<OUT_F32, MB>(p, g, nch, n_units, stream);
         default: return hipErrorInvalidValue;
     }
 }
