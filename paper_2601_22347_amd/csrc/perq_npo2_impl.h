@@ -457,9 +457,15 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
             if constexpr (OUT == OUT_FP4_TOKEN) inv = hi > 0.0f ? p.fp4_qmax / hi : 0.0f;
             if constexpr (OUT == OUT_INT4_ASYM) qa = int4_asym_row(lo, hi);
         }
+        // Rows of four chunks with 4-bit codes: a thread's four dwords of one pass belong to four chunks,
+        // those of the four threads of a quad to four consecutive runs of each.  A 4 x 4 transposition
+        // inside the quad (two exchange steps) hands thread q the 16 consecutive bytes of chunk q, so a
+        // pass ends in one 16-byte store per thread instead of four 4-byte ones.
+        constexpr bool kQuadStore = NCH == 4 && OUT != OUT_F32 && kRun == 8 && kGroups % 4 == 0;
 #pragma unroll
         for (int it = 0; it < kIts; ++it) {
             const int gI = t_row + kThreadsPerRow * it;
+            uint32_t wq[kQuadStore ? 4 : 1];
             if (gI < kGroups && row_live) {
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
@@ -504,10 +510,31 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                                 }
                             }
                         }
-                        uint8_t* dst = p.codes + row * (int64_t)(d >> 1) + (pos >> 1);
-                        if constexpr (kRun == 16) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
-                        else *reinterpret_cast<uint32_t*>(dst) = w[0];
+                        if constexpr (kQuadStore) {
+                            wq[ch] = w[0];
+                        } else {
+                            uint8_t* dst = p.codes + row * (int64_t)(d >> 1) + (pos >> 1);
+                            if constexpr (kRun == 16) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+                            else *reinterpret_cast<uint32_t*>(dst) = w[0];
+                        }
                     }
+                }
+                if constexpr (kQuadStore) {
+                    // (the threads of a quad are live together: kGroups is a multiple of 4 and so is a row's first thread)
+                    const int q = lane & 3;
+                    auto exchange = [&](uint32_t& keep_lo, uint32_t& keep_hi, bool upper, auto ctrl) {
+                        // the thread with the lower number keeps lo and receives the partner's lo in hi's place
+                        const uint32_t give = upper ? keep_lo : keep_hi;
+                        const uint32_t got = (uint32_t)__builtin_amdgcn_update_dpp((int)give, (int)give, decltype(ctrl)::value, 0xF, 0xF, false);
+                        if (upper) keep_lo = got; else keep_hi = got;
+                    };
+                    exchange(wq[0], wq[1], (q & 1) != 0, std::integral_constant<int, 0xB1>{});     // quad_perm [1,0,3,2]
+                    exchange(wq[2], wq[3], (q & 1) != 0, std::integral_constant<int, 0xB1>{});
+                    exchange(wq[0], wq[2], (q & 2) != 0, std::integral_constant<int, 0x4E>{});     // quad_perm [2,3,0,1]
+                    exchange(wq[1], wq[3], (q & 2) != 0, std::integral_constant<int, 0x4E>{});
+                    // thread q now holds chunk q's dwords of runs gI - q .. gI - q + 3
+                    uint8_t* dst = p.codes + row * (int64_t)(d >> 1) + ((q * kChunkPos + kRun * (gI - q)) >> 1);
+                    store_stream16(dst, make_uint4(wq[0], wq[1], wq[2], wq[3]));
                 }
             }
         }
