@@ -55,5 +55,48 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def check_table_reads() -> int:
+    """Compiler check for the prepared-form reads of the matrix-core kernel (perq_mfma.hip).
+
+    The kernel issues eight 16-byte loads as instructions, waits for them by count and only then hands
+    the eight register tuples back to the compiler (a comment line in the assembly lists them).  Were the
+    compiler to move one of the tuples in between, it would copy registers whose data have not arrived.
+    This compiles the file to assembly (about three minutes) and checks, for every kernel variant, that
+    the tuples handed back are the ones the loads were given.  Returns the number of variants checked;
+    raises on a mismatch.  Run after a compiler upgrade: `python -m paper_2601_22347_amd.build --check-table-reads`."""
+    import re
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        asm = os.path.join(tmp, "perq_mfma.s")
+        flags = [f for f in HIP_FLAGS if f != "-fPIC"]
+        cmd = [hipcc(), *flags, "--offload-device-only", "-S", "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+               "-x", "hip", os.path.join(CSRC, "perq_mfma.hip"), "-o", asm]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed:\n{res.stdout}")
+        text = open(asm).read()
+    checked = 0
+    for m in re.finditer(r"\n(_ZN4perq\S*mfma_kernel\S*): +; @", text):
+        body = text[m.end():text.index("s_endpgm", m.end())].split("\n")
+        handed = [l for l in body if "table reads have landed in" in l]
+        if not handed:
+            continue
+        loads = [re.search(r"global_load_dwordx4 (v\[\d+:\d+\])", body[i + 1]).group(1)
+                 for i, l in enumerate(body[:-1])
+                 if "#ASMSTART" in l and re.search(r"global_load_dwordx4 v\[\d+:\d+\], v\[\d+:\d+\], off\s*$", body[i + 1])]
+        for l in handed:
+            regs = sorted(re.findall(r"v\[\d+:\d+\]", l))
+            if len(loads) % 8 != 0 or regs not in (sorted(loads[:8]), sorted(loads[-8:])):
+                raise RuntimeError(f"{m.group(1)}: loads into {loads}, handed back {regs}")
+            checked += 1
+    if checked == 0:
+        raise RuntimeError("no kernel variant with the prepared-form reads found")
+    return checked
+
+
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    if "--check-table-reads" in sys.argv:
+        print(check_table_reads(), "kernel variants checked")
+    else:
+        print(build(verbose=True))

@@ -947,7 +947,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
                 default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
             }
 #undef PERQ_TABLE_WAIT
-            asm volatile("; table reads have landed"
+            asm volatile("; table reads have landed in %0 %1 %2 %3 %4 %5 %6 %7"
                          : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3]), "+v"(t[4]), "+v"(t[5]), "+v"(t[6]), "+v"(t[7])::"memory");
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
