@@ -660,6 +660,40 @@ def test_run_time_schedule_on_two_streams_and_in_a_graph():
         assert torch.equal(eager[0], ref[0])
 
 
+def test_prepared_form_and_chunked_kernel_in_a_graph():
+    """A captured launch with a prepared form (its table reads are waited for by count) and a captured
+    launch of the chunked kernel (its grid comes from an occupancy query) replay to the eager result,
+    with eager work between the replays."""
+    torch = _torch()
+    rng = np.random.default_rng(321)
+    st = torch.cuda.Stream()
+    for T, d, b, fmt, prepared in ((700, 8192, 64, "int4", True), (300, 14336, 2048, "int4_asym", True),
+                                   (500, 12288, 12288, "int4", False), (260, 16384, 8192, "mxfp4", False)):
+        print(f"[case] graph T={T} d={d} b={b} fmt={fmt} prepared={prepared}", flush=True)
+        x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d))))
+        perm_np = rng.permutation(d).astype(np.int32) if prepared else None
+        perm = torch.from_numpy(perm_np).cuda() if prepared else None
+        form = binding.placement_to_device(binding.perq_perm_prepare(perm_np, b)[0]) if prepared else None
+        ref = binding.perq_permute_rotate_quant(x, perm, b, fmt)
+        codes, scales = binding.alloc_outputs(T, d, fmt, x.device)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(st):
+            binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales, stream=st, placement=form)   # warm
+            st.synchronize()
+            with torch.cuda.graph(g, stream=st):
+                binding.perq_permute_rotate_quant(x, perm, b, fmt, codes=codes, scales=scales,
+                                                  stream=torch.cuda.current_stream(), placement=form)
+        for rep in range(3):
+            codes.fill_(0x55); scales.fill_(3)
+            eager = binding.perq_permute_rotate_quant(x, perm, b, fmt, placement=form)
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(codes, ref[0]) and torch.equal(scales, ref[1]), f"replay {rep}"
+            assert torch.equal(eager[0], ref[0]) and torch.equal(eager[1], ref[1])
+
+
 def test_run_time_schedule_more_streams_than_counter_sets_and_reset():
     """The 65th stream of a device gets no counter set: its launches take the fixed split.  All
     streams launch at once; every result equals the reference.  perq_reset_schedule leaves the
