@@ -558,6 +558,29 @@ def test_prepared_placement_gives_the_plain_call_bit_for_bit(T, d, b, fmt):
     assert rep.ok(), (rep.summary(), rep.notes[:5])
 
 
+def test_prepared_form_on_seeded_random_shapes():
+    """Forty seeded shapes (row widths in steps of 512 from 4096 to 32768, every block size that divides
+    them, every format, 1 to 300 rows): the prepared call equals the plain call bit for bit."""
+    torch = _torch()
+    rng = np.random.default_rng(20260)
+    fmts = ["int4", "mxfp4", "int4_asym", "fp4_token"]
+    for case in range(40):
+        d = 512 * int(rng.integers(8, 65))
+        bs = [b for b in (16, 32, 64, 128, 256, 512, 1024, 2048, 4096) if d % b == 0]
+        b = int(bs[rng.integers(len(bs))])
+        T = int(rng.integers(1, 301))
+        fmt = fmts[case % 4]
+        print(f"[case] prepared form, seeded shape {case}: T={T} d={d} b={b} fmt={fmt}", flush=True)
+        x = binding.bits_to_device(synth.f64_to_bf16_bits(rng.standard_t(4, size=(T, d))))
+        perm = rng.permutation(d).astype(np.int32)
+        perm_t = torch.from_numpy(perm).cuda()
+        form = binding.placement_to_device(binding.perq_perm_prepare(perm, b)[0])
+        plain = binding.perq_permute_rotate_quant(x, perm_t, b, fmt)
+        got = binding.perq_permute_rotate_quant(x, perm_t, b, fmt, placement=form)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], plain[0]) and torch.equal(got[1], plain[1]), (T, d, b, fmt)
+
+
 def test_prepared_placement_is_ignored_where_no_such_gather_runs():
     torch = _torch()
     rng = np.random.default_rng(77)
