@@ -16,8 +16,10 @@
 //   2. The rest of the Sylvester factor inside a wave's chunk: the a-bits held in the accumulator
 //      index are in-register butterflies, the bit that separates the half-waves is one swap stage.
 //      Bits above the chunk join different waves' chunks: every wave leaves its chunk in LDS as
-//      fp32 in position order, and after a barrier each thread collects 8 consecutive positions
-//      of every chunk of its row and finishes the remaining one to three stages in registers.
+//      fp32 in position order (for the bases 28 and 32 one half of it at a time, so that the exchange
+//      area is no larger than the raw rows and three workgroups stay resident), and after a barrier
+//      each thread collects 8 consecutive positions of every chunk of its row and finishes the
+//      remaining one to three stages in registers.
 //   3. In that layout (8 consecutive outputs per thread and chunk: one dword of codes) the row
 //      statistics, the rounding and the nibble packing are those of the other kernels.
 //
@@ -25,7 +27,8 @@
 // rows of 8 chunks (d = 28672 and 32768 for the bases 28 and 32) take workgroups of eight waves.
 // The raw rows go global -> registers (issued one iteration ahead) -> LDS; each chunk's bf16 data
 // lie at the start of the fp32 area of the same chunk; the owning wave puts them there and, without
-// a gather, is the only one to read them before it overwrites them: two barriers per row.
+// a gather, is the only one to read them before it overwrites them: two barriers per row (four
+// where the chunks go through LDS in two halves).
 #pragma once
 #include "perq_base.h"
 #include "perq_device.h"
@@ -93,7 +96,19 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     constexpr int kNpo2Chunks = npo2_waves(NCH);
     constexpr int kRows = kNpo2Chunks / NCH;
     constexpr int kThreadsPerRow = 64 * NCH;
-    constexpr int kIts = (kGroups + kThreadsPerRow - 1) / kThreadsPerRow;
+    // The chunks go through LDS in kRounds parts (a part = the row tiles 0, 1 or 2, 3 of every chunk, a
+    // contiguous half of its positions): the exchange area holds one part of every chunk, which is
+    // also the size of a chunk's raw bf16 data, and a third workgroup fits beside two
+    // (d = b = 14336: 275 -> 262 us).
+    // (one part where four whole chunks already leave room for three workgroups, the base 12: the two
+    //  extra barriers per row cost 1 % there; and for rows of eight chunks, whose workgroups of eight
+    //  waves are alone on a CU by their registers and would idle half their threads in every part)
+    constexpr int kRounds = (kAL == 4 && NCH <= 4 && 4 * kChunkPos * 4 > 160 * 1024 / 3) ? 2 : 1;
+    constexpr int kAreaPos = kChunkPos / kRounds;         // positions of a chunk in LDS at a time
+    constexpr int kGroupsR = kGroups / kRounds;           // runs per chunk and part
+    constexpr int kItsR = (kGroupsR + kThreadsPerRow - 1) / kThreadsPerRow;
+    constexpr int kIts = kRounds * kItsR;
+    static_assert(kGroups % kRounds == 0 && kGroupsR % 4 == 0, "a part holds whole 32-groups and whole quads of runs");
     // (a run of 8 is one dword of codes; where runs of 16 would leave 12 .. 40 % of the lanes of every
     //  wave idle in the last pass, whole waves skip it with runs of 8 instead)
     static_assert(kGroups % (32 / kRun) == 0 && kChunkPos % 32 == 0, "a 32-group is two or four neighbouring threads' runs");
@@ -101,7 +116,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     // 16-byte piece q of row a is kept at piece q ^ ((a >> 2) & 3) of the row instead (raw data only).
     constexpr bool kSwz = MB == 32;
 
-    __shared__ __attribute__((aligned(16))) float ex[kNpo2Chunks * kChunkPos];
+    __shared__ __attribute__((aligned(16))) float ex[kNpo2Chunks * kAreaPos];
     __shared__ float red[2][8];
 
     const int tid = threadIdx.x;
@@ -178,7 +193,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
                         const int ch = p.perm[pos];
                         const uint32_t cl = (uint32_t)(ch % kChunkPos);
                         // (in units of two bytes: eight chunks of fp32 pass 64 KiB)
-                        const uint32_t off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kChunkPos * 2) +
+                        const uint32_t off = (uint32_t)(ch / kChunkPos) * (uint32_t)(kAreaPos * 2) +
                                              (kSwz ? ((cl >> 5) * 4u + (((cl >> 3) & 3u) ^ ((cl >> 7) & 3u))) * 8u + (cl & 7u) : cl);
                         pair |= off << (16 * s);
                     }
@@ -194,7 +209,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     auto piece_live = [&](int i) { return kPreExact || i + 1 < kPre || lane + 64 * i < kChunkGranules; };
     const uint32_t g_base = (uint32_t)my_row * (uint32_t)(p.ldx * 2) + (uint32_t)my_chunk * (uint32_t)(kChunkPos * 2) + 16u * (uint32_t)lane;
     // (swizzled: piece lane + 64 i belongs to row (lane >> 2) + 16 i, whose bits 2, 3 are those of lane >> 4)
-    unsigned char* const l_base = ex_bytes + wave * (kChunkPos * 4) +
+    unsigned char* const l_base = ex_bytes + wave * (kAreaPos * 4) +
                                   16 * (kSwz ? ((lane & ~3) | ((lane & 3) ^ ((lane >> 4) & 3))) : lane);
 
     auto issue_loads = [&](uint4 (&pre)[kPre], int64_t unit) {
@@ -221,8 +236,8 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
     auto body = [&](int64_t unit) {
         if constexpr (PERM) workgroup_barrier_lds();               // the gather reads other waves' chunks too
         // ---- phase 1: base product and the in-wave stages on one chunk -------------------------
-        const unsigned char* stage = ex_bytes + wave * (kChunkPos * 4);
-        const unsigned char* row_stage = ex_bytes + my_row * NCH * (kChunkPos * 4);
+        const unsigned char* stage = ex_bytes + wave * (kAreaPos * 4);
+        const unsigned char* row_stage = ex_bytes + my_row * NCH * (kAreaPos * 4);
         bf16x8_t afrag[kAL][kKS];
 #pragma unroll
         for (int al = 0; al < kAL; ++al) {
@@ -334,55 +349,63 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         if (kAL == 1 || STG >= 0) phase1(std::integral_constant<int, 0>{});
         else if (kp == kChunkBits - 1) phase1(std::integral_constant<int, 2>{});
         else phase1(std::integral_constant<int, 3>{});
-        if constexpr (PERM) workgroup_barrier_lds();   // every wave has gathered its operands: the chunks may be overwritten
-        {
-            const int rl = c & kColMask;                // r' inside a column tile
-            float* dst = ex + wave * kChunkPos + (kA0 * h + (kA0 == 2 ? (c >> 4) : 0)) * MB + rl;
-#pragma unroll
-            for (int ao = 0; ao < kAL; ++ao)
-#pragma unroll
-                for (int nt = 0; nt < kNT; ++nt) {
-                    if (32 * nt + rl < MB) {
-#pragma unroll
-                        for (int j = 0; j < 16; ++j)
-                            dst[(kTileA * ao + kA0 * (8 * (j >> 2) + 4 * (j & 1) + (j & 2))) * MB + 32 * nt] =
-                                v[(ao * kNT + nt) * 16 + j];
-                    }
-                }
-        }
-        workgroup_barrier_lds();                                   // all chunks of all rows are in LDS
-
-        // ---- phase 2: runs of kRun = 8 consecutive positions of every chunk of the row per thread ---
+        // ---- the chunks through LDS, a part at a time; phase 2: runs of kRun = 8 consecutive positions
+        //      of every chunk of the row per thread ---------------------------------------------------
         const int t_row = tid - my_row * kThreadsPerRow;
         const int64_t row = unit * kRows + my_row;
         const bool row_live = row < p.T;
+        // pass `it` of a thread: run gI of every chunk (run_live: the thread has one in this pass)
+        auto run_live = [&](int it) { return t_row + kThreadsPerRow * (it % kItsR) < kGroupsR; };
+        auto run_of = [&](int it) { return (it / kItsR) * kGroupsR + t_row + kThreadsPerRow * (it % kItsR); };
         float f[kIts][NCH][kRun];
 #pragma unroll
-        for (int it = 0; it < kIts; ++it) {
-            const int gI = t_row + kThreadsPerRow * it;
-            const bool live = gI < kGroups;
+        for (int r = 0; r < kRounds; ++r) {
+            // r = 0: every wave has gathered its operands (the raw chunks may be overwritten);
+            // r = 1: every thread has read its runs of the first part
+            if (PERM || r > 0) workgroup_barrier_lds();
+            {
+                const int rl = c & kColMask;                // r' inside a column tile
+                float* dst = ex + wave * kAreaPos + (kA0 * h + (kA0 == 2 ? (c >> 4) : 0)) * MB + rl;
 #pragma unroll
-            for (int ch = 0; ch < NCH; ++ch) {
-                const float4* src = reinterpret_cast<const float4*>(ex + (my_row * NCH + ch) * kChunkPos + kRun * (live ? gI : 0));
+                for (int ao = r * (kAL / kRounds); ao < (r + 1) * (kAL / kRounds); ++ao)
 #pragma unroll
-                for (int q = 0; q < kRun / 4; ++q) {
-                    const float4 t4 = src[q];
-                    f[it][ch][4 * q] = t4.x; f[it][ch][4 * q + 1] = t4.y;
-                    f[it][ch][4 * q + 2] = t4.z; f[it][ch][4 * q + 3] = t4.w;
-                }
+                    for (int nt = 0; nt < kNT; ++nt) {
+                        if (32 * nt + rl < MB) {
+#pragma unroll
+                            for (int j = 0; j < 16; ++j)
+                                dst[(kTileA * (ao - r * (kAL / kRounds)) + kA0 * (8 * (j >> 2) + 4 * (j & 1) + (j & 2))) * MB + 32 * nt] =
+                                    v[(ao * kNT + nt) * 16 + j];
+                        }
+                    }
             }
-            // stages across chunks: bit s of the chunk index, s < STG
+            workgroup_barrier_lds();                                   // this part of all chunks of all rows is in LDS
 #pragma unroll
-            for (int sb = 0; sb < 3; ++sb) {
-                if (sb < STG && (2 << sb) <= NCH) {
+            for (int it = r * kItsR; it < (r + 1) * kItsR; ++it) {
+                const int gl = t_row + kThreadsPerRow * (it - r * kItsR);     // run inside the part
+                const bool live = gl < kGroupsR;
 #pragma unroll
-                    for (int ch = 0; ch < NCH; ++ch) {
-                        if ((ch & (1 << sb)) == 0) {
+                for (int ch = 0; ch < NCH; ++ch) {
+                    const float4* src = reinterpret_cast<const float4*>(ex + (my_row * NCH + ch) * kAreaPos + kRun * (live ? gl : 0));
 #pragma unroll
-                            for (int e = 0; e < kRun; ++e) {
-                                const float s = f[it][ch][e], t = f[it][ch | (1 << sb)][e];
-                                f[it][ch][e] = s + t;
-                                f[it][ch | (1 << sb)][e] = s - t;
+                    for (int q = 0; q < kRun / 4; ++q) {
+                        const float4 t4 = src[q];
+                        f[it][ch][4 * q] = t4.x; f[it][ch][4 * q + 1] = t4.y;
+                        f[it][ch][4 * q + 2] = t4.z; f[it][ch][4 * q + 3] = t4.w;
+                    }
+                }
+                // stages across chunks: bit s of the chunk index, s < STG
+#pragma unroll
+                for (int sb = 0; sb < 3; ++sb) {
+                    if (sb < STG && (2 << sb) <= NCH) {
+#pragma unroll
+                        for (int ch = 0; ch < NCH; ++ch) {
+                            if ((ch & (1 << sb)) == 0) {
+#pragma unroll
+                                for (int e = 0; e < kRun; ++e) {
+                                    const float s = f[it][ch][e], t = f[it][ch | (1 << sb)][e];
+                                    f[it][ch][e] = s + t;
+                                    f[it][ch | (1 << sb)][e] = s - t;
+                                }
                             }
                         }
                     }
@@ -398,7 +421,7 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
             if constexpr (OUT == OUT_INT4_ASYM) { m[0] = -3.0e38f; m[1] = -3.0e38f; }
 #pragma unroll
             for (int it = 0; it < kIts; ++it) {
-                if (t_row + kThreadsPerRow * it < kGroups) {
+                if (run_live(it)) {
 #pragma unroll
                     for (int ch = 0; ch < NCH; ++ch)
 #pragma unroll
@@ -461,12 +484,12 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         // those of the four threads of a quad to four consecutive runs of each.  A 4 x 4 transposition
         // inside the quad (two exchange steps) hands thread q the 16 consecutive bytes of chunk q, so a
         // pass ends in one 16-byte store per thread instead of four 4-byte ones.
-        constexpr bool kQuadStore = NCH == 4 && OUT != OUT_F32 && kRun == 8 && kGroups % 4 == 0;
+        constexpr bool kQuadStore = NCH == 4 && OUT != OUT_F32 && kRun == 8;
 #pragma unroll
         for (int it = 0; it < kIts; ++it) {
-            const int gI = t_row + kThreadsPerRow * it;
+            const int gI = run_of(it);
             uint32_t wq[kQuadStore ? 4 : 1];
-            if (gI < kGroups && row_live) {
+            if (run_live(it) && row_live) {
 #pragma unroll
                 for (int ch = 0; ch < NCH; ++ch) {
                     const int pos = ch * kChunkPos + kRun * gI;
