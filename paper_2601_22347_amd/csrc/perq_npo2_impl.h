@@ -216,10 +216,16 @@ npo2_kernel(const ApplyParams p, const Npo2Geom<MB> g) {
         // the unit's first row as a scalar base address; rows past the end are read as zeros
         const bool live = unit < n_units && unit * kRows + my_row < p.T;
         const unsigned char* base = reinterpret_cast<const unsigned char*>(p.x) + unit * kRows * p.ldx * 2 + g_base;
+        // (one test per unit, not a cleared register set per load)
+        if (live) {
 #pragma unroll
-        for (int i = 0; i < kPre; ++i) {
-            pre[i] = make_uint4(0, 0, 0, 0);
-            if (live && piece_live(i)) pre[i] = load_stream16(base + 1024 * i);
+            for (int i = 0; i < kPre; ++i) {
+                if (piece_live(i)) pre[i] = load_stream16(base + 1024 * i);
+                else pre[i] = make_uint4(0, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kPre; ++i) pre[i] = make_uint4(0, 0, 0, 0);
         }
     };
     auto stage_rows = [&](const uint4 (&pre)[kPre]) {
