@@ -311,6 +311,25 @@ def main() -> int:
                    "single_buffer_set_note": "same call on one input/output set (%.0f MB; cache resident if well under "
                                              "256 MB)" % (per_set / 1e6),
                    "device_copy_GBs": 2 * cp_src.numel() / (copy_ms * 1e-3) / 1e9}
+        # Launch time against the number of rows (the first T' rows of every buffer set, in turns): the
+        # fixed cost of a launch (start-up and drain, which no row accounts for) and the kernel's steady
+        # rate, from a least-squares line through four points.  The last point is the full workload, so
+        # the output buffers hold the timed configuration's results afterwards.
+        if T >= 2048:
+            pts = []
+            for frac4 in (1, 2, 3, 4):
+                Tp = T * frac4 // 4
+                ms = timed(lambda i: binding.perq_permute_rotate_quant(
+                    xs[i % nsets][:Tp], perm_t, b, fmt, codes=outs[i % nsets][0][:Tp], scales=outs[i % nsets][1][:Tp],
+                    stream=stream, algo=args.algo, placement=place_t), min(args.steps, 300))
+                pts.append((Tp, ms * 1e3))
+            A = np.array([[1.0, tp] for tp, _ in pts])
+            (fixed_us, us_per_row), *_ = np.linalg.lstsq(A, np.array([u for _, u in pts]), rcond=None)
+            steady = algorithmic_bytes(T, d, fmt) / T / (us_per_row * 1e-6) / 1e9 if us_per_row > 0 else None
+            context["launch_model"] = {"points_rows_us": [[int(tp), float(u)] for tp, u in pts],
+                                       "fixed_us": float(fixed_us), "ns_per_row": float(us_per_row * 1e3),
+                                       "steady_GBs": steady, "steady_frac": steady / HBM_PEAK_GBS if steady else None,
+                                       "note": "time = fixed + rows * per-row: the fixed part is start-up and drain of a launch"}
         if perm_t is not None and not args.arranged:
             # the same blocks in the order perq_perm_arrange gives them (fewer LDS bank conflicts in
             # the operand gather): all buffer sets, as in the timed region; not the headline value

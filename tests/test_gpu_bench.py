@@ -35,3 +35,6 @@ def test_bench_line_and_check(extra):
     assert r["check"]["ok"] and r["check"]["mismatch_fail"] == 0 and r["check"]["elements"] > 0
     if not extra:
         assert "arranged_perm" in r["context"]
+    lm = r["context"]["launch_model"]
+    assert [pt[0] for pt in lm["points_rows_us"]] == [512, 1024, 1536, 2048] and all(pt[1] > 0 for pt in lm["points_rows_us"])
+    assert lm["ns_per_row"] > 0
