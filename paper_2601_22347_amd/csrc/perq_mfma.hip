@@ -251,6 +251,16 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     constexpr bool kDouble = NWAVES == 4;
     constexpr uint32_t kBufStride = 32768;
 
+    // Every kernel argument the set-up needs, fetched in one round trip: left to itself the compiler
+    // loads each where it is first used, four to five trips to the argument segment one after the
+    // other (about half a microsecond each on a launch's cold scalar cache) ahead of the first row loads
+    // (first loads issued 2.7 -> 1.9 us after the launch at d = 4096, 4.4 -> 2.8 us at d = 14336;
+    // T = 2048, d = 8192: 14.1 -> 13.9 us, d = 14336, b = 128: 201.0 -> 199.6 us).  Not in the high-K
+    // variants, whose main loops came out 0.3 - 0.6 % slower with the arguments held in registers.
+    if constexpr (STAGES < 5)
+        asm volatile("; kernel arguments are in registers" ::"s"(p.x), "s"(p.T), "s"(p.ldx), "s"(p.perm), "s"(p.place),
+                     "s"(p.lane_table), "s"(p.d), "s"(p.b), "s"(g.tiles_per_row), "s"(g.rows), "s"(g.nload), "s"(g.row_bytes),
+                     "s"(g.ctr_set), "s"(g.dynamic), "s"(g.fold_mask), "s"(g.row_c_bits), "s"(g.row_per_half));
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -269,7 +279,14 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
     constexpr bool kElem = PERM || kHighK;          // operands gathered element by element
     bf16x8_t afrag[2], afrag_neg[2];
     const uint32_t sigma_i = layout::lane_sigma((uint32_t)lane & 31u);
-    {
+    // -1 / +1 of the cross-lane butterflies on c
+    float sgn[5];
+    // Filled in once the first row loads are on their way: nothing ahead of them needs these, and a
+    // launch is as long as its first loads are late (d = 4096, b = 128: 57.8 -> 56.9 us; T = 2048,
+    // d = 8192: 14.4 -> 14.1 us).  The high-K variants with the gather one unit ahead keep them up here:
+    // with them further down the same main loop came out 2 % slower (d = 14336, b = 2048: 208.9 -> 213.7 us).
+    constexpr bool kConstantsFirst = STAGES >= 5 && PIPE;
+    auto build_constants = [&]() {
         const uint32_t n = kHighK ? ((uint32_t)lane & 31u) : sigma_i;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
@@ -286,7 +303,10 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
             afrag_neg[kt] = __builtin_bit_cast(bf16x8_t, make_uint4(w[0] ^ 0x80008000u, w[1] ^ 0x80008000u,
                                                                    w[2] ^ 0x80008000u, w[3] ^ 0x80008000u));
         }
-    }
+#pragma unroll
+        for (int k = 0; k < 5; ++k) sgn[k] = (c >> k) & 1 ? -1.0f : 1.0f;
+    };
+    if constexpr (kConstantsFirst) build_constants();
 
     // ---- LDS addresses of this lane's operands (fixed for the whole launch) ----------------
     // PERM: one address per element; identity: one per 16-byte fragment.
@@ -305,11 +325,6 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         if constexpr (STAGES == 7) return 16 * ((2 * h + (q >> 1)) * 32 + c) + 2048 * (q & 1);
         return 16 * (q * 32 + c) + 2048 * h;
     };
-
-    // -1 / +1 of the cross-lane butterflies on c
-    float sgn[5];
-#pragma unroll
-    for (int k = 0; k < 5; ++k) sgn[k] = (c >> k) & 1 ? -1.0f : 1.0f;
 
     const uint32_t gpr = (uint32_t)d >> 3;                    // granules per row (multiple of 64)
     // Where a granule of the row sits in its staging buffer: the fixed swizzle, or the placement the
@@ -974,6 +989,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         const int n0 = u_cur < n_units ? issue_loads(u_cur, 0u) : 0;
         if (drawing) draw();
         if constexpr (kDouble) n_behind = u_nxt < n_units ? issue_loads(u_nxt, kBufStride) : 0;
+        if constexpr (!kConstantsFirst) build_constants();
         return n0 + (kDouble ? n_behind : 0);
     };
     if constexpr (!SHARED && !kLdsTable) {
@@ -1018,6 +1034,7 @@ mfma_kernel(ApplyParams p, MfmaGeom g) {
         // of the second staging buffer, still unused.  Every lane then picks its 64 offsets from
         // there.  Only after that is the second unit requested into that buffer.
         if (u_cur < n_units) issue_loads(u_cur, 0u);
+        if constexpr (!kConstantsFirst) build_constants();
         // Waves on the same tile (the rows of a row group; all four on rows of their own) share one
         // table and read a part of the tile's entries each.
         const uint32_t tile_id = (uint32_t)wave % (uint32_t)g.tiles_per_row;
